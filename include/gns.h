@@ -1,0 +1,192 @@
+/*
+ * gns.h -- C ABI of the MI355X (gfx950) Global Neighbor Sampling hot path.
+ *
+ * Paper: "Global Neighbor Sampling for Mixed CPU-GPU Training on Giant Graphs"
+ * (arxiv 2106.06150, KDD'21).  The library implements, on one GPU, the
+ * per-mini-batch sampler of Algorithm 1 and the data movement it feeds:
+ *
+ *   gns_sample_cache     Section 3.2 / Eq. (1) / Theorem 1: the periodic global
+ *                        node cache, inclusion driven by node degree
+ *   gns_sample_blocks    Algorithm 1 top-down loop; Section 2.1 (uniform
+ *                        node-wise sampling), Sections 3.3 and 4.1 (input layer
+ *                        restricted to cached neighbors), Section 3.4
+ *                        (importance-sampling coefficients); the set union
+ *                        B^{l-1} <- B^{l-1} U N_l(u) relabelled into block CSRs
+ *   gns_gather_features  Section 2.2 steps 2-3: slice the input-node features
+ *                        (cached rows come from the device-resident cache table)
+ *   gns_aggregate        Algorithm 1 bottom-up loop, f_l with the mean
+ *                        aggregator and Section 3.4's 1/p rescaling
+ *
+ * General rules
+ *  - Every pointer is a DEVICE pointer unless its name starts with host_ or it
+ *    is documented as a host pointer (struct pointers, out-parameters).
+ *  - The caller owns every buffer, including the workspace; the library
+ *    borrows them for the lifetime of the context and never frees them.  After
+ *    gns_create the library performs no device allocation.
+ *  - All device work is enqueued on the hipStream_t passed as `hip_stream`
+ *    (NULL = the default stream).  Calls that must report counts to the host
+ *    (gns_sample_cache, gns_sample_blocks) synchronise that stream before
+ *    returning; gns_gather_features and gns_aggregate only enqueue.
+ *  - Every call returns a gns_status; nothing aborts or prints.  A message for
+ *    the last failure is available from gns_last_error.
+ *  - One context serves one stream at a time; calls on the same context must
+ *    not overlap.  There is no global state.
+ *  - Results are a pure function of (graph, config, seed, epoch, seeds): the
+ *    random source is the counter-based Philox4x32-10 generator, so a repeated
+ *    call reproduces its output bit for bit.
+ */
+#ifndef GNS_H_
+#define GNS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GNS_MAX_LAYERS 8
+#define GNS_MAX_FANOUT 64
+
+typedef struct gns_ctx gns_ctx; /* opaque; one per (graph, config, device) */
+
+typedef enum {
+    GNS_OK = 0,
+    GNS_EINVAL = 1,     /* bad argument (null pointer, size out of range, duplicate or out-of-range seed) */
+    GNS_ECAPACITY = 2,  /* a caller buffer or the workspace is too small; nothing was written past it */
+    GNS_ESTATE = 3,     /* call order: a cache policy is configured but no cache has been drawn */
+    GNS_EHIP = 4,       /* a HIP runtime call failed */
+    GNS_ENOMEM = 5,     /* host allocation failed */
+    GNS_ENOTIMPL = 6    /* a policy or mode this build does not provide */
+} gns_status;
+
+/* Per-layer neighbor-selection policy (Algorithm 1, `sample(N(u), C)`). */
+enum {
+    GNS_UNIFORM = 0,    /* Section 2.1: min(k, deg(v)) neighbors uniformly without replacement, weight 1 */
+    GNS_CACHE_ONLY = 1, /* Sections 3.3 / 4.1: min(k, N_C(v)) of the cached neighbors, weight from Section 3.4 */
+    GNS_CACHE_FIRST = 2 /* Section 3.3 with fill from outside the cache: not provided (GNS_ENOTIMPL) */
+};
+
+/* Section 3.4 rescaling.  p^C_u = 1 - (1 - deg(u)/nnz)^|C|.
+ *  PRINTED:  weight = 1 / (p^C_u * k / min(k, N_C(v)))     (the formula as printed)
+ *  UNBIASED: weight = N_C(v) / (min(k, N_C(v)) * p^C_u)    (Horvitz-Thompson form) */
+enum { GNS_W_PRINTED = 0, GNS_W_UNBIASED = 1 };
+
+/* The graph G(V, E) of Algorithm 1 as a CSR adjacency, plus the input features.
+ * Rows must be sorted ascending and free of duplicates; deg(v) is the row length. */
+typedef struct {
+    int64_t num_nodes;             /* n = |V|, 1 <= n < 2^31                                   */
+    int64_t num_entries;           /* nnz = indptr[n], 1 <= nnz                                */
+    const void* indptr;            /* device: int32[n+1] or int64[n+1]                          */
+    int32_t indptr_is_i64;         /* 0: int32 offsets, 1: int64 offsets                        */
+    const int32_t* indices;        /* device: int32[nnz] neighbor ids                           */
+    int32_t feat_dim;              /* F >= 0 (0: no features, gather/cache table unavailable)   */
+    const float* feat_dev;         /* device fp32[n x F] row-major, or NULL                     */
+    const float* feat_host_pinned; /* pinned host fp32[n x F] readable from the device, or NULL */
+} gns_graph;
+
+typedef struct {
+    int32_t num_layers;               /* L, 1..GNS_MAX_LAYERS                                       */
+    int32_t fanout[GNS_MAX_LAYERS];   /* k per layer; index 0 is layer L (next to the seeds), index
+                                         L-1 is layer 1 (the input layer); 1..GNS_MAX_FANOUT        */
+    int32_t policy[GNS_MAX_LAYERS];   /* GNS_UNIFORM / GNS_CACHE_ONLY per layer, same indexing      */
+    int64_t cache_size;               /* |C|; 0 if no layer uses the cache                          */
+    int32_t wmode;                    /* GNS_W_PRINTED / GNS_W_UNBIASED                             */
+    int32_t max_seeds;                /* largest mini-batch |B| the context must accept             */
+} gns_config;
+
+/* One layer's block: a CSR over (dst rows) x (src columns) in local ids.
+ *   src_nodes[0..num_dst)       = the layer's dst nodes in their given order
+ *   src_nodes[num_dst..num_src) = the other sampled nodes, ascending global id
+ *   indptr[0..num_dst]          = exclusive prefix sum of the per-row counts
+ *   indices[e], weights[e]      = local src id and Section 3.4 weight of edge e;
+ *                                 a row's edges are in ascending CSR position
+ *   row_eligible[r]             = deg(v) (UNIFORM) or N_C(v) (CACHE_ONLY) of dst row r
+ * The five arrays are caller-allocated device buffers with the capacities
+ * below (see gns_block_capacity); the three counts are written by the library
+ * on the host.  src_nodes of layer l is the dst list of layer l-1.            */
+typedef struct {
+    int32_t num_dst, num_src, num_edges;
+    int32_t* indptr;       /* device int32[cap_dst + 1] */
+    int32_t* indices;      /* device int32[cap_edges]   */
+    int32_t* src_nodes;    /* device int32[cap_src]     */
+    int32_t* row_eligible; /* device int32[cap_dst]     */
+    float* weights;        /* device fp32[cap_edges]    */
+    int32_t cap_dst, cap_src, cap_edges;
+} gns_block;
+
+/* Bytes of device workspace gns_create needs for this graph and config
+ * (0 if the arguments are invalid).  Host call, no device work. */
+size_t gns_workspace_bytes(const gns_graph* graph, const gns_config* config);
+
+/* Worst-case sizes of block `layer_index` (0 = layer L) for a batch of
+ * config->max_seeds seeds: cap_dst = rows, cap_edges = rows * fanout,
+ * cap_src = min(rows + edges, n).  gns_sample_blocks requires at least these. */
+gns_status gns_block_capacity(const gns_graph* graph, const gns_config* config, int32_t layer_index,
+                              int32_t* cap_dst, int32_t* cap_src, int32_t* cap_edges);
+
+/* Creates a context.  `workspace` is a device buffer of at least
+ * gns_workspace_bytes bytes, 256-byte aligned, borrowed until gns_destroy.
+ * Validates the arguments (GNS_EINVAL), e.g. cache_size must not exceed the
+ * number of nodes with at least one neighbor when a cache policy is used.
+ * Initialises the workspace on `hip_stream` and synchronises it. */
+gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_config* config,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+gns_status gns_destroy(gns_ctx* ctx);
+
+/* Section 3.2, Eq. (1), Theorem 1.  Draws the cache C for (seed, epoch):
+ * the first cache_size distinct nodes of an i.i.d. stream in which node i
+ * appears with probability deg(i)/nnz (successive weighted sampling without
+ * replacement).  Builds the membership bitmap, the ascending node list, the
+ * node -> slot rank index, the per-slot 1/p^C table and, if features were
+ * given, the device table of the cached rows' features in slot order.
+ * epoch must be < 2^32.  GNS_ECAPACITY if the stream does not yield
+ * cache_size distinct nodes within the library's draw limit. */
+gns_status gns_sample_cache(gns_ctx* ctx, uint64_t seed, uint64_t epoch, void* hip_stream);
+
+/* Read-only views of the current cache (device pointers into the workspace,
+ * valid until the next gns_sample_cache): cache_nodes int32[*cache_size]
+ * ascending; bitmap uint64[ceil(n/64)], bit (i & 63) of word (i >> 6) set iff
+ * node i is cached; *num_draws = stream draws consumed.  Any out-pointer may
+ * be NULL.  GNS_ESTATE before the first draw. */
+gns_status gns_cache_view(gns_ctx* ctx, const int32_t** cache_nodes, int64_t* cache_size,
+                          const uint64_t** bitmap, int64_t* num_draws);
+
+/* Algorithm 1's top-down loop for one mini-batch.  seeds_dev: num_seeds
+ * distinct node ids in [0, n) (1 <= num_seeds <= max_seeds).  `seed` keys the
+ * neighbor draws: the draw for (layer l, node v, slot s) uses Philox counter
+ * (v, s >> 2, l, 'NBHS') and key (lo32(seed), hi32(seed)), so each row's sample
+ * is independent of the batch it appears in.  blocks: host array of
+ * num_layers gns_block, index 0 = layer L; their device buffers must have at
+ * least the capacities of gns_block_capacity (GNS_ECAPACITY otherwise, before
+ * any device work).  On return the counts in every block are valid and the
+ * stream has been synchronised.  GNS_EINVAL if a duplicate or out-of-range
+ * seed was detected (the blocks' contents are then unspecified). */
+gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
+                             gns_block* blocks, void* hip_stream);
+
+/* Section 2.2 steps 2-3.  out_dev[j, :] = feature row of nodes_dev[j]
+ * (fp32[num_nodes x F] row-major, bit copies).  A cached node is read from the
+ * device cache table, any other from feat_dev if given, else from
+ * feat_host_pinned.  num_nodes may be 0.  Enqueue only (no synchronisation). */
+gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t num_nodes, float* out_dev,
+                               void* hip_stream);
+
+/* Algorithm 1 bottom-up loop, one layer, mean aggregator with Section 3.4's
+ * rescaling: out_dev[v, :] = (1/n_v) * sum over row v's edges of
+ * weights[e] * x_src_dev[indices[e], :], n_v = row length, zeros for an empty
+ * row.  x_src_dev is fp32[block->num_src x feat_dim], out_dev is
+ * fp32[block->num_dst x feat_dim], both row-major.  fp32 arithmetic, edges
+ * accumulated in row order.  Uses the block's host counts.  Enqueue only. */
+gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_src_dev, int32_t feat_dim,
+                         float* out_dev, void* hip_stream);
+
+/* Message of the last failure on this context (or, for ctx == NULL, of the
+ * last failed gns_create / gns_workspace_bytes on this thread).  Never NULL. */
+const char* gns_last_error(const gns_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GNS_H_ */

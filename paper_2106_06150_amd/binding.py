@@ -1,0 +1,250 @@
+"""Thin ctypes binding of libgns.so: argument marshalling only.
+
+Every step of the hot path runs in the library's HIP kernels; torch is used for
+device memory and streams.  There is no CPU fallback: if the library is not
+built, importing this module raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgns.so")
+
+GNS_OK, GNS_EINVAL, GNS_ECAPACITY, GNS_ESTATE, GNS_EHIP, GNS_ENOMEM, GNS_ENOTIMPL = range(7)
+GNS_UNIFORM, GNS_CACHE_ONLY, GNS_CACHE_FIRST = 0, 1, 2
+GNS_W_PRINTED, GNS_W_UNBIASED = 0, 1
+GNS_MAX_LAYERS = 8
+GNS_MAX_FANOUT = 64
+
+STATUS_NAMES = ["GNS_OK", "GNS_EINVAL", "GNS_ECAPACITY", "GNS_ESTATE", "GNS_EHIP", "GNS_ENOMEM", "GNS_ENOTIMPL"]
+
+
+class gns_graph(ctypes.Structure):
+    _fields_ = [("num_nodes", ctypes.c_int64), ("num_entries", ctypes.c_int64),
+                ("indptr", ctypes.c_void_p), ("indptr_is_i64", ctypes.c_int32),
+                ("indices", ctypes.c_void_p), ("feat_dim", ctypes.c_int32),
+                ("feat_dev", ctypes.c_void_p), ("feat_host_pinned", ctypes.c_void_p)]
+
+
+class gns_config(ctypes.Structure):
+    _fields_ = [("num_layers", ctypes.c_int32), ("fanout", ctypes.c_int32 * GNS_MAX_LAYERS),
+                ("policy", ctypes.c_int32 * GNS_MAX_LAYERS), ("cache_size", ctypes.c_int64),
+                ("wmode", ctypes.c_int32), ("max_seeds", ctypes.c_int32)]
+
+
+class gns_block(ctypes.Structure):
+    _fields_ = [("num_dst", ctypes.c_int32), ("num_src", ctypes.c_int32), ("num_edges", ctypes.c_int32),
+                ("indptr", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("src_nodes", ctypes.c_void_p),
+                ("row_eligible", ctypes.c_void_p), ("weights", ctypes.c_void_p),
+                ("cap_dst", ctypes.c_int32), ("cap_src", ctypes.c_int32), ("cap_edges", ctypes.c_int32)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libgns.so is not built: run `python -m paper_2106_06150_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, u64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64
+    P = ctypes.POINTER
+    lib.gns_workspace_bytes.argtypes = [P(gns_graph), P(gns_config)]
+    lib.gns_workspace_bytes.restype = ctypes.c_size_t
+    lib.gns_block_capacity.argtypes = [P(gns_graph), P(gns_config), i32, P(i32), P(i32), P(i32)]
+    lib.gns_block_capacity.restype = ctypes.c_int
+    lib.gns_create.argtypes = [P(vp), P(gns_graph), P(gns_config), vp, ctypes.c_size_t, vp]
+    lib.gns_create.restype = ctypes.c_int
+    lib.gns_destroy.argtypes = [vp]
+    lib.gns_destroy.restype = ctypes.c_int
+    lib.gns_sample_cache.argtypes = [vp, u64, u64, vp]
+    lib.gns_sample_cache.restype = ctypes.c_int
+    lib.gns_cache_view.argtypes = [vp, P(vp), P(i64), P(vp), P(i64)]
+    lib.gns_cache_view.restype = ctypes.c_int
+    lib.gns_sample_blocks.argtypes = [vp, u64, vp, i32, P(gns_block), vp]
+    lib.gns_sample_blocks.restype = ctypes.c_int
+    lib.gns_gather_features.argtypes = [vp, vp, i32, vp, vp]
+    lib.gns_gather_features.restype = ctypes.c_int
+    lib.gns_aggregate.argtypes = [vp, P(gns_block), vp, i32, vp, vp]
+    lib.gns_aggregate.restype = ctypes.c_int
+    lib.gns_last_error.argtypes = [vp]
+    lib.gns_last_error.restype = ctypes.c_char_p
+    return lib
+
+
+lib = _load()
+
+EXPORTED = ["gns_workspace_bytes", "gns_block_capacity", "gns_create", "gns_destroy", "gns_sample_cache",
+            "gns_cache_view", "gns_sample_blocks", "gns_gather_features", "gns_aggregate", "gns_last_error"]
+
+
+class GnsError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("%s: %s" % (STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status, message))
+        self.status = status
+
+
+def _check(status, ctx=None):
+    if status != GNS_OK:
+        raise GnsError(status, lib.gns_last_error(ctx).decode())
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def make_graph(indptr, indices, feat_dev=None, feat_host_pinned=None, feat_dim=None):
+    """gns_graph from torch tensors (indptr/indices on the device; features on the
+    device and/or in pinned host memory)."""
+    assert indptr.is_cuda and indices.is_cuda and indices.dtype == torch.int32
+    assert indptr.dtype in (torch.int32, torch.int64)
+    g = gns_graph()
+    g.num_nodes = indptr.numel() - 1
+    g.num_entries = indices.numel()
+    g.indptr = indptr.data_ptr()
+    g.indptr_is_i64 = 1 if indptr.dtype == torch.int64 else 0
+    g.indices = indices.data_ptr()
+    feat = feat_dev if feat_dev is not None else feat_host_pinned
+    g.feat_dim = int(feat.shape[1]) if feat is not None else int(feat_dim or 0)
+    if feat_dev is not None:
+        assert feat_dev.is_cuda and feat_dev.dtype == torch.float32 and feat_dev.is_contiguous()
+        g.feat_dev = feat_dev.data_ptr()
+    if feat_host_pinned is not None:
+        assert feat_host_pinned.is_pinned() and feat_host_pinned.dtype == torch.float32
+        g.feat_host_pinned = feat_host_pinned.data_ptr()
+    g._keep = (indptr, indices, feat_dev, feat_host_pinned)
+    return g
+
+
+def make_config(fanouts, policies, cache_size, max_seeds, wmode=GNS_W_PRINTED):
+    c = gns_config()
+    c.num_layers = len(fanouts)
+    for i, (k, p) in enumerate(zip(fanouts, policies)):
+        c.fanout[i] = k
+        c.policy[i] = p
+    c.cache_size = cache_size
+    c.wmode = wmode
+    c.max_seeds = max_seeds
+    return c
+
+
+def gns_workspace_bytes(graph, config):
+    n = lib.gns_workspace_bytes(ctypes.byref(graph), ctypes.byref(config))
+    if n == 0:
+        raise GnsError(GNS_EINVAL, lib.gns_last_error(None).decode())
+    return n
+
+
+def gns_block_capacity(graph, config, layer_index):
+    a, b, c = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(lib.gns_block_capacity(ctypes.byref(graph), ctypes.byref(config), layer_index,
+                                  ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+    return a.value, b.value, c.value
+
+
+def gns_create(graph, config, workspace, stream=None):
+    ctx = ctypes.c_void_p()
+    _check(lib.gns_create(ctypes.byref(ctx), ctypes.byref(graph), ctypes.byref(config),
+                          workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+    return ctx
+
+
+def gns_destroy(ctx):
+    _check(lib.gns_destroy(ctx))
+
+
+def gns_sample_cache(ctx, seed, epoch, stream=None):
+    _check(lib.gns_sample_cache(ctx, seed, epoch, _stream_ptr(stream)), ctx)
+
+
+def gns_cache_view(ctx):
+    """Returns (cache_nodes_ptr, cache_size, bitmap_ptr, num_draws) -- raw device pointers."""
+    nodes, bitmap = ctypes.c_void_p(), ctypes.c_void_p()
+    size, draws = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib.gns_cache_view(ctx, ctypes.byref(nodes), ctypes.byref(size), ctypes.byref(bitmap),
+                              ctypes.byref(draws)), ctx)
+    return nodes.value, size.value, bitmap.value, draws.value
+
+
+def gns_sample_blocks(ctx, seed, seeds_dev, blocks, stream=None):
+    """blocks: ctypes array of gns_block (see alloc_blocks)."""
+    assert seeds_dev.is_cuda and seeds_dev.dtype == torch.int32 and seeds_dev.is_contiguous()
+    _check(lib.gns_sample_blocks(ctx, seed, seeds_dev.data_ptr(), seeds_dev.numel(), blocks, _stream_ptr(stream)), ctx)
+
+
+def gns_gather_features(ctx, nodes_dev, num_nodes, out_dev, stream=None):
+    _check(lib.gns_gather_features(ctx, nodes_dev.data_ptr(), num_nodes, out_dev.data_ptr(), _stream_ptr(stream)), ctx)
+
+
+def gns_aggregate(ctx, block, x_src_dev, feat_dim, out_dev, stream=None):
+    _check(lib.gns_aggregate(ctx, ctypes.byref(block), x_src_dev.data_ptr(), feat_dim, out_dev.data_ptr(),
+                             _stream_ptr(stream)), ctx)
+
+
+# ---------------------------------------------------------------------------
+# Memory plumbing helpers (allocation only).
+
+class BlockBuffers:
+    """Worst-case device buffers for the blocks of one mini-batch, plus the
+    ctypes array the library fills in."""
+
+    def __init__(self, graph, config, device):
+        L = config.num_layers
+        self.array = (gns_block * L)()
+        self.tensors = []
+        for i in range(L):
+            cap_dst, cap_src, cap_edges = gns_block_capacity(graph, config, i)
+            t = dict(indptr=torch.empty(cap_dst + 1, dtype=torch.int32, device=device),
+                     indices=torch.empty(max(cap_edges, 1), dtype=torch.int32, device=device),
+                     src_nodes=torch.empty(max(cap_src, 1), dtype=torch.int32, device=device),
+                     row_eligible=torch.empty(max(cap_dst, 1), dtype=torch.int32, device=device),
+                     weights=torch.empty(max(cap_edges, 1), dtype=torch.float32, device=device))
+            self.tensors.append(t)
+            b = self.array[i]
+            b.indptr, b.indices, b.src_nodes = t["indptr"].data_ptr(), t["indices"].data_ptr(), t["src_nodes"].data_ptr()
+            b.row_eligible, b.weights = t["row_eligible"].data_ptr(), t["weights"].data_ptr()
+            b.cap_dst, b.cap_src, b.cap_edges = cap_dst, cap_src, cap_edges
+
+    def views(self, i):
+        """Tensors of block i trimmed to the counts the library reported."""
+        b, t = self.array[i], self.tensors[i]
+        return dict(indptr=t["indptr"][:b.num_dst + 1], indices=t["indices"][:b.num_edges],
+                    src_nodes=t["src_nodes"][:b.num_src], row_eligible=t["row_eligible"][:b.num_dst],
+                    weights=t["weights"][:b.num_edges], num_dst=b.num_dst, num_src=b.num_src,
+                    num_edges=b.num_edges)
+
+
+def alloc_workspace(graph, config, device):
+    nbytes = gns_workspace_bytes(graph, config)
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def device_view_i32(ptr, count, device):
+    """Copies `count` int32 from a raw device pointer into a new tensor (for tests)."""
+    out = torch.empty(count, dtype=torch.int32, device=device)
+    if count:
+        rc = _hip_memcpy_dtod(out.data_ptr(), ptr, count * 4)
+        assert rc == 0
+    return out
+
+
+def device_view_u64(ptr, count, device):
+    out = torch.empty(count, dtype=torch.int64, device=device)
+    if count:
+        rc = _hip_memcpy_dtod(out.data_ptr(), ptr, count * 8)
+        assert rc == 0
+    return out
+
+
+_hip = None
+
+
+def _hip_memcpy_dtod(dst, src, nbytes):
+    global _hip
+    if _hip is None:
+        _hip = ctypes.CDLL("libamdhip64.so")
+        _hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+        _hip.hipMemcpy.restype = ctypes.c_int
+    torch.cuda.synchronize()
+    return _hip.hipMemcpy(dst, src, nbytes, 3)  # hipMemcpyDeviceToDevice

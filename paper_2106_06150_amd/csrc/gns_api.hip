@@ -1,0 +1,318 @@
+// C ABI of the GNS library: argument validation, workspace layout and the
+// per-call launch sequences.  See include/gns.h for the contract.
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include <new>
+#include "gns_internal.h"
+#include "gns_device.hpp"
+
+namespace gns {
+
+static thread_local char g_create_err[256] = "";
+
+static inline size_t align_up(size_t x) { return (x + 255u) & ~(size_t) 255u; }
+
+static inline uint32_t pow2_at_least(uint64_t x)
+{
+    uint64_t p = 1024;
+    while (p < x) p <<= 1;
+    return (uint32_t) p;
+}
+
+static bool config_uses_cache(const gns_config* cfg)
+{
+    for (int i = 0; i < cfg->num_layers; ++i)
+        if (cfg->policy[i] != GNS_UNIFORM) return true;
+    return false;
+}
+
+bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char* err, size_t errlen)
+{
+#define GNS_BAD(msg) do { snprintf(err, errlen, "%s", msg); return false; } while (0)
+    if (!g || !cfg) GNS_BAD("null graph or config");
+    if (g->num_nodes < 1 || g->num_nodes >= (int64_t) 1 << 31) GNS_BAD("num_nodes must be in [1, 2^31)");
+    if (g->num_entries < 1) GNS_BAD("num_entries must be >= 1");
+    if (!g->indptr || !g->indices) GNS_BAD("null CSR arrays");
+    if (!g->indptr_is_i64 && g->num_entries >= (int64_t) 1 << 31) GNS_BAD("int32 offsets cannot address num_entries");
+    if (g->feat_dim < 0) GNS_BAD("feat_dim must be >= 0");
+    if (g->feat_dim > 0 && !g->feat_dev && !g->feat_host_pinned) GNS_BAD("feat_dim > 0 but no feature store given");
+    if (cfg->num_layers < 1 || cfg->num_layers > GNS_MAX_LAYERS) GNS_BAD("num_layers out of range");
+    if (cfg->max_seeds < 1) GNS_BAD("max_seeds must be >= 1");
+    if (cfg->wmode != GNS_W_PRINTED && cfg->wmode != GNS_W_UNBIASED) GNS_BAD("unknown weight mode");
+    for (int i = 0; i < cfg->num_layers; ++i) {
+        if (cfg->fanout[i] < 1 || cfg->fanout[i] > GNS_MAX_FANOUT) GNS_BAD("fanout out of range");
+        if (cfg->policy[i] != GNS_UNIFORM && cfg->policy[i] != GNS_CACHE_ONLY && cfg->policy[i] != GNS_CACHE_FIRST)
+            GNS_BAD("unknown policy");
+    }
+    const bool uses_cache = config_uses_cache(cfg);
+    if (uses_cache && (cfg->cache_size < 1 || cfg->cache_size > g->num_nodes)) GNS_BAD("cache_size out of range");
+    if (!uses_cache && cfg->cache_size < 0) GNS_BAD("cache_size must be >= 0");
+
+    Layout L;
+    memset(&L, 0, sizeof(L));
+    const int64_t n = g->num_nodes;
+    const int64_t C = uses_cache ? cfg->cache_size : 0;
+    L.words = (n + 63) / 64;
+    L.word_tiles = (L.words + kTile - 1) / kTile;
+
+    // worst-case frontier growth: rows[i+1] = min(rows[i] * (1 + k_i), n)
+    L.rows[0] = cfg->max_seeds;
+    L.max_rows = 0;
+    L.max_edges = 0;
+    for (int i = 0; i < cfg->num_layers; ++i) {
+        L.edges[i] = L.rows[i] * cfg->fanout[i];
+        int64_t src = L.rows[i] + L.edges[i];
+        if (src > n) src = n;
+        L.rows[i + 1] = src;
+        if (L.rows[i] > L.max_rows) L.max_rows = L.rows[i];
+        if (L.edges[i] > L.max_edges) L.max_edges = L.edges[i];
+        if (L.edges[i] >= (int64_t) 1 << 31) GNS_BAD("a layer's worst-case edge count exceeds 2^31");
+    }
+    L.row_tiles = (L.max_rows + kTile - 1) / kTile;
+    L.hash_cap = pow2_at_least(2 * (uint64_t) L.rows[cfg->num_layers]);
+
+    L.draw_chunk = C;
+    if (L.draw_chunk < 65536) L.draw_chunk = 65536;
+    if (L.draw_chunk > (int64_t) 1 << 22) L.draw_chunk = (int64_t) 1 << 22;
+    L.draw_tiles = (L.draw_chunk + kTile - 1) / kTile;
+    L.draw_hash_cap = pow2_at_least(2 * (uint64_t) (C + L.draw_chunk));
+
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    L.state = take(sizeof(DeviceState) + 64);
+    L.cache_bitmap = take((size_t) L.words * 8);
+    L.cache_prefix = take((size_t) L.words * 4);
+    L.cache_nodes = take((size_t) (C > 0 ? C : 1) * 4);
+    L.cache_inv_pc = take((size_t) (C > 0 ? C : 1) * 8);
+    L.cache_feat = take((size_t) (C > 0 ? C : 1) * (size_t) (g->feat_dim > 0 ? g->feat_dim : 1) * 4);
+    if (uses_cache) {
+        L.draw_keys = take((size_t) L.draw_hash_cap * 4);
+        L.draw_vals = take((size_t) L.draw_hash_cap * 4);
+        L.draw_node = take((size_t) L.draw_chunk * 4);
+        L.draw_slot = take((size_t) L.draw_chunk * 4);
+    }
+    L.mark_bitmap = take((size_t) L.words * 8);
+    L.hash_slots = take((size_t) L.hash_cap * 8);
+    L.s_nbr = take((size_t) L.max_edges * 4);
+    L.s_w = take((size_t) L.max_edges * 4);
+    L.s_cnt = take((size_t) L.max_rows * 4);
+    L.sums_rows = take((size_t) (L.row_tiles + 1) * 4);
+    const int64_t word_or_draw_tiles = L.word_tiles > L.draw_tiles ? L.word_tiles : L.draw_tiles;
+    L.sums_words = take((size_t) (word_or_draw_tiles + 1) * 4);
+    L.total = off;
+    *out = L;
+    return true;
+#undef GNS_BAD
+}
+
+static gns_status ctx_fail(gns_ctx* c, gns_status st, const char* what, hipError_t e = hipSuccess)
+{
+    if (e != hipSuccess) snprintf(c->err, sizeof(c->err), "%s: %s", what, hipGetErrorString(e));
+    else snprintf(c->err, sizeof(c->err), "%s", what);
+    return st;
+}
+
+}  // namespace gns
+
+using namespace gns;
+
+extern "C" {
+
+size_t gns_workspace_bytes(const gns_graph* graph, const gns_config* config)
+{
+    Layout L;
+    if (!compute_layout(graph, config, &L, g_create_err, sizeof(g_create_err))) return 0;
+    return L.total;
+}
+
+gns_status gns_block_capacity(const gns_graph* graph, const gns_config* config, int32_t layer_index,
+                              int32_t* cap_dst, int32_t* cap_src, int32_t* cap_edges)
+{
+    Layout L;
+    if (!compute_layout(graph, config, &L, g_create_err, sizeof(g_create_err))) return GNS_EINVAL;
+    if (layer_index < 0 || layer_index >= config->num_layers) {
+        snprintf(g_create_err, sizeof(g_create_err), "layer_index out of range");
+        return GNS_EINVAL;
+    }
+    if (cap_dst) *cap_dst = (int32_t) L.rows[layer_index];
+    if (cap_src) *cap_src = (int32_t) L.rows[layer_index + 1];
+    if (cap_edges) *cap_edges = (int32_t) L.edges[layer_index];
+    return GNS_OK;
+}
+
+gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_config* config, void* workspace,
+                      size_t workspace_bytes, void* hip_stream)
+{
+    if (!out_ctx) { snprintf(g_create_err, sizeof(g_create_err), "null out_ctx"); return GNS_EINVAL; }
+    *out_ctx = nullptr;
+    Layout L;
+    if (!compute_layout(graph, config, &L, g_create_err, sizeof(g_create_err))) return GNS_EINVAL;
+    for (int i = 0; i < config->num_layers; ++i)
+        if (config->policy[i] == GNS_CACHE_FIRST) {
+            snprintf(g_create_err, sizeof(g_create_err), "policy GNS_CACHE_FIRST is not provided");
+            return GNS_ENOTIMPL;
+        }
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) {
+        snprintf(g_create_err, sizeof(g_create_err), "workspace must be a 256-byte aligned device pointer");
+        return GNS_EINVAL;
+    }
+    if (workspace_bytes < L.total) {
+        snprintf(g_create_err, sizeof(g_create_err), "workspace too small: need %zu bytes", L.total);
+        return GNS_ECAPACITY;
+    }
+    gns_ctx* c = new (std::nothrow) gns_ctx;
+    if (!c) { snprintf(g_create_err, sizeof(g_create_err), "host allocation failed"); return GNS_ENOMEM; }
+    memset(c, 0, sizeof(*c));
+    c->graph = *graph;
+    c->config = *config;
+    c->lay = L;
+    c->ws = static_cast<char*>(workspace);
+    c->d_state = ws_ptr<DeviceState>(c, L.state);
+    c->uses_cache = config_uses_cache(config);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    auto bail = [&](gns_status st, const char* what, hipError_t e) {
+        if (e != hipSuccess) snprintf(g_create_err, sizeof(g_create_err), "%s: %s", what, hipGetErrorString(e));
+        else snprintf(g_create_err, sizeof(g_create_err), "%s", what);
+        if (c->h_state) (void) hipHostFree(c->h_state);
+        delete c;
+        return st;
+    };
+
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return bail(GNS_EHIP, "hipGetDevice", e);
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) return bail(GNS_EHIP, "hipGetDeviceProperties", e);
+    c->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    e = hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(DeviceState), hipHostMallocDefault);
+    if (e != hipSuccess) { c->h_state = nullptr; return bail(GNS_EHIP, "hipHostMalloc", e); }
+
+    // zero the state, the mark bitmap and the cache bitmap; validate the graph
+    e = launch_fill_u32(reinterpret_cast<uint32_t*>(c->d_state), (sizeof(DeviceState) + 64) / 4, 0u, s);
+    if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.mark_bitmap), (size_t) L.words, 0ull, s);
+    if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.cache_bitmap), (size_t) L.words, 0ull, s);
+    if (e != hipSuccess) return bail(GNS_EHIP, "workspace init", e);
+    int32_t* d_info = ws_ptr<int32_t>(c, L.sums_words);   // scratch, 4 ints
+    e = launch_count_nonzero_rows(c, s, d_info);
+    if (e != hipSuccess) return bail(GNS_EHIP, "graph validation launch", e);
+    int32_t info[4] = {0, 0, 0, 0};
+    e = hipMemcpyAsync(info, d_info, sizeof(info), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return bail(GNS_EHIP, "graph validation", e);
+    if (info[1]) return bail(GNS_EINVAL, "indptr is not a non-decreasing offset array from 0 to num_entries", hipSuccess);
+    if (info[2]) return bail(GNS_EINVAL, "indices holds an id outside [0, num_nodes)", hipSuccess);
+    if (info[3]) return bail(GNS_EINVAL, "CSR rows must be sorted ascending without duplicates", hipSuccess);
+    c->nonzero_degree_nodes = info[0];
+    if (c->uses_cache && config->cache_size > c->nonzero_degree_nodes)
+        return bail(GNS_EINVAL, "cache_size exceeds the number of nodes that have a neighbor", hipSuccess);
+    *out_ctx = c;
+    return GNS_OK;
+}
+
+gns_status gns_destroy(gns_ctx* ctx)
+{
+    if (!ctx) return GNS_OK;
+    if (ctx->h_state) (void) hipHostFree(ctx->h_state);
+    delete ctx;
+    return GNS_OK;
+}
+
+gns_status gns_sample_cache(gns_ctx* ctx, uint64_t seed, uint64_t epoch, void* hip_stream)
+{
+    if (!ctx) return GNS_EINVAL;
+    if (!ctx->uses_cache) return ctx_fail(ctx, GNS_ESTATE, "no layer of this config uses the cache");
+    if (epoch >> 32) return ctx_fail(ctx, GNS_EINVAL, "epoch must be < 2^32");
+    return run_sample_cache(ctx, seed, epoch, static_cast<hipStream_t>(hip_stream));
+}
+
+gns_status gns_cache_view(gns_ctx* ctx, const int32_t** cache_nodes, int64_t* cache_size, const uint64_t** bitmap,
+                          int64_t* num_draws)
+{
+    if (!ctx) return GNS_EINVAL;
+    if (!ctx->uses_cache || !ctx->cache_valid) return ctx_fail(ctx, GNS_ESTATE, "no cache has been drawn");
+    if (cache_nodes) *cache_nodes = ws_ptr<int32_t>(ctx, ctx->lay.cache_nodes);
+    if (cache_size) *cache_size = ctx->config.cache_size;
+    if (bitmap) *bitmap = ws_ptr<uint64_t>(ctx, ctx->lay.cache_bitmap);
+    if (num_draws) *num_draws = ctx->cache_draws;
+    return GNS_OK;
+}
+
+gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
+                             gns_block* blocks, void* hip_stream)
+{
+    if (!ctx) return GNS_EINVAL;
+    gns_ctx* c = ctx;
+    if (!seeds_dev || !blocks) return ctx_fail(c, GNS_EINVAL, "null seeds or blocks");
+    if (num_seeds < 1 || num_seeds > c->config.max_seeds) return ctx_fail(c, GNS_EINVAL, "num_seeds out of range");
+    if (c->uses_cache && !c->cache_valid) return ctx_fail(c, GNS_ESTATE, "gns_sample_cache must run before gns_sample_blocks");
+    const Layout& L = c->lay;
+    const int nl = c->config.num_layers;
+    for (int i = 0; i < nl; ++i) {
+        gns_block* b = &blocks[i];
+        if (!b->indptr || !b->indices || !b->src_nodes || !b->row_eligible || !b->weights)
+            return ctx_fail(c, GNS_EINVAL, "a block has a null buffer");
+        if (b->cap_dst < L.rows[i] || b->cap_src < L.rows[i + 1] || b->cap_edges < L.edges[i]) {
+            snprintf(c->err, sizeof(c->err), "block %d too small: need cap_dst %lld cap_src %lld cap_edges %lld", i,
+                     (long long) L.rows[i], (long long) L.rows[i + 1], (long long) L.edges[i]);
+            return GNS_ECAPACITY;
+        }
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = launch_batch_begin(c, seeds_dev, num_seeds, s);
+    if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "batch begin", e);
+    const int32_t* dst = seeds_dev;
+    for (int i = 0; i < nl; ++i) {
+        e = launch_sample_layer(c, i, seed, dst, blocks[i].row_eligible, s);
+        if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample layer", e);
+        e = launch_finish_layer(c, i, dst, &blocks[i], s);
+        if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "finish layer", e);
+        dst = blocks[i].src_nodes;
+    }
+    e = hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample_blocks readback", e);
+    for (int i = 0; i < nl; ++i) {
+        blocks[i].num_dst = c->h_state->num_dst[i];
+        blocks[i].num_src = c->h_state->num_dst[i + 1];
+        blocks[i].num_edges = c->h_state->num_edges[i];
+    }
+    if (c->h_state->bad_seed) return ctx_fail(c, GNS_EINVAL, "seeds must be distinct node ids in [0, num_nodes)");
+    return GNS_OK;
+}
+
+gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t num_nodes, float* out_dev,
+                               void* hip_stream)
+{
+    if (!ctx) return GNS_EINVAL;
+    if (ctx->graph.feat_dim <= 0) return ctx_fail(ctx, GNS_ESTATE, "the graph was created without features");
+    if (num_nodes < 0) return ctx_fail(ctx, GNS_EINVAL, "num_nodes must be >= 0");
+    if (num_nodes == 0) return GNS_OK;
+    if (!nodes_dev || !out_dev) return ctx_fail(ctx, GNS_EINVAL, "null nodes or output");
+    hipError_t e = launch_gather(ctx, nodes_dev, num_nodes, out_dev, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "gather launch", e);
+    return GNS_OK;
+}
+
+gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_src_dev, int32_t feat_dim,
+                         float* out_dev, void* hip_stream)
+{
+    if (!ctx) return GNS_EINVAL;
+    if (!block || !x_src_dev || !out_dev) return ctx_fail(ctx, GNS_EINVAL, "null block, input or output");
+    if (feat_dim < 1) return ctx_fail(ctx, GNS_EINVAL, "feat_dim must be >= 1");
+    if (block->num_dst < 0 || block->num_src < block->num_dst || block->num_edges < 0)
+        return ctx_fail(ctx, GNS_EINVAL, "block counts are inconsistent");
+    if (!block->indptr || !block->indices || !block->weights) return ctx_fail(ctx, GNS_EINVAL, "block has a null buffer");
+    hipError_t e = launch_aggregate(ctx, block, x_src_dev, feat_dim, out_dev, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "aggregate launch", e);
+    return GNS_OK;
+}
+
+const char* gns_last_error(const gns_ctx* ctx)
+{
+    return ctx ? ctx->err : g_create_err;
+}
+
+}  // extern "C"

@@ -1,0 +1,364 @@
+// The periodic global node cache (paper Section 3.2, Eq. (1); Theorem 1: the
+// cache is drawn without replacement and has |C| nodes).
+//
+// The cache is the set of the first |C| distinct nodes of an i.i.d. stream in
+// which node i appears with probability deg(i)/nnz: draw j picks a CSR entry
+// uniformly with a Philox word pair and takes the row that owns it.  The
+// stream is processed in chunks; a small hash map keeps, per drawn node, the
+// smallest stream index at which it appeared (atomicMin), which makes "draw j
+// is the first occurrence of its node" a pure function of the stream and
+// independent of thread order.  First occurrences are counted with a prefix
+// scan; the chunk in which the count reaches |C| is cut at exactly that draw.
+#include "gns_internal.h"
+#include "gns_device.hpp"
+
+namespace gns {
+
+// ---------------------------------------------------------------------------
+// Graph validation at create time: offsets non-decreasing, ids in range, rows
+// strictly ascending; also counts the rows with at least one neighbor.
+struct ValidateOut {
+    int32_t nonzero_rows;
+    int32_t bad_offsets;
+    int32_t bad_index;
+    int32_t unsorted;
+};
+
+template <typename OffT>
+__global__ void __launch_bounds__(kBlock) k_validate_graph(const void* indptr, const int32_t* indices, int64_t n,
+                                                           int64_t nnz, ValidateOut* out)
+{
+    __shared__ int32_t smem[kBlock / kWave + 1];
+    int32_t nonzero = 0;
+    for (int64_t v = (int64_t) blockIdx.x * blockDim.x + threadIdx.x; v < n; v += (int64_t) gridDim.x * blockDim.x) {
+        const int64_t b = load_off<OffT>(indptr, v), e = load_off<OffT>(indptr, v + 1);
+        if (b < 0 || e < b || e > nnz || (v == 0 && b != 0) || (v == n - 1 && e != nnz)) { out->bad_offsets = 1; continue; }
+        if (e > b) ++nonzero;
+        int32_t prev = -1;
+        for (int64_t q = b; q < e; ++q) {
+            const int32_t u = indices[q];
+            if (u < 0 || (int64_t) u >= n) out->bad_index = 1;
+            if (u <= prev) out->unsorted = 1;
+            prev = u;
+        }
+    }
+    nonzero = block_sum(nonzero, smem);
+    if (threadIdx.x == 0 && nonzero) atomicAdd(&out->nonzero_rows, nonzero);
+}
+
+hipError_t launch_count_nonzero_rows(gns_ctx* c, hipStream_t s, int32_t* d_out)
+{
+    const int64_t n = c->graph.num_nodes;
+    int64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > (int64_t) c->num_cus * 32) blocks = (int64_t) c->num_cus * 32;
+    hipError_t e = launch_fill_u32(reinterpret_cast<uint32_t*>(d_out), 4, 0u, s);
+    if (e != hipSuccess) return e;
+    ValidateOut* out = reinterpret_cast<ValidateOut*>(d_out);
+    if (c->graph.indptr_is_i64)
+        hipLaunchKernelGGL((k_validate_graph<int64_t>), dim3((unsigned) blocks), dim3(kBlock), 0, s, c->graph.indptr,
+                           c->graph.indices, n, c->graph.num_entries, out);
+    else
+        hipLaunchKernelGGL((k_validate_graph<int32_t>), dim3((unsigned) blocks), dim3(kBlock), 0, s, c->graph.indptr,
+                           c->graph.indices, n, c->graph.num_entries, out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+struct DrawArgs {
+    DeviceState* st;
+    const void* indptr;
+    int64_t n;
+    uint64_t nnz;
+    uint32_t key0, key1, epoch;
+    uint64_t j0;               // stream index of the chunk's first draw
+    int32_t count;             // draws in this chunk
+    uint32_t* keys;            // draw hash: node ids (0xFFFFFFFF = empty)
+    uint32_t* first;           // draw hash: smallest stream index seen for the node
+    uint32_t hmask, hshift;
+    int32_t* draw_node;        // [chunk]
+    int32_t* draw_slot;        // [chunk] slot of the node in the draw hash
+    int32_t* sums;             // [tiles + 1]
+    int32_t tiles;
+    uint64_t* cache_bitmap;
+    int32_t limit;             // commit: number of first occurrences of this chunk that enter the cache
+    int32_t is_final;
+};
+
+// the unique row i with indptr[i] <= e < indptr[i+1]
+template <typename OffT>
+__device__ __forceinline__ int64_t owner_row(const void* indptr, int64_t n, int64_t e)
+{
+    int64_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (load_off<OffT>(indptr, mid) <= e) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+template <typename OffT>
+__global__ void __launch_bounds__(kBlock) k_cache_draw(DrawArgs a)
+{
+    const int32_t t = (int32_t) (blockIdx.x * blockDim.x + threadIdx.x);
+    if (t >= a.count) return;
+    const uint64_t j = a.j0 + (uint64_t) t;
+    const Philox4 r = philox4x32_10((uint32_t) j, (uint32_t) (j >> 32), a.epoch, kTagCache, a.key0, a.key1);
+    const uint64_t r64 = ((uint64_t) r.w[1] << 32) | (uint64_t) r.w[0];
+    const uint64_t e = __umul64hi(r64, a.nnz);                      // uniform CSR entry
+    const uint32_t node = (uint32_t) owner_row<OffT>(a.indptr, a.n, (int64_t) e);
+    uint32_t h = hash_start(node, a.hshift);
+    for (uint32_t probe = 0; probe <= a.hmask; ++probe) {
+        const uint32_t old = atomicCAS(&a.keys[h], 0xFFFFFFFFu, node);
+        if (old == 0xFFFFFFFFu || old == node) break;
+        h = (h + 1) & a.hmask;
+    }
+    atomicMin(&a.first[h], (uint32_t) j);
+    a.draw_node[t] = (int32_t) node;
+    a.draw_slot[t] = (int32_t) h;
+}
+
+__device__ __forceinline__ int32_t is_first_occurrence(const DrawArgs& a, int32_t t)
+{
+    if (t >= a.count) return 0;
+    return a.first[a.draw_slot[t]] == (uint32_t) (a.j0 + (uint64_t) t) ? 1 : 0;
+}
+
+__global__ void __launch_bounds__(kBlock) k_cache_flags_phase1(DrawArgs a)
+{
+    __shared__ int32_t smem[kBlock / kWave + 1];
+    const int32_t base = (int32_t) blockIdx.x * kTile;
+    int32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) sum += is_first_occurrence(a, base + i * kBlock + (int32_t) threadIdx.x);
+    sum = block_sum(sum, smem);
+    if (threadIdx.x == 0) a.sums[blockIdx.x] = sum;
+}
+
+__global__ void __launch_bounds__(kBlock) k_cache_flags_phase2(DrawArgs a)
+{
+    __shared__ int32_t smem[kBlock / kWave + 1];
+    int32_t carry = 0;
+    for (int32_t base = 0; base < a.tiles; base += kBlock) {
+        const int32_t i = base + (int32_t) threadIdx.x;
+        const int32_t v = (i < a.tiles) ? a.sums[i] : 0;
+        int32_t total;
+        const int32_t ex = block_exclusive_scan(v, smem, &total);
+        if (i < a.tiles) a.sums[i] = carry + ex;
+        carry += total;
+    }
+    if (threadIdx.x == 0) a.st->chunk_distinct = carry;
+}
+
+__global__ void __launch_bounds__(kBlock) k_cache_commit(DrawArgs a)
+{
+    __shared__ int32_t smem[kBlock / kWave + 1];
+    const int32_t base = (int32_t) blockIdx.x * kTile;
+    const int32_t t0 = base + (int32_t) threadIdx.x * kItems;
+    int32_t f[kItems];
+    int32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) { f[i] = is_first_occurrence(a, t0 + i); sum += f[i]; }
+    int32_t total;
+    int32_t g = a.sums[blockIdx.x] + block_exclusive_scan(sum, smem, &total);
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        if (f[i]) {
+            if (g < a.limit) {
+                const uint32_t node = (uint32_t) a.draw_node[t0 + i];
+                atomicOr(reinterpret_cast<unsigned long long*>(&a.cache_bitmap[node >> 6]), 1ull << (node & 63u));
+                if (a.is_final && g == a.limit - 1) a.st->cut_draw = a.j0 + (uint64_t) (t0 + i);
+            }
+            ++g;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Rank index and ascending node list from the finished bitmap.
+struct IndexArgs {
+    const uint64_t* bitmap;
+    int64_t words;
+    int32_t* sums;
+    int32_t tiles;
+    int32_t* word_prefix;
+    int32_t* cache_nodes;
+};
+
+__global__ void __launch_bounds__(kBlock) k_cache_index_phase1(IndexArgs a)
+{
+    __shared__ int32_t smem[kBlock / kWave + 1];
+    const int64_t base = (int64_t) blockIdx.x * kTile;
+    int32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        const int64_t w = base + (int64_t) i * kBlock + threadIdx.x;
+        if (w < a.words) sum += __popcll(a.bitmap[w]);
+    }
+    sum = block_sum(sum, smem);
+    if (threadIdx.x == 0) a.sums[blockIdx.x] = sum;
+}
+
+__global__ void __launch_bounds__(kBlock) k_cache_index_phase2(IndexArgs a)
+{
+    __shared__ int32_t smem[kBlock / kWave + 1];
+    int32_t carry = 0;
+    for (int32_t base = 0; base < a.tiles; base += kBlock) {
+        const int32_t i = base + (int32_t) threadIdx.x;
+        const int32_t v = (i < a.tiles) ? a.sums[i] : 0;
+        int32_t total;
+        const int32_t ex = block_exclusive_scan(v, smem, &total);
+        if (i < a.tiles) a.sums[i] = carry + ex;
+        carry += total;
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) k_cache_index_phase3(IndexArgs a)
+{
+    __shared__ int32_t smem[kBlock / kWave + 1];
+    const int64_t base = (int64_t) blockIdx.x * kTile;
+    const int64_t w0 = base + (int64_t) threadIdx.x * kItems;
+    uint64_t word[kItems];
+    int32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        word[i] = (w0 + i < a.words) ? a.bitmap[w0 + i] : 0ull;
+        sum += __popcll(word[i]);
+    }
+    int32_t total;
+    int32_t pos = a.sums[blockIdx.x] + block_exclusive_scan(sum, smem, &total);
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+        if (w0 + i < a.words) {
+            a.word_prefix[w0 + i] = pos;
+            uint64_t rest = word[i];
+            while (rest) {
+                const int bit = __builtin_ctzll(rest);
+                rest &= rest - 1;
+                a.cache_nodes[pos++] = (int32_t) ((w0 + i) * 64 + bit);
+            }
+        }
+    }
+}
+
+// Section 3.4: p_u = deg(u)/nnz, p^C_u = 1 - (1 - p_u)^|C|; the table keeps 1/p^C_u
+// per cache slot in fp64 (expm1/log1p keep the digits of tiny p_u).
+template <typename OffT>
+__global__ void __launch_bounds__(kBlock) k_cache_inv_pc(const void* indptr, double nnz, int64_t cache_size,
+                                                         const int32_t* cache_nodes, double* inv_pc)
+{
+    const int64_t slot = (int64_t) blockIdx.x * blockDim.x + threadIdx.x;
+    if (slot >= cache_size) return;
+    const int64_t u = cache_nodes[slot];
+    const double deg = (double) (load_off<OffT>(indptr, u + 1) - load_off<OffT>(indptr, u));
+    const double p = deg / nnz;
+    const double pc = (p >= 1.0) ? 1.0 : -expm1((double) cache_size * log1p(-p));
+    inv_pc[slot] = 1.0 / pc;
+}
+
+// ---------------------------------------------------------------------------
+static gns_status fail(gns_ctx* c, gns_status st, const char* what, hipError_t e)
+{
+    if (e != hipSuccess) snprintf(c->err, sizeof(c->err), "%s: %s", what, hipGetErrorString(e));
+    else snprintf(c->err, sizeof(c->err), "%s", what);
+    return st;
+}
+
+#define GNS_HIP_TRY(expr, what)                                        \
+    do {                                                               \
+        hipError_t e__ = (expr);                                       \
+        if (e__ != hipSuccess) return fail(c, GNS_EHIP, what, e__);    \
+    } while (0)
+
+gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream_t s)
+{
+    const Layout& L = c->lay;
+    const int64_t C = c->config.cache_size;
+    uint64_t* bitmap = ws_ptr<uint64_t>(c, L.cache_bitmap);
+    c->cache_valid = false;
+
+    GNS_HIP_TRY(launch_fill_u64(reinterpret_cast<unsigned long long*>(bitmap), (size_t) L.words, 0ull, s), "clear cache bitmap");
+    GNS_HIP_TRY(launch_fill_u32(ws_ptr<uint32_t>(c, L.draw_keys), L.draw_hash_cap, 0xFFFFFFFFu, s), "clear draw keys");
+    GNS_HIP_TRY(launch_fill_u32(ws_ptr<uint32_t>(c, L.draw_vals), L.draw_hash_cap, 0xFFFFFFFFu, s), "clear draw vals");
+
+    DrawArgs a;
+    a.st = c->d_state;
+    a.indptr = c->graph.indptr;
+    a.n = c->graph.num_nodes;
+    a.nnz = (uint64_t) c->graph.num_entries;
+    a.key0 = (uint32_t) seed;
+    a.key1 = (uint32_t) (seed >> 32);
+    a.epoch = (uint32_t) epoch;
+    a.keys = ws_ptr<uint32_t>(c, L.draw_keys);
+    a.first = ws_ptr<uint32_t>(c, L.draw_vals);
+    a.hmask = L.draw_hash_cap - 1;
+    a.hshift = 32u - (uint32_t) __builtin_ctz(L.draw_hash_cap);
+    a.draw_node = ws_ptr<int32_t>(c, L.draw_node);
+    a.draw_slot = ws_ptr<int32_t>(c, L.draw_slot);
+    a.sums = ws_ptr<int32_t>(c, L.sums_words);      // sized for max(word tiles, draw tiles)
+    a.cache_bitmap = bitmap;
+
+    // The draw hash holds every distinct node seen so far: fewer than |C| before the final
+    // chunk plus at most one chunk's worth, which is what it was sized for.  Stream indices
+    // are kept in 32 bits; a cache that needs more draws than the limit is refused.
+    uint64_t draw_limit = 256ull * (uint64_t) C + 64ull * (uint64_t) L.draw_chunk;
+    if (draw_limit > 0xFFFFFFFFull) draw_limit = 0xFFFFFFFFull;
+    uint64_t j0 = 0;
+    int64_t distinct = 0;
+    const bool i64 = c->graph.indptr_is_i64 != 0;
+    while (distinct < C) {
+        const int64_t count = L.draw_chunk;
+        if (j0 + (uint64_t) count > draw_limit)
+            return fail(c, GNS_ECAPACITY, "cache draw: the stream did not yield cache_size distinct nodes within the draw limit (cache_size too close to the number of nodes with neighbors)", hipSuccess);
+        a.j0 = j0;
+        a.count = (int32_t) count;
+        a.tiles = (int32_t) ((count + kTile - 1) / kTile);
+        a.limit = 0;
+        a.is_final = 0;
+        const unsigned draw_blocks = (unsigned) ((count + kBlock - 1) / kBlock);
+        if (i64) hipLaunchKernelGGL((k_cache_draw<int64_t>), dim3(draw_blocks), dim3(kBlock), 0, s, a);
+        else     hipLaunchKernelGGL((k_cache_draw<int32_t>), dim3(draw_blocks), dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL(k_cache_flags_phase1, dim3((unsigned) a.tiles), dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL(k_cache_flags_phase2, dim3(1), dim3(kBlock), 0, s, a);
+        GNS_HIP_TRY(hipGetLastError(), "cache draw launch");
+        GNS_HIP_TRY(hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s), "cache draw readback");
+        GNS_HIP_TRY(hipStreamSynchronize(s), "cache draw sync");
+        const int64_t found = c->h_state->chunk_distinct;
+        const int64_t need = C - distinct;
+        a.limit = (int32_t) (found < need ? found : need);
+        a.is_final = (found >= need) ? 1 : 0;
+        hipLaunchKernelGGL(k_cache_commit, dim3((unsigned) a.tiles), dim3(kBlock), 0, s, a);
+        GNS_HIP_TRY(hipGetLastError(), "cache commit launch");
+        distinct += a.limit;
+        j0 += (uint64_t) count;
+    }
+
+    IndexArgs x;
+    x.bitmap = bitmap;
+    x.words = L.words;
+    x.sums = ws_ptr<int32_t>(c, L.sums_words);
+    x.tiles = (int32_t) L.word_tiles;
+    x.word_prefix = ws_ptr<int32_t>(c, L.cache_prefix);
+    x.cache_nodes = ws_ptr<int32_t>(c, L.cache_nodes);
+    hipLaunchKernelGGL(k_cache_index_phase1, dim3((unsigned) x.tiles), dim3(kBlock), 0, s, x);
+    hipLaunchKernelGGL(k_cache_index_phase2, dim3(1), dim3(kBlock), 0, s, x);
+    hipLaunchKernelGGL(k_cache_index_phase3, dim3((unsigned) x.tiles), dim3(kBlock), 0, s, x);
+    const unsigned pc_blocks = (unsigned) ((C + kBlock - 1) / kBlock);
+    if (i64) hipLaunchKernelGGL((k_cache_inv_pc<int64_t>), dim3(pc_blocks), dim3(kBlock), 0, s, c->graph.indptr,
+                                (double) c->graph.num_entries, C, x.cache_nodes, ws_ptr<double>(c, L.cache_inv_pc));
+    else     hipLaunchKernelGGL((k_cache_inv_pc<int32_t>), dim3(pc_blocks), dim3(kBlock), 0, s, c->graph.indptr,
+                                (double) c->graph.num_entries, C, x.cache_nodes, ws_ptr<double>(c, L.cache_inv_pc));
+    GNS_HIP_TRY(hipGetLastError(), "cache index launch");
+
+    if (c->graph.feat_dim > 0) {
+        // fill the device table of cached feature rows (slot order) straight from the full store
+        c->cache_valid = false;   // gather below must not consult the table being written
+        GNS_HIP_TRY(launch_gather(c, x.cache_nodes, (int32_t) C, ws_ptr<float>(c, L.cache_feat), s), "cache feature fill");
+    }
+    GNS_HIP_TRY(hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s), "cache readback");
+    GNS_HIP_TRY(hipStreamSynchronize(s), "cache sync");
+    c->cache_draws = (int64_t) c->h_state->cut_draw + 1;
+    c->cache_valid = true;
+    return GNS_OK;
+}
+
+}  // namespace gns

@@ -1,0 +1,191 @@
+// Feature gather (paper Section 2.2 steps 2-3: slice the input nodes' rows;
+// cached rows are already device resident, Section 3.2) and the weighted mean
+// aggregation of one layer (Algorithm 1 bottom-up loop with Section 3.4's
+// rescaling).  Both are pure data movement / fp32 FMA streams: a group of
+// lanes owns one row and moves it with 128-bit accesses.
+#include "gns_internal.h"
+#include "gns_device.hpp"
+
+namespace gns {
+
+struct GatherArgs {
+    const int32_t* nodes;
+    int32_t num_nodes;
+    int64_t n;
+    int32_t feat_dim;
+    float* out;
+    int32_t use_cache;
+    const uint64_t* cache_bitmap;
+    const int32_t* cache_prefix;
+    const float* cache_feat;
+    const float* store;          // device store or device-visible pinned host store
+};
+
+// kLanes lanes per row; kVec: rows are moved as float4 (feat_dim % 4 == 0, 16-byte aligned bases)
+template <int kLanes, bool kVec>
+__global__ void __launch_bounds__(kBlock) k_gather(GatherArgs a)
+{
+    const int lane = (int) (threadIdx.x % kLanes);
+    const int64_t groups_per_block = kBlock / kLanes;
+    const int64_t group = (int64_t) blockIdx.x * groups_per_block + threadIdx.x / kLanes;
+    const int64_t num_groups = (int64_t) gridDim.x * groups_per_block;
+    const int64_t F = a.feat_dim;
+    for (int64_t row = group; row < a.num_nodes; row += num_groups) {
+        const int32_t u = a.nodes[row];
+        const bool valid = u >= 0 && (int64_t) u < a.n;
+        const float* src = nullptr;
+        if (valid) {
+            if (a.use_cache && bitmap_test(a.cache_bitmap, (uint32_t) u))
+                src = a.cache_feat + (int64_t) bitmap_rank(a.cache_bitmap, a.cache_prefix, (uint32_t) u) * F;
+            else
+                src = a.store + (int64_t) u * F;
+        }
+        float* dst = a.out + row * F;
+        if (kVec) {
+            const float4* s4 = reinterpret_cast<const float4*>(src);
+            float4* d4 = reinterpret_cast<float4*>(dst);
+            for (int i = lane; i < (int) (F >> 2); i += kLanes)
+                d4[i] = valid ? s4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        } else {
+            for (int i = lane; i < (int) F; i += kLanes) dst[i] = valid ? src[i] : 0.f;
+        }
+    }
+}
+
+static inline int lanes_for(int64_t units)
+{
+    int l = 4;
+    while (l < 64 && l < units) l <<= 1;
+    return l;
+}
+
+template <bool kVec>
+static void gather_dispatch(int lanes, unsigned blocks, hipStream_t s, const GatherArgs& a)
+{
+    switch (lanes) {
+        case 4:  hipLaunchKernelGGL((k_gather<4, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
+        case 8:  hipLaunchKernelGGL((k_gather<8, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
+        case 16: hipLaunchKernelGGL((k_gather<16, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
+        case 32: hipLaunchKernelGGL((k_gather<32, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
+        default: hipLaunchKernelGGL((k_gather<64, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
+    }
+}
+
+hipError_t launch_gather(gns_ctx* c, const int32_t* nodes, int32_t num_nodes, float* out, hipStream_t s)
+{
+    if (num_nodes == 0) return hipSuccess;
+    const Layout& L = c->lay;
+    GatherArgs a;
+    a.nodes = nodes;
+    a.num_nodes = num_nodes;
+    a.n = c->graph.num_nodes;
+    a.feat_dim = c->graph.feat_dim;
+    a.out = out;
+    a.use_cache = (c->uses_cache && c->cache_valid) ? 1 : 0;
+    a.cache_bitmap = ws_ptr<uint64_t>(c, L.cache_bitmap);
+    a.cache_prefix = ws_ptr<int32_t>(c, L.cache_prefix);
+    a.cache_feat = ws_ptr<float>(c, L.cache_feat);
+    a.store = c->graph.feat_dev ? c->graph.feat_dev : c->graph.feat_host_pinned;
+    const int64_t F = a.feat_dim;
+    const bool vec = (F % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.store) & 15u) == 0) &&
+                     ((reinterpret_cast<uintptr_t>(out) & 15u) == 0);
+    const int lanes = lanes_for(vec ? F / 4 : F);
+    const int64_t groups_per_block = kBlock / lanes;
+    int64_t blocks = (num_nodes + groups_per_block - 1) / groups_per_block;
+    const int64_t cap = (int64_t) c->num_cus * 16;
+    if (blocks > cap) blocks = cap;
+    if (vec) gather_dispatch<true>(lanes, (unsigned) blocks, s, a);
+    else     gather_dispatch<false>(lanes, (unsigned) blocks, s, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+struct AggArgs {
+    const int32_t* indptr;
+    const int32_t* indices;
+    const float* weights;
+    const float* x_src;
+    float* out;
+    int32_t num_dst;
+    int32_t num_src;
+    int32_t feat_dim;
+};
+
+template <int kLanes, bool kVec>
+__global__ void __launch_bounds__(kBlock) k_aggregate(AggArgs a)
+{
+    const int lane = (int) (threadIdx.x % kLanes);
+    const int64_t groups_per_block = kBlock / kLanes;
+    const int64_t group = (int64_t) blockIdx.x * groups_per_block + threadIdx.x / kLanes;
+    const int64_t num_groups = (int64_t) gridDim.x * groups_per_block;
+    const int64_t F = a.feat_dim;
+    for (int64_t row = group; row < a.num_dst; row += num_groups) {
+        const int32_t b = a.indptr[row], e = a.indptr[row + 1];
+        const float n_v = (float) (e - b);
+        if (kVec) {
+            const float4* x4 = reinterpret_cast<const float4*>(a.x_src);
+            float4* o4 = reinterpret_cast<float4*>(a.out + row * F);
+            const int64_t F4 = F >> 2;
+            for (int i = lane; i < (int) F4; i += kLanes) {
+                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                for (int32_t q = b; q < e; ++q) {
+                    const float w = a.weights[q];
+                    const float4 x = x4[(int64_t) a.indices[q] * F4 + i];
+                    acc.x = fmaf(w, x.x, acc.x);
+                    acc.y = fmaf(w, x.y, acc.y);
+                    acc.z = fmaf(w, x.z, acc.z);
+                    acc.w = fmaf(w, x.w, acc.w);
+                }
+                if (e > b) { acc.x /= n_v; acc.y /= n_v; acc.z /= n_v; acc.w /= n_v; }
+                o4[i] = acc;
+            }
+        } else {
+            for (int i = lane; i < (int) F; i += kLanes) {
+                float acc = 0.f;
+                for (int32_t q = b; q < e; ++q) acc = fmaf(a.weights[q], a.x_src[(int64_t) a.indices[q] * F + i], acc);
+                if (e > b) acc /= n_v;
+                a.out[row * F + i] = acc;
+            }
+        }
+    }
+}
+
+template <bool kVec>
+static void aggregate_dispatch(int lanes, unsigned blocks, hipStream_t s, const AggArgs& a)
+{
+    switch (lanes) {
+        case 4:  hipLaunchKernelGGL((k_aggregate<4, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
+        case 8:  hipLaunchKernelGGL((k_aggregate<8, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
+        case 16: hipLaunchKernelGGL((k_aggregate<16, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
+        case 32: hipLaunchKernelGGL((k_aggregate<32, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
+        default: hipLaunchKernelGGL((k_aggregate<64, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
+    }
+}
+
+hipError_t launch_aggregate(gns_ctx* c, const gns_block* blk, const float* x_src, int32_t feat_dim, float* out,
+                            hipStream_t s)
+{
+    if (blk->num_dst == 0 || feat_dim == 0) return hipSuccess;
+    AggArgs a;
+    a.indptr = blk->indptr;
+    a.indices = blk->indices;
+    a.weights = blk->weights;
+    a.x_src = x_src;
+    a.out = out;
+    a.num_dst = blk->num_dst;
+    a.num_src = blk->num_src;
+    a.feat_dim = feat_dim;
+    const int64_t F = feat_dim;
+    const bool vec = (F % 4 == 0) && ((reinterpret_cast<uintptr_t>(x_src) & 15u) == 0) &&
+                     ((reinterpret_cast<uintptr_t>(out) & 15u) == 0);
+    const int lanes = lanes_for(vec ? F / 4 : F);
+    const int64_t groups_per_block = kBlock / lanes;
+    int64_t blocks = (blk->num_dst + groups_per_block - 1) / groups_per_block;
+    const int64_t cap = (int64_t) c->num_cus * 16;
+    if (blocks > cap) blocks = cap;
+    if (vec) aggregate_dispatch<true>(lanes, (unsigned) blocks, s, a);
+    else     aggregate_dispatch<false>(lanes, (unsigned) blocks, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace gns

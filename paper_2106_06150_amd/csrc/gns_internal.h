@@ -1,0 +1,94 @@
+// Host-side internals of the GNS library: context, workspace layout and the
+// launch functions each kernel file exports to the API layer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/gns.h"
+
+namespace gns {
+
+// Device-resident scalars the kernels of one call communicate through.  The
+// whole struct is copied to a pinned host mirror when a call has to report
+// counts.
+struct DeviceState {
+    int32_t num_dst[GNS_MAX_LAYERS + 1];  // rows of layer index i (num_dst[i+1] = num_src of layer i)
+    int32_t num_edges[GNS_MAX_LAYERS];
+    int32_t queue[GNS_MAX_LAYERS];        // row work-queue heads of the per-row sampler
+    int32_t bad_seed;                     // set if a seed was out of range or repeated
+    int32_t chunk_distinct;               // cache draw: first occurrences found in the current chunk
+    int32_t pad0;
+    unsigned long long cut_draw;          // cache draw: stream index of the draw that completed the cache
+};
+
+struct Layout {
+    // persistent cache structures
+    size_t cache_bitmap, cache_prefix, cache_nodes, cache_inv_pc, cache_feat;
+    // cache-draw scratch
+    size_t draw_keys, draw_vals, draw_node, draw_slot;
+    // frontier structures
+    size_t mark_bitmap, hash_slots;
+    // per-layer sampler scratch (fixed stride fanout)
+    size_t s_nbr, s_w, s_cnt;
+    // scan partials
+    size_t sums_rows, sums_words;
+    size_t state;
+    size_t total;
+    // sizes
+    int64_t words;            // ceil(n / 64)
+    int64_t word_tiles;       // ceil(words / kTile)
+    int64_t row_tiles;        // ceil(max rows / kTile)
+    int64_t draw_chunk;       // stream draws processed per round of the cache draw
+    int64_t draw_tiles;
+    uint32_t draw_hash_cap;   // power of two
+    uint32_t hash_cap;        // power of two
+    int64_t max_rows;         // worst-case dst rows of any layer
+    int64_t max_edges;        // worst-case edges of any layer
+    int64_t rows[GNS_MAX_LAYERS + 1];
+    int64_t edges[GNS_MAX_LAYERS];
+};
+
+}  // namespace gns
+
+struct gns_ctx {
+    gns_graph graph;
+    gns_config config;
+    gns::Layout lay;
+    char* ws;                        // device workspace base
+    gns::DeviceState* d_state;       // device
+    gns::DeviceState* h_state;       // pinned host mirror
+    bool uses_cache;
+    bool cache_valid;
+    int64_t cache_draws;
+    int64_t nonzero_degree_nodes;
+    int num_cus;
+    char err[256];
+};
+
+namespace gns {
+
+template <typename T>
+static inline T* ws_ptr(const gns_ctx* c, size_t off) { return reinterpret_cast<T*>(c->ws + off); }
+
+bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char* err, size_t errlen);
+
+// gns_cache.hip
+hipError_t launch_count_nonzero_rows(gns_ctx* c, hipStream_t s, int32_t* d_out);
+gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream_t s);
+
+// gns_sampler.hip
+hipError_t launch_sample_layer(gns_ctx* c, int layer_index, uint64_t seed, const int32_t* dst_nodes,
+                               int32_t* row_eligible, hipStream_t s);
+
+// gns_frontier.hip
+hipError_t launch_batch_begin(gns_ctx* c, const int32_t* seeds, int32_t num_seeds, hipStream_t s);
+hipError_t launch_finish_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s);
+hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v, hipStream_t s);
+hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
+
+// gns_feature.hip
+hipError_t launch_gather(gns_ctx* c, const int32_t* nodes, int32_t num_nodes, float* out, hipStream_t s);
+hipError_t launch_aggregate(gns_ctx* c, const gns_block* blk, const float* x_src, int32_t feat_dim, float* out,
+                            hipStream_t s);
+
+}  // namespace gns

@@ -1,0 +1,267 @@
+"""GPU parity: the HIP library, called through the C ABI, against the CPU oracle.
+
+Integer outputs (cache list, bitmap, draw count, block CSRs, src lists,
+eligible counts, gathered rows) must be bit-exact; fp32 weights within 1e-5
+relative; aggregates within 1e-5 of (1/n_v) * sum |w_e x_e| per element.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from conftest import random_symmetric_csr
+from paper_2106_06150_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2106_06150_amd import binding as B
+    from gpu_harness import GpuGns, full_parity, compare_cache, compare_blocks
+
+U, C = 0, 1
+
+
+def _small(n=3000, avg=14, seed=3, hub=1):
+    ip, ix = random_symmetric_csr(n, avg, np.random.default_rng(seed), hub_boost=hub)
+    return torch.from_numpy(ip), torch.from_numpy(ix)
+
+
+def _feat(n, F, seed=0):
+    g = torch.Generator().manual_seed(seed)
+    return torch.randn((n, F), dtype=torch.float32, generator=g)
+
+
+@pytest.mark.parametrize("offsets", [torch.int32, torch.int64])
+@pytest.mark.parametrize("fanouts,policies", [((10, 5), (U, C)), ((15, 10, 5), (U, U, C)), ((3, 2, 1), (C, C, C)),
+                                              ((4, 4), (U, U)), ((20, 17), (U, C))])
+def test_small_graph_parity(offsets, fanouts, policies):
+    ip, ix = _small()
+    n = ip.numel() - 1
+    feat = _feat(n, 64)
+    gns = GpuGns(ip.to(offsets), ix, feat, fanouts=fanouts, policies=policies, cache_size=300, max_seeds=200)
+    try:
+        for trial in range(3):
+            seeds = synth.uniform_seed_batch(n, 200 - 37 * trial, 100 + trial)
+            full_parity(gns, cache_seed=9, epoch=trial, batch_seed=1000 + trial, seeds=seeds)
+    finally:
+        gns.close()
+
+
+@pytest.mark.parametrize("F", [1, 3, 4, 100, 128, 260])
+def test_feature_widths_and_host_store(F):
+    ip, ix = _small(n=1500)
+    n = ip.numel() - 1
+    feat = _feat(n, F, seed=F)
+    for on_host in (False, True):
+        gns = GpuGns(ip, ix, feat, fanouts=(6, 4), policies=(U, C), cache_size=150, max_seeds=64, feat_on_host=on_host)
+        try:
+            seeds = synth.uniform_seed_batch(n, 64, 5)
+            full_parity(gns, cache_seed=1, epoch=0, batch_seed=77, seeds=seeds)
+        finally:
+            gns.close()
+
+
+def test_unbiased_weight_mode():
+    ip, ix = _small()
+    n = ip.numel() - 1
+    gns = GpuGns(ip, ix, _feat(n, 32), fanouts=(8, 3), policies=(U, C), cache_size=400, max_seeds=128,
+                 wmode=B.GNS_W_UNBIASED)
+    try:
+        full_parity(gns, cache_seed=4, epoch=2, batch_seed=5, seeds=synth.uniform_seed_batch(n, 128, 9))
+    finally:
+        gns.close()
+
+
+def _star_graph(n, hub_degree, extra_avg, seed):
+    """A hub joined to `hub_degree` nodes plus a sparse random background, so one
+    row spans several LDS segments of the per-row sampler."""
+    rng = np.random.default_rng(seed)
+    leaves = rng.choice(np.arange(1, n), size=hub_degree, replace=False)
+    a = np.concatenate([np.zeros(hub_degree, dtype=np.int64), rng.integers(1, n, size=n * extra_avg // 2)])
+    b = np.concatenate([leaves, rng.integers(1, n, size=n * extra_avg // 2)])
+    keep = a != b
+    a, b = a[keep], b[keep]
+    key = np.unique(np.minimum(a, b) * n + np.maximum(a, b))
+    a, b = key // n, key % n
+    row = np.concatenate([a, b])
+    col = np.concatenate([b, a])
+    order = np.lexsort((col, row))
+    row, col = row[order], col[order]
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(np.bincount(row, minlength=n), out=indptr[1:])
+    return torch.from_numpy(indptr), torch.from_numpy(col.astype(np.int32))
+
+
+@pytest.mark.parametrize("hub_degree", [16384, 16385, 40000])
+def test_hub_row_longer_than_one_segment(hub_degree):
+    n = 60000
+    ip, ix = _star_graph(n, hub_degree, 6, hub_degree)
+    assert int(ip[1] - ip[0]) == hub_degree
+    gns = GpuGns(ip, ix, None, fanouts=(5, 7), policies=(C, C), cache_size=3000, max_seeds=16)
+    try:
+        seeds = torch.tensor([0, 5, 17, 9, 33], dtype=torch.int32)       # the hub is a seed
+        full_parity(gns, cache_seed=2, epoch=0, batch_seed=3, seeds=seeds)
+        views, ref = full_parity(gns, cache_seed=2, epoch=1, batch_seed=4, seeds=seeds)
+        assert ref[0].row_eligible[0] > 7                                 # the hub really drew a subset
+    finally:
+        gns.close()
+
+
+def test_rows_with_no_neighbors_and_no_cached_neighbors():
+    # nodes 0..9 isolated, the rest a ring; tiny cache -> most rows have N_C = 0
+    n = 200
+    ring = np.arange(10, n)
+    a = ring
+    b = np.concatenate([ring[1:], ring[:1]])
+    row = np.concatenate([a, b])
+    col = np.concatenate([b, a])
+    order = np.lexsort((col, row))
+    row, col = row[order], col[order]
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(np.bincount(row, minlength=n), out=indptr[1:])
+    ip, ix = torch.from_numpy(indptr), torch.from_numpy(col.astype(np.int32))
+    gns = GpuGns(ip, ix, _feat(n, 8), fanouts=(2, 2), policies=(U, C), cache_size=3, max_seeds=50)
+    try:
+        seeds = torch.arange(0, 50, dtype=torch.int32)                   # includes the isolated nodes
+        views, ref = full_parity(gns, cache_seed=6, epoch=0, batch_seed=8, seeds=seeds)
+        assert (np.diff(ref[1].indptr) == 0).any()
+    finally:
+        gns.close()
+
+
+def test_single_seed_and_repeatability():
+    ip, ix = _small()
+    n = ip.numel() - 1
+    gns = GpuGns(ip, ix, _feat(n, 16), fanouts=(5, 5), policies=(U, C), cache_size=100, max_seeds=8)
+    try:
+        seeds = torch.tensor([42], dtype=torch.int32)
+        v1, _ = full_parity(gns, cache_seed=1, epoch=0, batch_seed=2, seeds=seeds)
+        snap = [{k: (t.clone() if torch.is_tensor(t) else t) for k, t in v.items()} for v in v1]
+        v2, _ = full_parity(gns, cache_seed=1, epoch=0, batch_seed=2, seeds=seeds)
+        for a, b in zip(snap, v2):
+            for k in ("indptr", "indices", "src_nodes", "weights"):
+                assert torch.equal(a[k], b[k])
+    finally:
+        gns.close()
+
+
+def test_error_paths():
+    ip, ix = _small(n=500)
+    n = ip.numel() - 1
+    gns = GpuGns(ip, ix, None, fanouts=(3, 2), policies=(U, C), cache_size=50, max_seeds=32)
+    try:
+        seeds = synth.uniform_seed_batch(n, 32, 1).cuda()
+        with pytest.raises(B.GnsError) as e:                               # no cache drawn yet
+            B.gns_sample_blocks(gns.ctx, 1, seeds, gns.blocks.array)
+        assert e.value.status == B.GNS_ESTATE
+        B.gns_sample_cache(gns.ctx, 1, 0)
+        dup = seeds.clone()
+        dup[5] = dup[4]
+        with pytest.raises(B.GnsError) as e:
+            B.gns_sample_blocks(gns.ctx, 1, dup, gns.blocks.array)
+        assert e.value.status == B.GNS_EINVAL
+        bad = seeds.clone()
+        bad[0] = n
+        with pytest.raises(B.GnsError) as e:
+            B.gns_sample_blocks(gns.ctx, 1, bad, gns.blocks.array)
+        assert e.value.status == B.GNS_EINVAL
+        B.gns_sample_blocks(gns.ctx, 1, seeds, gns.blocks.array)          # still healthy afterwards
+        ref_cache = oracle.sample_cache(ip.numpy(), 1, 0, 50)
+        ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), ref_cache[1], 50, 1, seeds.cpu().numpy(), [3, 2], [U, C])
+        compare_blocks([gns.blocks.views(i) for i in range(2)], ref)
+        small = gns.blocks.array[1].cap_edges
+        gns.blocks.array[1].cap_edges = small - 1
+        with pytest.raises(B.GnsError) as e:
+            B.gns_sample_blocks(gns.ctx, 1, seeds, gns.blocks.array)
+        assert e.value.status == B.GNS_ECAPACITY
+        gns.blocks.array[1].cap_edges = small
+        with pytest.raises(B.GnsError) as e:                               # too many seeds
+            B.gns_sample_blocks(gns.ctx, 1, torch.arange(33, dtype=torch.int32).cuda(), gns.blocks.array)
+        assert e.value.status == B.GNS_EINVAL
+        with pytest.raises(B.GnsError) as e:                               # no features configured
+            B.gns_gather_features(gns.ctx, seeds, 4, torch.empty(4, device="cuda"))
+        assert e.value.status == B.GNS_ESTATE
+    finally:
+        gns.close()
+
+
+def test_create_rejects_bad_graphs_and_configs():
+    ip, ix = _small(n=300)
+    n = ip.numel() - 1
+    dev = torch.device("cuda:0")
+
+    def create(indptr, indices, fanouts=(2,), policies=(C,), cache_size=10, ws_shrink=0):
+        g = B.make_graph(indptr.to(dev), indices.to(dev))
+        c = B.make_config(fanouts, policies, cache_size, 8)
+        ws = B.alloc_workspace(g, c, dev)
+        if ws_shrink:
+            ws = ws[:ws.numel() - ws_shrink]
+        ctx = B.gns_create(g, c, ws)
+        B.gns_destroy(ctx)
+
+    create(ip, ix)
+    unsorted = ix.clone()
+    b, e = int(ip[7]), int(ip[8])
+    assert e - b >= 2
+    unsorted[b], unsorted[b + 1] = ix[b + 1], ix[b]
+    with pytest.raises(B.GnsError) as err:
+        create(ip, unsorted)
+    assert err.value.status == B.GNS_EINVAL
+    out_of_range = ix.clone()
+    out_of_range[3] = n
+    with pytest.raises(B.GnsError):
+        create(ip, out_of_range)
+    bad_ip = ip.clone()
+    bad_ip[5] = bad_ip[6] + 1
+    with pytest.raises(B.GnsError):
+        create(bad_ip, ix)
+    with pytest.raises(B.GnsError) as err:                                  # more cache than nodes with neighbors
+        create(ip, ix, cache_size=n + 1)
+    assert err.value.status == B.GNS_EINVAL
+    with pytest.raises(B.GnsError) as err:
+        create(ip, ix, policies=(B.GNS_CACHE_FIRST,))
+    assert err.value.status == B.GNS_ENOTIMPL
+    with pytest.raises(B.GnsError) as err:
+        create(ip, ix, ws_shrink=256)
+    assert err.value.status == B.GNS_ECAPACITY
+
+
+def test_cache_nearly_all_nodes():
+    # the cache takes every node that has a neighbor: the stream must run until the rarest node shows up
+    ip, ix = _small(n=300, avg=6)
+    deg = (ip[1:] - ip[:-1])
+    support = int((deg > 0).sum())
+    gns = GpuGns(ip, ix, None, fanouts=(2,), policies=(C,), cache_size=support, max_seeds=8)
+    try:
+        compare_cache(gns.sample_cache(3, 0), oracle.sample_cache(ip.numpy(), 3, 0, support))
+    finally:
+        gns.close()
+
+
+def _config_parity(cfg_id, batches, device_gen="cpu"):
+    c = synth.CONFIGS[cfg_id]
+    sd = synth.config_seeds(cfg_id)
+    g = synth.make_config_graph(cfg_id, device=device_gen)
+    indptr, indices = g.indptr.cpu(), g.indices.cpu()
+    feat = synth.node_features(c["n"], c["feat"], sd["feat"])
+    cache_size = int(c["n"] * c["cache_frac"])
+    L = len(c["fanouts"])
+    policies = [U] * (L - 1) + [C]
+    gns = GpuGns(indptr, indices, feat, fanouts=c["fanouts"], policies=policies, cache_size=cache_size,
+                 max_seeds=c["batch"], feat_on_host=c["feat_on_host"])
+    try:
+        for b in range(batches):
+            seeds = synth.uniform_seed_batch(c["n"], c["batch"], sd["batch"] + b)
+            views, ref = full_parity(gns, cache_seed=sd["cache"], epoch=b, batch_seed=sd["batch"] + b, seeds=seeds)
+            print("cfg%d batch %d: rows/src/edges per layer %s" % (
+                cfg_id, b, [(r.num_dst, r.num_src, r.num_edges) for r in ref]), flush=True)
+    finally:
+        gns.close()
+
+
+def test_config1_tiny_graph():
+    _config_parity(1, batches=3)
+
+
+def test_config2_medium_graph():
+    _config_parity(2, batches=2)
