@@ -182,6 +182,23 @@ gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t n
 gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_src_dev, int32_t feat_dim,
                          float* out_dev, void* hip_stream);
 
+/* Stage timing for benchmarks (no part of the method).  Stages: GNS_STAGE_SAMPLE + i
+ * = the sampler kernel of layer index i; GNS_STAGE_FINISH + i = the union / relabel
+ * kernels of layer index i; GNS_STAGE_GATHER; GNS_STAGE_AGGREGATE.
+ * gns_profile_begin(ctx, stage_mask, capacity) makes the following calls bracket
+ * every launch of a stage whose bit is set in stage_mask with a pair of HIP events on
+ * the caller's stream (at most `capacity` pairs are kept, later ones are dropped;
+ * stage_mask 0 switches timing off and releases the events).
+ * gns_profile_collect(ctx, stage, &total_ms, &launches) synchronises the recorded
+ * events of that stage, returns the sum of their elapsed times and their number, and
+ * forgets them.  Both are host calls; event creation is the only allocation. */
+#define GNS_STAGE_SAMPLE 0
+#define GNS_STAGE_FINISH 8
+#define GNS_STAGE_GATHER 16
+#define GNS_STAGE_AGGREGATE 17
+gns_status gns_profile_begin(gns_ctx* ctx, uint32_t stage_mask, int32_t capacity);
+gns_status gns_profile_collect(gns_ctx* ctx, int32_t stage, double* total_ms, int32_t* launches);
+
 /* Message of the last failure on this context (or, for ctx == NULL, of the
  * last failed gns_create / gns_workspace_bytes on this thread).  Never NULL. */
 const char* gns_last_error(const gns_ctx* ctx);

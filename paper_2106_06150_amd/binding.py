@@ -66,6 +66,10 @@ def _load():
     lib.gns_gather_features.restype = ctypes.c_int
     lib.gns_aggregate.argtypes = [vp, P(gns_block), vp, i32, vp, vp]
     lib.gns_aggregate.restype = ctypes.c_int
+    lib.gns_profile_begin.argtypes = [vp, ctypes.c_uint32, i32]
+    lib.gns_profile_begin.restype = ctypes.c_int
+    lib.gns_profile_collect.argtypes = [vp, i32, P(ctypes.c_double), P(i32)]
+    lib.gns_profile_collect.restype = ctypes.c_int
     lib.gns_last_error.argtypes = [vp]
     lib.gns_last_error.restype = ctypes.c_char_p
     return lib
@@ -74,7 +78,10 @@ def _load():
 lib = _load()
 
 EXPORTED = ["gns_workspace_bytes", "gns_block_capacity", "gns_create", "gns_destroy", "gns_sample_cache",
-            "gns_cache_view", "gns_sample_blocks", "gns_gather_features", "gns_aggregate", "gns_last_error"]
+            "gns_cache_view", "gns_sample_blocks", "gns_gather_features", "gns_aggregate", "gns_last_error",
+            "gns_profile_begin", "gns_profile_collect"]
+
+GNS_STAGE_SAMPLE, GNS_STAGE_FINISH, GNS_STAGE_GATHER, GNS_STAGE_AGGREGATE = 0, 8, 16, 17
 
 
 class GnsError(RuntimeError):
@@ -180,6 +187,17 @@ def gns_gather_features(ctx, nodes_dev, num_nodes, out_dev, stream=None):
 def gns_aggregate(ctx, block, x_src_dev, feat_dim, out_dev, stream=None):
     _check(lib.gns_aggregate(ctx, ctypes.byref(block), x_src_dev.data_ptr(), feat_dim, out_dev.data_ptr(),
                              _stream_ptr(stream)), ctx)
+
+
+def gns_profile_begin(ctx, stage_mask, capacity):
+    _check(lib.gns_profile_begin(ctx, stage_mask, capacity), ctx)
+
+
+def gns_profile_collect(ctx, stage):
+    """Returns (total_ms, launches) of the recorded launches of `stage`."""
+    ms, n = ctypes.c_double(), ctypes.c_int32()
+    _check(lib.gns_profile_collect(ctx, stage, ctypes.byref(ms), ctypes.byref(n)), ctx)
+    return ms.value, n.value
 
 
 # ---------------------------------------------------------------------------

@@ -212,9 +212,73 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
     return GNS_OK;
 }
 
+static void profile_release(gns_ctx* c)
+{
+    for (int32_t i = 0; i < c->prof_capacity; ++i) {
+        (void) hipEventDestroy(c->prof[i].start);
+        (void) hipEventDestroy(c->prof[i].stop);
+    }
+    free(c->prof);
+    c->prof = nullptr;
+    c->prof_capacity = 0;
+    c->prof_count = 0;
+    c->prof_mask = 0;
+}
+
+gns_status gns_profile_begin(gns_ctx* ctx, uint32_t stage_mask, int32_t capacity)
+{
+    if (!ctx) return GNS_EINVAL;
+    profile_release(ctx);
+    if (stage_mask == 0) return GNS_OK;
+    if (capacity < 1 || capacity > (1 << 20)) return ctx_fail(ctx, GNS_EINVAL, "profile capacity out of range");
+    ctx->prof = static_cast<ProfileRecord*>(calloc((size_t) capacity, sizeof(ProfileRecord)));
+    if (!ctx->prof) return ctx_fail(ctx, GNS_ENOMEM, "profile records");
+    for (int32_t i = 0; i < capacity; ++i) {
+        hipError_t e = hipEventCreate(&ctx->prof[i].start);
+        if (e == hipSuccess) e = hipEventCreate(&ctx->prof[i].stop);
+        if (e != hipSuccess) {
+            ctx->prof_capacity = i;
+            profile_release(ctx);
+            return ctx_fail(ctx, GNS_EHIP, "hipEventCreate", e);
+        }
+    }
+    ctx->prof_capacity = capacity;
+    ctx->prof_mask = stage_mask;
+    return GNS_OK;
+}
+
+gns_status gns_profile_collect(gns_ctx* ctx, int32_t stage, double* total_ms, int32_t* launches)
+{
+    if (!ctx || !total_ms || !launches) return GNS_EINVAL;
+    double sum = 0.0;
+    int32_t n = 0, kept = 0;
+    for (int32_t i = 0; i < ctx->prof_count; ++i) {
+        ProfileRecord r = ctx->prof[i];
+        if (r.stage != stage) {                 // keep records of other stages, compacted to the front
+            ProfileRecord tmp = ctx->prof[kept];
+            ctx->prof[kept] = r;
+            ctx->prof[i] = tmp;
+            ++kept;
+            continue;
+        }
+        hipError_t e = hipEventSynchronize(r.stop);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.start, r.stop);
+        if (e != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "profile collect", e);
+        sum += (double) ms;
+        ++n;
+    }
+    // the collected records' events now sit behind `kept`; reuse them
+    ctx->prof_count = kept;
+    *total_ms = sum;
+    *launches = n;
+    return GNS_OK;
+}
+
 gns_status gns_destroy(gns_ctx* ctx)
 {
     if (!ctx) return GNS_OK;
+    profile_release(ctx);
     if (ctx->h_state) (void) hipHostFree(ctx->h_state);
     delete ctx;
     return GNS_OK;
@@ -265,9 +329,15 @@ gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_d
     if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "batch begin", e);
     const int32_t* dst = seeds_dev;
     for (int i = 0; i < nl; ++i) {
-        e = launch_sample_layer(c, i, seed, dst, blocks[i].row_eligible, s);
+        {
+            StageTimer t(c, GNS_STAGE_SAMPLE + i, s);
+            e = launch_sample_layer(c, i, seed, dst, blocks[i].row_eligible, s);
+        }
         if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample layer", e);
-        e = launch_finish_layer(c, i, dst, &blocks[i], s);
+        {
+            StageTimer t(c, GNS_STAGE_FINISH + i, s);
+            e = launch_finish_layer(c, i, dst, &blocks[i], s);
+        }
         if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "finish layer", e);
         dst = blocks[i].src_nodes;
     }
@@ -291,6 +361,7 @@ gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t n
     if (num_nodes < 0) return ctx_fail(ctx, GNS_EINVAL, "num_nodes must be >= 0");
     if (num_nodes == 0) return GNS_OK;
     if (!nodes_dev || !out_dev) return ctx_fail(ctx, GNS_EINVAL, "null nodes or output");
+    StageTimer t(ctx, GNS_STAGE_GATHER, static_cast<hipStream_t>(hip_stream));
     hipError_t e = launch_gather(ctx, nodes_dev, num_nodes, out_dev, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "gather launch", e);
     return GNS_OK;
@@ -305,6 +376,7 @@ gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_sr
     if (block->num_dst < 0 || block->num_src < block->num_dst || block->num_edges < 0)
         return ctx_fail(ctx, GNS_EINVAL, "block counts are inconsistent");
     if (!block->indptr || !block->indices || !block->weights) return ctx_fail(ctx, GNS_EINVAL, "block has a null buffer");
+    StageTimer t(ctx, GNS_STAGE_AGGREGATE, static_cast<hipStream_t>(hip_stream));
     hipError_t e = launch_aggregate(ctx, block, x_src_dev, feat_dim, out_dev, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "aggregate launch", e);
     return GNS_OK;

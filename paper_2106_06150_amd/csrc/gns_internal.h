@@ -50,6 +50,13 @@ struct Layout {
 
 }  // namespace gns
 
+namespace gns {
+struct ProfileRecord {
+    int32_t stage;
+    hipEvent_t start, stop;
+};
+}  // namespace gns
+
 struct gns_ctx {
     gns_graph graph;
     gns_config config;
@@ -62,6 +69,11 @@ struct gns_ctx {
     int64_t cache_draws;
     int64_t nonzero_degree_nodes;
     int num_cus;
+    // optional stage timing (benchmarks only)
+    uint32_t prof_mask;
+    int32_t prof_capacity;
+    int32_t prof_count;
+    gns::ProfileRecord* prof;
     char err[256];
 };
 
@@ -71,6 +83,24 @@ template <typename T>
 static inline T* ws_ptr(const gns_ctx* c, size_t off) { return reinterpret_cast<T*>(c->ws + off); }
 
 bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char* err, size_t errlen);
+
+// Brackets a stage's launches with events when that stage is being timed.
+struct StageTimer {
+    gns_ctx* c;
+    hipStream_t s;
+    int32_t slot;
+    StageTimer(gns_ctx* ctx, int32_t stage, hipStream_t stream) : c(ctx), s(stream), slot(-1)
+    {
+        if (!(c->prof_mask & (1u << stage)) || c->prof_count >= c->prof_capacity) return;
+        slot = c->prof_count++;
+        c->prof[slot].stage = stage;
+        (void) hipEventRecord(c->prof[slot].start, s);
+    }
+    ~StageTimer()
+    {
+        if (slot >= 0) (void) hipEventRecord(c->prof[slot].stop, s);
+    }
+};
 
 // gns_cache.hip
 hipError_t launch_count_nonzero_rows(gns_ctx* c, hipStream_t s, int32_t* d_out);

@@ -207,13 +207,15 @@ __global__ void __launch_bounds__(kBlock) k_sample_cache_only(SampleArgs a)
     const int32_t R = a.st->num_dst[a.layer_index];
     const int k = a.fanout;
 
-    for (;;) {
-        // Row index, node and row extent are made wave-uniform scalars (readfirstlane): every
-        // loop below then branches on scalar conditions and the wave stays converged around
-        // the ballots and the LDS exchange.
-        const int32_t row = claim_row(&a.st->queue[a.layer_index]);
+    // Rows are dealt round-robin to the waves of the grid.  (A single atomic row counter was
+    // measured first: same-address atomics serialise at roughly 12 ns each, which alone cost
+    // 1 ms for 85K rows.)  Row index, node and row extent are wave-uniform scalars
+    // (readfirstlane): every loop below branches on scalar conditions and the wave stays
+    // converged around the ballots and the LDS exchange.
+    const int32_t wave_global = (int32_t) blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
+    const int32_t num_waves = (int32_t) gridDim.x * kWavesPerBlock;
+    for (int32_t row = wave_global; row < R; row += num_waves) {
         const int lane = opaque_lane_id();
-        if (row >= R) break;                                   // every wave reaches this
 
         const int32_t vi = __builtin_amdgcn_readfirstlane(a.dst_nodes[row]);
         int64_t start = 0, deg = 0;

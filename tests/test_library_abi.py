@@ -25,7 +25,7 @@ def declared_functions():
 
 def test_header_functions_are_exported():
     names = declared_functions()
-    assert len(names) == 10, names
+    assert len(names) == 12, names
     lib = ctypes.CDLL(LIB)
     for name in names:
         assert hasattr(lib, name), name
@@ -92,6 +92,7 @@ def test_null_context_calls_return_einval():
     assert lib.gns_aggregate(None, None, None, 1, None, None) == B.GNS_EINVAL
     assert lib.gns_cache_view(None, None, None, None, None) == B.GNS_EINVAL
     assert lib.gns_destroy(None) == B.GNS_OK
+    assert lib.gns_profile_begin(None, 1, 4) == B.GNS_EINVAL
     assert isinstance(lib.gns_last_error(None), bytes)
 
 
