@@ -32,6 +32,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload id (see synth.CONFIGS)")
     ap.add_argument("--cpu-batches", type=int, default=32, help="mini-batches the CPU oracle is timed on (0: skip)")
     ap.add_argument("--stages", action="store_true", help="add an untimed pass that times every stage")
+    ap.add_argument("--threads", type=int, default=0, help="1: one host thread per slot")
+    ap.add_argument("--slots", type=int, default=4,
+                    help="mini-batches kept in flight (one context + stream each; they share the cache)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported"
@@ -65,31 +68,83 @@ def main():
     config = B.make_config(fanouts, policies, cache_size, batch)
     ws = B.alloc_workspace(graph, config, dev)
     ctx = B.gns_create(graph, config, ws)
-    blocks = B.BlockBuffers(graph, config, dev)
     last = L - 1
-    x_in = torch.empty((blocks.array[last].cap_src, F), dtype=torch.float32, device=dev)
-    h_out = torch.empty((blocks.array[last].cap_dst, F), dtype=torch.float32, device=dev)
-    src_last = blocks.tensors[last]["src_nodes"]
+    # one slot = context + stream + output buffers; slot 0 is the created context, the others are forks
+    S = max(1, args.slots)
+    ctxs, fork_ws = [ctx], []
+    for _ in range(S - 1):
+        w = torch.empty(B.gns_fork_workspace_bytes(ctx), dtype=torch.uint8, device=dev)
+        fork_ws.append(w)
+        ctxs.append(B.gns_fork(ctx, w))
+    streams = [torch.cuda.Stream() for _ in range(S)]
+    bufs = [B.BlockBuffers(graph, config, dev) for _ in range(S)]
+    x_in = [torch.empty((bufs[i].array[last].cap_src, F), dtype=torch.float32, device=dev) for i in range(S)]
+    h_out = [torch.empty((bufs[i].array[last].cap_dst, F), dtype=torch.float32, device=dev) for i in range(S)]
+    blocks = bufs[0]
 
     def step(b):
+        """One mini-batch, enqueued on its slot's stream without any host synchronisation."""
         if b % refresh == 0:
-            B.gns_sample_cache(ctx, sd["cache"], b // refresh)
-        B.gns_sample_blocks(ctx, sd["batch"] + b, seeds[b], blocks.array)
-        blk = blocks.array[last]
-        B.gns_gather_features(ctx, src_last, blk.num_src, x_in)
-        B.gns_aggregate(ctx, blk, x_in, F, h_out)
+            torch.cuda.synchronize()                      # no batch may be in flight while the cache changes
+            B.gns_sample_cache(ctx, sd["cache"], b // refresh, streams[0])
+        i = b % S
+        st = streams[i]
+        B.gns_sample_blocks_async(ctxs[i], sd["batch"] + b, seeds[b], bufs[i].array, st)
+        B.gns_gather_features(ctxs[i], bufs[i].tensors[last]["src_nodes"], -1, x_in[i], st)
+        B.gns_aggregate(ctxs[i], bufs[i].array[last], x_in[i], F, h_out[i], st)
 
+    def step_sync(b):
+        """The same mini-batch on slot 0 with host-visible counts (used for the byte accounting)."""
+        if b % refresh == 0:
+            torch.cuda.synchronize()
+            B.gns_sample_cache(ctx, sd["cache"], b // refresh, streams[0])
+        B.gns_sample_blocks(ctx, sd["batch"] + b, seeds[b], blocks.array, streams[0])
+        blk = blocks.array[last]
+        B.gns_gather_features(ctx, blocks.tensors[last]["src_nodes"], blk.num_src, x_in[0], streams[0])
+        B.gns_aggregate(ctx, blk, x_in[0], F, h_out[0], streams[0])
+
+    torch.cuda.synchronize()
     for b in range(args.warmup):
         step(b)
     torch.cuda.synchronize()
 
-    # ---- timed region: the input-layer sampler kernel is bracketed by HIP events
+    def run_range(lo, hi):
+        """Steps lo..hi-1.  With --threads, each slot is driven by its own host thread (kernel
+        launches are host-bound); the threads meet at every cache refresh."""
+        if not args.threads or S == 1:
+            for b in range(lo, hi):
+                step(b)
+            return
+        import threading
+        barrier = threading.Barrier(S)
+
+        def worker(i):
+            for b in range(lo, hi):
+                if b % refresh == 0:
+                    barrier.wait()
+                    if i == 0:
+                        torch.cuda.synchronize()
+                        B.gns_sample_cache(ctx, sd["cache"], b // refresh, streams[0])
+                    barrier.wait()
+                if b % S != i:
+                    continue
+                st = streams[i]
+                B.gns_sample_blocks_async(ctxs[i], sd["batch"] + b, seeds[b], bufs[i].array, st)
+                B.gns_gather_features(ctxs[i], bufs[i].tensors[last]["src_nodes"], -1, x_in[i], st)
+                B.gns_aggregate(ctxs[i], bufs[i].array[last], x_in[i], F, h_out[i], st)
+
+        ths = [threading.Thread(target=worker, args=(i,)) for i in range(S)]
+        for t in ths:
+            t.start()
+        for t in ths:
+            t.join()
+
+    # ---- timed region: on slot 0 the input-layer sampler is bracketed by HIP events
     dom_stage = B.GNS_STAGE_SAMPLE + last
     B.gns_profile_begin(ctx, 1 << dom_stage, args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for b in range(args.warmup, total):
-        step(b)
+    run_range(args.warmup, total)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     dom_ms, dom_launches = B.gns_profile_collect(ctx, dom_stage)
@@ -110,7 +165,8 @@ def main():
         mask |= (1 << B.GNS_STAGE_GATHER) | (1 << B.GNS_STAGE_AGGREGATE)
         B.gns_profile_begin(ctx, mask, args.steps * (2 * L + 2))
     for b in range(args.warmup, total):
-        step(b)
+        step_sync(b)
+        torch.cuda.synchronize()
         blk = blocks.array[last]
         v = blocks.views(last)
         rows = blk.num_dst
@@ -138,6 +194,8 @@ def main():
             stage_ms[name] = round(1e3 * ms / max(cnt, 1), 2)
         B.gns_profile_begin(ctx, 0, 0)
 
+    for c_ in ctxs[1:]:
+        B.gns_destroy(c_)
     achieved = (alg_bytes / args.steps) / (1e6 * dom_ms / max(dom_launches, 1))   # GB/s
     roofline = {
         "kernel": "k_sample_cache_only (input-layer sampler)",
@@ -199,7 +257,7 @@ def main():
         "config": {"workload": "config %d: Chung-Lu graph n=%d nnz=%d gamma=%.1f, F=%d fp32 in HBM, cache %d nodes "
                                "redrawn every %d mini-batches, fanouts %s, batch %d"
                                % (cfg_id, n, g.nnz, c["gamma"], F, cache_size, refresh, fanouts, batch),
-                   "max_degree": g.max_degree,
+                   "max_degree": g.max_degree, "batches_in_flight": S,
                    "avg_per_batch": {k: round(v / args.steps, 1) for k, v in stats.items()}},
         "roofline": roofline,
         "cpu_baseline": cpu,

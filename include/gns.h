@@ -133,6 +133,17 @@ gns_status gns_block_capacity(const gns_graph* graph, const gns_config* config, 
 gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_config* config,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* A second context on the same graph, config and cache, for keeping several
+ * mini-batches in flight (one context per stream; mini-batches are independent
+ * given the cache, as the paper's sampling workers are).  The fork owns its per-batch
+ * scratch in `workspace` (gns_fork_workspace_bytes(parent) bytes, 256-byte aligned) and
+ * reads the cache structures of the context made by gns_create, which must outlive it.
+ * gns_sample_cache is called on that original context only, and only while no fork has
+ * work in flight.  Destroy forks with gns_destroy. */
+size_t gns_fork_workspace_bytes(const gns_ctx* parent);
+gns_status gns_fork(gns_ctx* parent, void* workspace, size_t workspace_bytes, void* hip_stream,
+                    gns_ctx** out_child);
+
 gns_status gns_destroy(gns_ctx* ctx);
 
 /* Section 3.2, Eq. (1), Theorem 1.  Draws the cache C for (seed, epoch):
@@ -166,10 +177,27 @@ gns_status gns_cache_view(gns_ctx* ctx, const int32_t** cache_nodes, int64_t* ca
 gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
                              gns_block* blocks, void* hip_stream);
 
+/* The same work without the final synchronisation, for callers that keep several
+ * mini-batches in flight.  gns_sample_blocks_async validates, enqueues everything
+ * (including the copy of the counts to pinned host memory) and returns; until
+ * gns_sample_blocks_wait the blocks' host counts hold the placeholder
+ * GNS_DEVICE_COUNTS(layer_index), which gns_aggregate understands (see there).
+ * gns_sample_blocks_wait synchronises the stream, fills in the counts and reports
+ * GNS_EINVAL for bad seeds.  gns_sample_blocks is exactly async followed by wait.
+ * Between the two calls no other call may use the context's block state except
+ * gns_gather_features / gns_aggregate on the same stream. */
+#define GNS_DEVICE_COUNTS(layer_index) (-1 - (layer_index))
+gns_status gns_sample_blocks_async(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
+                                   gns_block* blocks, void* hip_stream);
+gns_status gns_sample_blocks_wait(gns_ctx* ctx, gns_block* blocks, void* hip_stream);
+
 /* Section 2.2 steps 2-3.  out_dev[j, :] = feature row of nodes_dev[j]
  * (fp32[num_nodes x F] row-major, bit copies).  A cached node is read from the
  * device cache table, any other from feat_dev if given, else from
- * feat_host_pinned.  num_nodes may be 0.  Enqueue only (no synchronisation). */
+ * feat_host_pinned.  num_nodes may be 0.  Enqueue only (no synchronisation).
+ * num_nodes < 0 means: the number of input nodes (src nodes of the input-layer
+ * block) of the last gns_sample_blocks(_async) on this context, read on the device;
+ * out_dev must then hold the input layer's cap_src rows. */
 gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t num_nodes, float* out_dev,
                                void* hip_stream);
 
@@ -178,7 +206,9 @@ gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t n
  * weights[e] * x_src_dev[indices[e], :], n_v = row length, zeros for an empty
  * row.  x_src_dev is fp32[block->num_src x feat_dim], out_dev is
  * fp32[block->num_dst x feat_dim], both row-major.  fp32 arithmetic, edges
- * accumulated in row order.  Uses the block's host counts.  Enqueue only. */
+ * accumulated in row order.  Uses the block's host counts; if block->num_dst is
+ * GNS_DEVICE_COUNTS(i) the row count of layer index i is read on the device instead
+ * (out_dev must then hold cap_dst rows).  Enqueue only. */
 gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_src_dev, int32_t feat_dim,
                          float* out_dev, void* hip_stream);
 

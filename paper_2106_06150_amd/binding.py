@@ -54,6 +54,10 @@ def _load():
     lib.gns_block_capacity.restype = ctypes.c_int
     lib.gns_create.argtypes = [P(vp), P(gns_graph), P(gns_config), vp, ctypes.c_size_t, vp]
     lib.gns_create.restype = ctypes.c_int
+    lib.gns_fork_workspace_bytes.argtypes = [vp]
+    lib.gns_fork_workspace_bytes.restype = ctypes.c_size_t
+    lib.gns_fork.argtypes = [vp, vp, ctypes.c_size_t, vp, P(vp)]
+    lib.gns_fork.restype = ctypes.c_int
     lib.gns_destroy.argtypes = [vp]
     lib.gns_destroy.restype = ctypes.c_int
     lib.gns_sample_cache.argtypes = [vp, u64, u64, vp]
@@ -62,6 +66,10 @@ def _load():
     lib.gns_cache_view.restype = ctypes.c_int
     lib.gns_sample_blocks.argtypes = [vp, u64, vp, i32, P(gns_block), vp]
     lib.gns_sample_blocks.restype = ctypes.c_int
+    lib.gns_sample_blocks_async.argtypes = [vp, u64, vp, i32, P(gns_block), vp]
+    lib.gns_sample_blocks_async.restype = ctypes.c_int
+    lib.gns_sample_blocks_wait.argtypes = [vp, P(gns_block), vp]
+    lib.gns_sample_blocks_wait.restype = ctypes.c_int
     lib.gns_gather_features.argtypes = [vp, vp, i32, vp, vp]
     lib.gns_gather_features.restype = ctypes.c_int
     lib.gns_aggregate.argtypes = [vp, P(gns_block), vp, i32, vp, vp]
@@ -79,7 +87,8 @@ lib = _load()
 
 EXPORTED = ["gns_workspace_bytes", "gns_block_capacity", "gns_create", "gns_destroy", "gns_sample_cache",
             "gns_cache_view", "gns_sample_blocks", "gns_gather_features", "gns_aggregate", "gns_last_error",
-            "gns_profile_begin", "gns_profile_collect"]
+            "gns_profile_begin", "gns_profile_collect", "gns_sample_blocks_async", "gns_sample_blocks_wait",
+            "gns_fork", "gns_fork_workspace_bytes"]
 
 GNS_STAGE_SAMPLE, GNS_STAGE_FINISH, GNS_STAGE_GATHER, GNS_STAGE_AGGREGATE = 0, 8, 16, 17
 
@@ -157,6 +166,17 @@ def gns_create(graph, config, workspace, stream=None):
     return ctx
 
 
+def gns_fork_workspace_bytes(parent):
+    return lib.gns_fork_workspace_bytes(parent)
+
+
+def gns_fork(parent, workspace, stream=None):
+    child = ctypes.c_void_p()
+    _check(lib.gns_fork(parent, workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                        _stream_ptr(stream), ctypes.byref(child)), parent)
+    return child
+
+
 def gns_destroy(ctx):
     _check(lib.gns_destroy(ctx))
 
@@ -178,6 +198,16 @@ def gns_sample_blocks(ctx, seed, seeds_dev, blocks, stream=None):
     """blocks: ctypes array of gns_block (see alloc_blocks)."""
     assert seeds_dev.is_cuda and seeds_dev.dtype == torch.int32 and seeds_dev.is_contiguous()
     _check(lib.gns_sample_blocks(ctx, seed, seeds_dev.data_ptr(), seeds_dev.numel(), blocks, _stream_ptr(stream)), ctx)
+
+
+def gns_sample_blocks_async(ctx, seed, seeds_dev, blocks, stream=None):
+    assert seeds_dev.is_cuda and seeds_dev.dtype == torch.int32 and seeds_dev.is_contiguous()
+    _check(lib.gns_sample_blocks_async(ctx, seed, seeds_dev.data_ptr(), seeds_dev.numel(), blocks,
+                                       _stream_ptr(stream)), ctx)
+
+
+def gns_sample_blocks_wait(ctx, blocks, stream=None):
+    _check(lib.gns_sample_blocks_wait(ctx, blocks, _stream_ptr(stream)), ctx)
 
 
 def gns_gather_features(ctx, nodes_dev, num_nodes, out_dev, stream=None):

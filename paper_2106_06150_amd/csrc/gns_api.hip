@@ -55,6 +55,7 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     const int64_t C = uses_cache ? cfg->cache_size : 0;
     L.words = (n + 63) / 64;
     L.word_tiles = (L.words + kTile - 1) / kTile;
+    L.mark_tiles = (L.words + kMarkTile - 1) / kMarkTile;
 
     // worst-case frontier growth: rows[i+1] = min(rows[i] * (1 + k_i), n)
     L.rows[0] = cfg->max_seeds;
@@ -80,18 +81,8 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
 
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    // per-batch scratch (every forked context has its own copy of these sections)
     L.state = take(sizeof(DeviceState) + 64);
-    L.cache_bitmap = take((size_t) L.words * 8);
-    L.cache_prefix = take((size_t) L.words * 4);
-    L.cache_nodes = take((size_t) (C > 0 ? C : 1) * 4);
-    L.cache_inv_pc = take((size_t) (C > 0 ? C : 1) * 8);
-    L.cache_feat = take((size_t) (C > 0 ? C : 1) * (size_t) (g->feat_dim > 0 ? g->feat_dim : 1) * 4);
-    if (uses_cache) {
-        L.draw_keys = take((size_t) L.draw_hash_cap * 4);
-        L.draw_vals = take((size_t) L.draw_hash_cap * 4);
-        L.draw_node = take((size_t) L.draw_chunk * 4);
-        L.draw_slot = take((size_t) L.draw_chunk * 4);
-    }
     L.mark_bitmap = take((size_t) L.words * 8);
     L.hash_slots = take((size_t) L.hash_cap * 8);
     L.s_nbr = take((size_t) L.max_edges * 4);
@@ -100,6 +91,29 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     L.sums_rows = take((size_t) (L.row_tiles + 1) * 4);
     const int64_t word_or_draw_tiles = L.word_tiles > L.draw_tiles ? L.word_tiles : L.draw_tiles;
     L.sums_words = take((size_t) (word_or_draw_tiles + 1) * 4);
+    L.sums_marks = take((size_t) (L.mark_tiles + 1) * 4);
+    L.sums_plan = take((size_t) (L.max_rows / kBlock + 2) * 4);
+    if (uses_cache) {
+        // a dst row of deg entries touches at most deg/64 + 2 aligned chunks; dst rows are distinct
+        L.max_chunks = g->num_entries / 64 + 2 * L.max_rows + 64;
+        if (L.max_chunks >= (int64_t) 1 << 31) GNS_BAD("graph too large for 32-bit chunk ids");
+        L.plan_cnt = take((size_t) L.max_rows * 4);
+        L.plan_g0 = take((size_t) L.max_rows * 4);
+        L.plan_desc = take((size_t) L.max_chunks * 4);
+    }
+    // shared: the cache and everything that is a pure function of (graph, cache)
+    L.shared_begin = off;
+    L.cache_bitmap = take((size_t) L.words * 8);
+    L.cache_prefix = take((size_t) L.words * 4);
+    L.cache_nodes = take((size_t) (C > 0 ? C : 1) * 4);
+    L.cache_feat = take((size_t) (C > 0 ? C : 1) * (size_t) (g->feat_dim > 0 ? g->feat_dim : 1) * 4);
+    if (uses_cache) {
+        L.draw_keys = take((size_t) L.draw_hash_cap * 4);
+        L.draw_vals = take((size_t) L.draw_hash_cap * 4);
+        L.draw_node = take((size_t) L.draw_chunk * 4);
+        L.draw_slot = take((size_t) L.draw_chunk * 4);
+        L.edge_flags = take((size_t) (g->num_entries / 64 + 1) * 8);
+    }
     L.total = off;
     *out = L;
     return true;
@@ -168,6 +182,8 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
     c->config = *config;
     c->lay = L;
     c->ws = static_cast<char*>(workspace);
+    c->shared_ws = c->ws;
+    c->root = c;
     c->d_state = ws_ptr<DeviceState>(c, L.state);
     c->uses_cache = config_uses_cache(config);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -187,6 +203,8 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
     e = hipGetDeviceProperties(&prop, dev);
     if (e != hipSuccess) return bail(GNS_EHIP, "hipGetDeviceProperties", e);
     c->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    // the flag kernel may keep the whole cache bitmap in LDS (one 1024-thread block per CU)
+    c->lds_bitmap_limit = prop.sharedMemPerBlock > 1024 ? prop.sharedMemPerBlock - 1024 : 0;
     e = hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(DeviceState), hipHostMallocDefault);
     if (e != hipSuccess) { c->h_state = nullptr; return bail(GNS_EHIP, "hipHostMalloc", e); }
 
@@ -275,6 +293,45 @@ gns_status gns_profile_collect(gns_ctx* ctx, int32_t stage, double* total_ms, in
     return GNS_OK;
 }
 
+size_t gns_fork_workspace_bytes(const gns_ctx* parent)
+{
+    return parent ? parent->lay.shared_begin : 0;
+}
+
+gns_status gns_fork(gns_ctx* parent, void* workspace, size_t workspace_bytes, void* hip_stream, gns_ctx** out_child)
+{
+    if (!parent || !out_child) return GNS_EINVAL;
+    *out_child = nullptr;
+    gns_ctx* root = parent->root;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return ctx_fail(parent, GNS_EINVAL, "workspace must be a 256-byte aligned device pointer");
+    if (workspace_bytes < root->lay.shared_begin) return ctx_fail(parent, GNS_ECAPACITY, "fork workspace too small");
+    gns_ctx* c = new (std::nothrow) gns_ctx;
+    if (!c) return ctx_fail(parent, GNS_ENOMEM, "host allocation failed");
+    memcpy(c, root, sizeof(*c));
+    c->ws = static_cast<char*>(workspace);
+    c->shared_ws = root->ws;
+    c->root = root;
+    c->d_state = ws_ptr<DeviceState>(c, c->lay.state);
+    c->h_state = nullptr;
+    c->prof = nullptr;
+    c->prof_capacity = c->prof_count = 0;
+    c->prof_mask = 0;
+    c->err[0] = 0;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(DeviceState), hipHostMallocDefault);
+    if (e == hipSuccess) e = launch_fill_u32(reinterpret_cast<uint32_t*>(c->d_state), (sizeof(DeviceState) + 64) / 4, 0u, s);
+    if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, c->lay.mark_bitmap), (size_t) c->lay.words, 0ull, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) {
+        if (c->h_state) (void) hipHostFree(c->h_state);
+        delete c;
+        return ctx_fail(parent, GNS_EHIP, "fork init", e);
+    }
+    *out_child = c;
+    return GNS_OK;
+}
+
 gns_status gns_destroy(gns_ctx* ctx)
 {
     if (!ctx) return GNS_OK;
@@ -288,6 +345,7 @@ gns_status gns_sample_cache(gns_ctx* ctx, uint64_t seed, uint64_t epoch, void* h
 {
     if (!ctx) return GNS_EINVAL;
     if (!ctx->uses_cache) return ctx_fail(ctx, GNS_ESTATE, "no layer of this config uses the cache");
+    if (ctx->root != ctx) return ctx_fail(ctx, GNS_EINVAL, "draw the cache on the context made by gns_create, not on a fork");
     if (epoch >> 32) return ctx_fail(ctx, GNS_EINVAL, "epoch must be < 2^32");
     return run_sample_cache(ctx, seed, epoch, static_cast<hipStream_t>(hip_stream));
 }
@@ -296,22 +354,22 @@ gns_status gns_cache_view(gns_ctx* ctx, const int32_t** cache_nodes, int64_t* ca
                           int64_t* num_draws)
 {
     if (!ctx) return GNS_EINVAL;
-    if (!ctx->uses_cache || !ctx->cache_valid) return ctx_fail(ctx, GNS_ESTATE, "no cache has been drawn");
+    if (!ctx->uses_cache || !ctx->root->cache_valid) return ctx_fail(ctx, GNS_ESTATE, "no cache has been drawn");
     if (cache_nodes) *cache_nodes = ws_ptr<int32_t>(ctx, ctx->lay.cache_nodes);
     if (cache_size) *cache_size = ctx->config.cache_size;
     if (bitmap) *bitmap = ws_ptr<uint64_t>(ctx, ctx->lay.cache_bitmap);
-    if (num_draws) *num_draws = ctx->cache_draws;
+    if (num_draws) *num_draws = ctx->root->cache_draws;
     return GNS_OK;
 }
 
-gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
-                             gns_block* blocks, void* hip_stream)
+gns_status gns_sample_blocks_async(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
+                                   gns_block* blocks, void* hip_stream)
 {
     if (!ctx) return GNS_EINVAL;
     gns_ctx* c = ctx;
     if (!seeds_dev || !blocks) return ctx_fail(c, GNS_EINVAL, "null seeds or blocks");
     if (num_seeds < 1 || num_seeds > c->config.max_seeds) return ctx_fail(c, GNS_EINVAL, "num_seeds out of range");
-    if (c->uses_cache && !c->cache_valid) return ctx_fail(c, GNS_ESTATE, "gns_sample_cache must run before gns_sample_blocks");
+    if (c->uses_cache && !c->root->cache_valid) return ctx_fail(c, GNS_ESTATE, "gns_sample_cache must run before gns_sample_blocks");
     const Layout& L = c->lay;
     const int nl = c->config.num_layers;
     for (int i = 0; i < nl; ++i) {
@@ -342,9 +400,23 @@ gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_d
         dst = blocks[i].src_nodes;
     }
     e = hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s);
-    if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample_blocks readback", e);
     for (int i = 0; i < nl; ++i) {
+        blocks[i].num_dst = GNS_DEVICE_COUNTS(i);
+        blocks[i].num_src = -1;
+        blocks[i].num_edges = -1;
+    }
+    return GNS_OK;
+}
+
+gns_status gns_sample_blocks_wait(gns_ctx* ctx, gns_block* blocks, void* hip_stream)
+{
+    if (!ctx) return GNS_EINVAL;
+    gns_ctx* c = ctx;
+    if (!blocks) return ctx_fail(c, GNS_EINVAL, "null blocks");
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample_blocks wait", e);
+    for (int i = 0; i < c->config.num_layers; ++i) {
         blocks[i].num_dst = c->h_state->num_dst[i];
         blocks[i].num_src = c->h_state->num_dst[i + 1];
         blocks[i].num_edges = c->h_state->num_edges[i];
@@ -353,12 +425,19 @@ gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_d
     return GNS_OK;
 }
 
+gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
+                             gns_block* blocks, void* hip_stream)
+{
+    const gns_status st = gns_sample_blocks_async(ctx, seed, seeds_dev, num_seeds, blocks, hip_stream);
+    if (st != GNS_OK) return st;
+    return gns_sample_blocks_wait(ctx, blocks, hip_stream);
+}
+
 gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t num_nodes, float* out_dev,
                                void* hip_stream)
 {
     if (!ctx) return GNS_EINVAL;
     if (ctx->graph.feat_dim <= 0) return ctx_fail(ctx, GNS_ESTATE, "the graph was created without features");
-    if (num_nodes < 0) return ctx_fail(ctx, GNS_EINVAL, "num_nodes must be >= 0");
     if (num_nodes == 0) return GNS_OK;
     if (!nodes_dev || !out_dev) return ctx_fail(ctx, GNS_EINVAL, "null nodes or output");
     StageTimer t(ctx, GNS_STAGE_GATHER, static_cast<hipStream_t>(hip_stream));
@@ -373,8 +452,11 @@ gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_sr
     if (!ctx) return GNS_EINVAL;
     if (!block || !x_src_dev || !out_dev) return ctx_fail(ctx, GNS_EINVAL, "null block, input or output");
     if (feat_dim < 1) return ctx_fail(ctx, GNS_EINVAL, "feat_dim must be >= 1");
-    if (block->num_dst < 0 || block->num_src < block->num_dst || block->num_edges < 0)
+    if (block->num_dst < 0) {
+        if (-1 - block->num_dst >= ctx->config.num_layers) return ctx_fail(ctx, GNS_EINVAL, "bad device-count placeholder");
+    } else if (block->num_src < block->num_dst || block->num_edges < 0) {
         return ctx_fail(ctx, GNS_EINVAL, "block counts are inconsistent");
+    }
     if (!block->indptr || !block->indices || !block->weights) return ctx_fail(ctx, GNS_EINVAL, "block has a null buffer");
     StageTimer t(ctx, GNS_STAGE_AGGREGATE, static_cast<hipStream_t>(hip_stream));
     hipError_t e = launch_aggregate(ctx, block, x_src_dev, feat_dim, out_dev, static_cast<hipStream_t>(hip_stream));

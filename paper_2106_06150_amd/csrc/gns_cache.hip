@@ -240,21 +240,6 @@ __global__ void __launch_bounds__(kBlock) k_cache_index_phase3(IndexArgs a)
     }
 }
 
-// Section 3.4: p_u = deg(u)/nnz, p^C_u = 1 - (1 - p_u)^|C|; the table keeps 1/p^C_u
-// per cache slot in fp64 (expm1/log1p keep the digits of tiny p_u).
-template <typename OffT>
-__global__ void __launch_bounds__(kBlock) k_cache_inv_pc(const void* indptr, double nnz, int64_t cache_size,
-                                                         const int32_t* cache_nodes, double* inv_pc)
-{
-    const int64_t slot = (int64_t) blockIdx.x * blockDim.x + threadIdx.x;
-    if (slot >= cache_size) return;
-    const int64_t u = cache_nodes[slot];
-    const double deg = (double) (load_off<OffT>(indptr, u + 1) - load_off<OffT>(indptr, u));
-    const double p = deg / nnz;
-    const double pc = (p >= 1.0) ? 1.0 : -expm1((double) cache_size * log1p(-p));
-    inv_pc[slot] = 1.0 / pc;
-}
-
 // ---------------------------------------------------------------------------
 static gns_status fail(gns_ctx* c, gns_status st, const char* what, hipError_t e)
 {
@@ -342,11 +327,6 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
     hipLaunchKernelGGL(k_cache_index_phase1, dim3((unsigned) x.tiles), dim3(kBlock), 0, s, x);
     hipLaunchKernelGGL(k_cache_index_phase2, dim3(1), dim3(kBlock), 0, s, x);
     hipLaunchKernelGGL(k_cache_index_phase3, dim3((unsigned) x.tiles), dim3(kBlock), 0, s, x);
-    const unsigned pc_blocks = (unsigned) ((C + kBlock - 1) / kBlock);
-    if (i64) hipLaunchKernelGGL((k_cache_inv_pc<int64_t>), dim3(pc_blocks), dim3(kBlock), 0, s, c->graph.indptr,
-                                (double) c->graph.num_entries, C, x.cache_nodes, ws_ptr<double>(c, L.cache_inv_pc));
-    else     hipLaunchKernelGGL((k_cache_inv_pc<int32_t>), dim3(pc_blocks), dim3(kBlock), 0, s, c->graph.indptr,
-                                (double) c->graph.num_entries, C, x.cache_nodes, ws_ptr<double>(c, L.cache_inv_pc));
     GNS_HIP_TRY(hipGetLastError(), "cache index launch");
 
     if (c->graph.feat_dim > 0) {

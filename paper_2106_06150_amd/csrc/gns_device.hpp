@@ -9,6 +9,7 @@ constexpr int kWave = 64;
 constexpr int kBlock = 256;                 // threads per block for the scan-style kernels
 constexpr int kItems = 8;                   // items per thread in a scan tile
 constexpr int kTile = kBlock * kItems;      // 2048 items per scan tile
+constexpr int kMarkTile = kBlock;           // frontier mark bitmap: one 64-bit word per thread
 
 constexpr uint32_t kTagCache = 0x43414348u;     // 'CACH'
 constexpr uint32_t kTagNeighbor = 0x4E424853u;  // 'NBHS'

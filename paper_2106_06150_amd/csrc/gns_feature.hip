@@ -11,6 +11,7 @@ namespace gns {
 struct GatherArgs {
     const int32_t* nodes;
     int32_t num_nodes;
+    const int32_t* num_nodes_dev;   // if not null the count is read here (num_nodes is then the worst case)
     int64_t n;
     int32_t feat_dim;
     float* out;
@@ -30,7 +31,8 @@ __global__ void __launch_bounds__(kBlock) k_gather(GatherArgs a)
     const int64_t group = (int64_t) blockIdx.x * groups_per_block + threadIdx.x / kLanes;
     const int64_t num_groups = (int64_t) gridDim.x * groups_per_block;
     const int64_t F = a.feat_dim;
-    for (int64_t row = group; row < a.num_nodes; row += num_groups) {
+    const int64_t count = a.num_nodes_dev ? (int64_t) *a.num_nodes_dev : (int64_t) a.num_nodes;
+    for (int64_t row = group; row < count; row += num_groups) {
         const int32_t u = a.nodes[row];
         const bool valid = u >= 0 && (int64_t) u < a.n;
         const float* src = nullptr;
@@ -77,11 +79,16 @@ hipError_t launch_gather(gns_ctx* c, const int32_t* nodes, int32_t num_nodes, fl
     const Layout& L = c->lay;
     GatherArgs a;
     a.nodes = nodes;
+    a.num_nodes_dev = nullptr;
+    if (num_nodes < 0) {            // input nodes of the last sampled batch, counted on the device
+        a.num_nodes_dev = &c->d_state->num_dst[c->config.num_layers];
+        num_nodes = (int32_t) L.rows[c->config.num_layers];
+    }
     a.num_nodes = num_nodes;
     a.n = c->graph.num_nodes;
     a.feat_dim = c->graph.feat_dim;
     a.out = out;
-    a.use_cache = (c->uses_cache && c->cache_valid) ? 1 : 0;
+    a.use_cache = (c->uses_cache && c->root->cache_valid) ? 1 : 0;
     a.cache_bitmap = ws_ptr<uint64_t>(c, L.cache_bitmap);
     a.cache_prefix = ws_ptr<int32_t>(c, L.cache_prefix);
     a.cache_feat = ws_ptr<float>(c, L.cache_feat);
@@ -107,7 +114,7 @@ struct AggArgs {
     const float* x_src;
     float* out;
     int32_t num_dst;
-    int32_t num_src;
+    const int32_t* num_dst_dev;     // if not null the row count is read here
     int32_t feat_dim;
 };
 
@@ -119,7 +126,8 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggArgs a)
     const int64_t group = (int64_t) blockIdx.x * groups_per_block + threadIdx.x / kLanes;
     const int64_t num_groups = (int64_t) gridDim.x * groups_per_block;
     const int64_t F = a.feat_dim;
-    for (int64_t row = group; row < a.num_dst; row += num_groups) {
+    const int64_t count = a.num_dst_dev ? (int64_t) *a.num_dst_dev : (int64_t) a.num_dst;
+    for (int64_t row = group; row < count; row += num_groups) {
         const int32_t b = a.indptr[row], e = a.indptr[row + 1];
         const float n_v = (float) (e - b);
         if (kVec) {
@@ -167,20 +175,26 @@ hipError_t launch_aggregate(gns_ctx* c, const gns_block* blk, const float* x_src
 {
     if (blk->num_dst == 0 || feat_dim == 0) return hipSuccess;
     AggArgs a;
+    int32_t rows = blk->num_dst;
+    a.num_dst_dev = nullptr;
+    if (rows < 0) {                 // GNS_DEVICE_COUNTS(layer): rows counted on the device
+        const int layer = -1 - rows;
+        a.num_dst_dev = &c->d_state->num_dst[layer];
+        rows = (int32_t) c->lay.rows[layer];
+    }
     a.indptr = blk->indptr;
     a.indices = blk->indices;
     a.weights = blk->weights;
     a.x_src = x_src;
     a.out = out;
-    a.num_dst = blk->num_dst;
-    a.num_src = blk->num_src;
+    a.num_dst = rows;
     a.feat_dim = feat_dim;
     const int64_t F = feat_dim;
     const bool vec = (F % 4 == 0) && ((reinterpret_cast<uintptr_t>(x_src) & 15u) == 0) &&
                      ((reinterpret_cast<uintptr_t>(out) & 15u) == 0);
     const int lanes = lanes_for(vec ? F / 4 : F);
     const int64_t groups_per_block = kBlock / lanes;
-    int64_t blocks = (blk->num_dst + groups_per_block - 1) / groups_per_block;
+    int64_t blocks = (rows + groups_per_block - 1) / groups_per_block;
     const int64_t cap = (int64_t) c->num_cus * 16;
     if (blocks > cap) blocks = cap;
     if (vec) aggregate_dispatch<true>(lanes, (unsigned) blocks, s, a);

@@ -4,15 +4,13 @@
 // The sampler leaves, per dst row, up to k global neighbor ids at a fixed
 // stride and has set one bit per sampled id in a node-indexed mark bitmap.
 // Here:
-//   phase 1  per-tile sums of the row counts, and of the mark bitmap's
-//            population after removing ids that already have a local id
-//            (the dst nodes, found through the batch's hash map)
-//   phase 2  one block scans both arrays of tile sums and publishes the
-//            layer's edge and src counts
-//   phase 3  tiles are scanned again with their offsets: indptr is written,
-//            the marked ids are emitted in ascending order behind the dst
-//            prefix, inserted into the hash map with their local ids, and the
-//            bitmap words are cleared for the next layer
+//   phase 1  per-tile sums of the row counts and of the mark bitmap's
+//            population (the sampler marks only ids without a local id)
+//   phase 3  every block adds up the sums of the tiles before its own, scans
+//            its tile and writes: indptr for row tiles; for bitmap tiles the
+//            marked ids in ascending order behind the dst prefix, one thread
+//            per new id, each inserted into the hash map with its local id;
+//            the bitmap words are cleared for the next layer
 //   relabel  every sampled edge looks its neighbor's local id up and is
 //            compacted to its CSR position
 // Sorted order comes from walking the bitmap, so the result does not depend on
@@ -65,7 +63,7 @@ __global__ void k_batch_clear(unsigned long long* slots, size_t cap, DeviceState
     const size_t stride = (size_t) gridDim.x * blockDim.x;
     if (i == 0) {
         st->num_dst[0] = num_seeds;
-        for (int l = 0; l < GNS_MAX_LAYERS; ++l) { st->queue[l] = 0; st->num_edges[l] = 0; st->num_dst[l + 1] = 0; }
+        for (int l = 0; l < GNS_MAX_LAYERS; ++l) { st->num_edges[l] = 0; st->num_dst[l + 1] = 0; }
         st->bad_seed = 0;
     }
     for (; i < cap; i += stride) slots[i] = kEmptySlot;
@@ -108,9 +106,9 @@ struct FinishArgs {
     unsigned long long* slots;
     uint32_t hmask, hshift;
     int32_t* sums_rows;            // [row_tiles + 1]
-    int32_t* sums_words;           // [word_tiles + 1]
+    int32_t* sums_marks;           // [mark_tiles + 1]
     int32_t row_tiles_max;         // grid split point: blocks [0, row_tiles_max) work on rows
-    int32_t word_tiles;
+    int32_t mark_tiles;            // tiles of kMarkTile bitmap words
     int32_t* indptr;               // block outputs
     int32_t* indices;
     float* weights;
@@ -134,68 +132,34 @@ __global__ void __launch_bounds__(kBlock) k_finish_phase1(FinishArgs a)
         if (threadIdx.x == 0) a.sums_rows[blockIdx.x] = sum;
     } else {
         const int32_t tile = (int32_t) blockIdx.x - a.row_tiles_max;
-        const int64_t base = (int64_t) tile * kTile;
-        int32_t sum = 0;
-#pragma unroll
-        for (int i = 0; i < kItems; ++i) {
-            const int64_t w = base + (int64_t) i * kBlock + threadIdx.x;
-            if (w < a.words) {
-                uint64_t word = a.mark[w];
-                if (word) {
-                    // drop ids that already own a local id (they are dst nodes of this layer)
-                    uint64_t rest = word;
-                    while (rest) {
-                        const int bit = __builtin_ctzll(rest);
-                        rest &= rest - 1;
-                        const uint32_t node = (uint32_t) (w * 64 + bit);
-                        if (hash_lookup(a.slots, a.hmask, a.hshift, node) >= 0) word &= ~(1ull << bit);
-                    }
-                    a.mark[w] = word;
-                    sum += __popcll(word);
-                }
-            }
-        }
+        const int64_t w = (int64_t) tile * kMarkTile + threadIdx.x;
+        int32_t sum = (w < a.words) ? __popcll(a.mark[w]) : 0;
         sum = block_sum(sum, smem);
-        if (threadIdx.x == 0) a.sums_words[tile] = sum;
+        if (threadIdx.x == 0) a.sums_marks[tile] = sum;
     }
 }
 
-// exclusive scan of vals[0..count) in place by one block; returns the total in every thread
-__device__ int32_t scan_in_place(int32_t* vals, int32_t count, int32_t* smem)
+// sum of vals[0..count) by the whole block
+__device__ __forceinline__ int32_t block_sum_array(const int32_t* vals, int32_t count, int32_t* smem)
 {
-    int32_t carry = 0;
-    for (int32_t base = 0; base < count; base += kBlock) {
-        const int32_t i = base + (int32_t) threadIdx.x;
-        const int32_t v = (i < count) ? vals[i] : 0;
-        int32_t total;
-        const int32_t ex = block_exclusive_scan(v, smem, &total);
-        if (i < count) vals[i] = carry + ex;
-        carry += total;
-    }
-    return carry;
+    int32_t v = 0;
+    for (int32_t t = (int32_t) threadIdx.x; t < count; t += kBlock) v += vals[t];
+    return block_sum(v, smem);
 }
 
-__global__ void __launch_bounds__(kBlock) k_finish_phase2(FinishArgs a)
-{
-    __shared__ int32_t smem[kBlock / kWave + 1];
-    const int32_t R = a.st->num_dst[a.layer_index];
-    const int32_t row_tiles = (R + kTile - 1) / kTile;
-    const int32_t edges = scan_in_place(a.sums_rows, row_tiles, smem);
-    const int32_t fresh = scan_in_place(a.sums_words, a.word_tiles, smem);
-    if (threadIdx.x == 0) {
-        a.st->num_edges[a.layer_index] = edges;
-        a.st->num_dst[a.layer_index + 1] = R + fresh;
-        a.indptr[R] = edges;
-    }
-}
-
+// Phase 3 needs each tile's offset = the sum of the earlier tiles' sums.  Every block adds
+// those up itself (at most a few thousand values), which saves a single-block scan kernel.
 __global__ void __launch_bounds__(kBlock) k_finish_phase3(FinishArgs a)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
+    __shared__ int32_t s_off[kMarkTile + 1];
+    __shared__ uint64_t s_word[kMarkTile];
     const int32_t R = a.st->num_dst[a.layer_index];
+    const int32_t row_tiles = (R + kTile - 1) / kTile;
     if ((int32_t) blockIdx.x < a.row_tiles_max) {
         const int64_t base = (int64_t) blockIdx.x * kTile;
         if (base >= R) return;
+        const int32_t before = block_sum_array(a.sums_rows, (int32_t) blockIdx.x, smem);
         // blocked arrangement: thread t owns rows base + t*kItems .. +kItems
         int32_t c[kItems];
         int32_t sum = 0;
@@ -206,7 +170,11 @@ __global__ void __launch_bounds__(kBlock) k_finish_phase3(FinishArgs a)
             sum += c[i];
         }
         int32_t total;
-        int32_t off = a.sums_rows[blockIdx.x] + block_exclusive_scan(sum, smem, &total);
+        int32_t off = before + block_exclusive_scan(sum, smem, &total);
+        if ((int32_t) blockIdx.x == row_tiles - 1 && threadIdx.x == 0) {
+            a.st->num_edges[a.layer_index] = before + total;
+            a.indptr[R] = before + total;
+        }
 #pragma unroll
         for (int i = 0; i < kItems; ++i) {
             if (r0 + i < R) {
@@ -217,32 +185,32 @@ __global__ void __launch_bounds__(kBlock) k_finish_phase3(FinishArgs a)
         }
     } else {
         const int32_t tile = (int32_t) blockIdx.x - a.row_tiles_max;
-        const int64_t base = (int64_t) tile * kTile;
-        uint64_t word[kItems];
-        int32_t sum = 0;
-        const int64_t w0 = base + (int64_t) threadIdx.x * kItems;
-#pragma unroll
-        for (int i = 0; i < kItems; ++i) {
-            word[i] = (w0 + i < a.words) ? a.mark[w0 + i] : 0ull;
-            sum += __popcll(word[i]);
-        }
+        const int64_t base = (int64_t) tile * kMarkTile;
+        const int32_t before = block_sum_array(a.sums_marks, tile, smem);
+        const int32_t here = a.sums_marks[tile];
+        if (tile == a.mark_tiles - 1 && threadIdx.x == 0) a.st->num_dst[a.layer_index + 1] = R + before + here;
+        if (here == 0) return;
+        // one bitmap word per thread; exclusive offsets of the tile's words into LDS
+        const int64_t w = base + threadIdx.x;
+        const uint64_t word = (w < a.words) ? a.mark[w] : 0ull;
         int32_t total;
-        int32_t pos = R + a.sums_words[tile] + block_exclusive_scan(sum, smem, &total);
-        if (total == 0) return;
-#pragma unroll
-        for (int i = 0; i < kItems; ++i) {
-            uint64_t rest = word[i];
-            if (rest) {
-                while (rest) {
-                    const int bit = __builtin_ctzll(rest);
-                    rest &= rest - 1;
-                    const uint32_t node = (uint32_t) ((w0 + i) * 64 + bit);
-                    a.src_nodes[pos] = (int32_t) node;
-                    hash_insert(a.slots, a.hmask, a.hshift, node, (uint32_t) pos);
-                    ++pos;
-                }
-                a.mark[w0 + i] = 0ull;
+        s_off[threadIdx.x] = block_exclusive_scan(__popcll(word), smem, &total);
+        s_word[threadIdx.x] = word;
+        if (threadIdx.x == 0) s_off[kMarkTile] = total;
+        if (word) a.mark[w] = 0ull;                                  // ready for the next layer
+        __syncthreads();
+        // one thread per new node: locate its word (last word whose offset is <= j), then its bit
+        for (int32_t j = (int32_t) threadIdx.x; j < total; j += kBlock) {
+            int32_t lo = 0, hi = kMarkTile;                          // answer in [lo, hi)
+            while (hi - lo > 1) {
+                const int32_t mid = (lo + hi) >> 1;
+                if (s_off[mid] <= j) lo = mid; else hi = mid;
             }
+            const int bit = select_bit64(s_word[lo], j - s_off[lo]);
+            const uint32_t node = (uint32_t) ((base + lo) * 64 + bit);
+            const int32_t pos = R + before + j;
+            a.src_nodes[pos] = (int32_t) node;
+            hash_insert(a.slots, a.hmask, a.hshift, node, (uint32_t) pos);
         }
     }
 }
@@ -282,17 +250,16 @@ hipError_t launch_finish_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
     a.hmask = L.hash_cap - 1;
     a.hshift = 32u - (uint32_t) __builtin_ctz(L.hash_cap);
     a.sums_rows = ws_ptr<int32_t>(c, L.sums_rows);
-    a.sums_words = ws_ptr<int32_t>(c, L.sums_words);
+    a.sums_marks = ws_ptr<int32_t>(c, L.sums_marks);
     a.row_tiles_max = (int32_t) ((L.rows[layer_index] + kTile - 1) / kTile);
-    a.word_tiles = (int32_t) L.word_tiles;
+    a.mark_tiles = (int32_t) L.mark_tiles;
     a.indptr = blk->indptr;
     a.indices = blk->indices;
     a.weights = blk->weights;
     a.src_nodes = blk->src_nodes;
 
-    const unsigned grid = (unsigned) (a.row_tiles_max + a.word_tiles);
+    const unsigned grid = (unsigned) (a.row_tiles_max + a.mark_tiles);
     hipLaunchKernelGGL(k_finish_phase1, dim3(grid), dim3(kBlock), 0, s, a);
-    hipLaunchKernelGGL(k_finish_phase2, dim3(1), dim3(kBlock), 0, s, a);
     hipLaunchKernelGGL(k_finish_phase3, dim3(grid), dim3(kBlock), 0, s, a);
     const int64_t max_slots = L.rows[layer_index] * (int64_t) a.fanout;
     int64_t rb = (max_slots + kBlock - 1) / kBlock;

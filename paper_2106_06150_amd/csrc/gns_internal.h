@@ -14,29 +14,33 @@ namespace gns {
 struct DeviceState {
     int32_t num_dst[GNS_MAX_LAYERS + 1];  // rows of layer index i (num_dst[i+1] = num_src of layer i)
     int32_t num_edges[GNS_MAX_LAYERS];
-    int32_t queue[GNS_MAX_LAYERS];        // row work-queue heads of the per-row sampler
     int32_t bad_seed;                     // set if a seed was out of range or repeated
     int32_t chunk_distinct;               // cache draw: first occurrences found in the current chunk
-    int32_t pad0;
+    int32_t plan_chunks;                  // CACHE_ONLY sampler: aligned chunks in the current work list
     unsigned long long cut_draw;          // cache draw: stream index of the draw that completed the cache
 };
 
 struct Layout {
     // persistent cache structures
-    size_t cache_bitmap, cache_prefix, cache_nodes, cache_inv_pc, cache_feat;
+    size_t cache_bitmap, cache_prefix, cache_nodes, cache_feat;
     // cache-draw scratch
     size_t draw_keys, draw_vals, draw_node, draw_slot;
     // frontier structures
     size_t mark_bitmap, hash_slots;
     // per-layer sampler scratch (fixed stride fanout)
     size_t s_nbr, s_w, s_cnt;
+    // CACHE_ONLY sampler: per-row chunk counts, chunk work list, CSR-aligned membership flags
+    size_t plan_cnt, plan_g0, plan_desc, edge_flags;
+    int64_t max_chunks;
     // scan partials
-    size_t sums_rows, sums_words;
+    size_t sums_rows, sums_words, sums_marks, sums_plan;
     size_t state;
+    size_t shared_begin;      // sections at or past this offset are shared with forked contexts
     size_t total;
     // sizes
     int64_t words;            // ceil(n / 64)
     int64_t word_tiles;       // ceil(words / kTile)
+    int64_t mark_tiles;       // ceil(words / kMarkTile)
     int64_t row_tiles;        // ceil(max rows / kTile)
     int64_t draw_chunk;       // stream draws processed per round of the cache draw
     int64_t draw_tiles;
@@ -61,7 +65,9 @@ struct gns_ctx {
     gns_graph graph;
     gns_config config;
     gns::Layout lay;
-    char* ws;                        // device workspace base
+    char* ws;                        // device workspace base (per-batch scratch sections)
+    char* shared_ws;                 // base for the shared sections (the root context's workspace)
+    gns_ctx* root;                   // owner of the cache; this for a context made by gns_create
     gns::DeviceState* d_state;       // device
     gns::DeviceState* h_state;       // pinned host mirror
     bool uses_cache;
@@ -69,6 +75,7 @@ struct gns_ctx {
     int64_t cache_draws;
     int64_t nonzero_degree_nodes;
     int num_cus;
+    size_t lds_bitmap_limit;         // largest cache bitmap (bytes) the flag kernel stages in LDS
     // optional stage timing (benchmarks only)
     uint32_t prof_mask;
     int32_t prof_capacity;
@@ -80,7 +87,10 @@ struct gns_ctx {
 namespace gns {
 
 template <typename T>
-static inline T* ws_ptr(const gns_ctx* c, size_t off) { return reinterpret_cast<T*>(c->ws + off); }
+static inline T* ws_ptr(const gns_ctx* c, size_t off)
+{
+    return reinterpret_cast<T*>((off >= c->lay.shared_begin ? c->shared_ws : c->ws) + off);
+}
 
 bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char* err, size_t errlen);
 

@@ -13,8 +13,9 @@
 // integer arithmetic, so the sample does not depend on scheduling.
 //
 // Output per row r (fixed stride k): s_nbr[r*k + i], s_w[r*k + i] for
-// i < s_cnt[r], row_eligible[r]; every emitted id also sets its bit in the
-// node-indexed mark bitmap that the frontier stage turns into the src list.
+// i < s_cnt[r], row_eligible[r]; every emitted id that has no local id yet
+// (it is not a dst node of this layer) also sets its bit in the node-indexed
+// mark bitmap that the frontier stage turns into the src list.
 #include "gns_internal.h"
 #include "gns_device.hpp"
 
@@ -33,12 +34,22 @@ struct SampleArgs {
     const int32_t* dst_nodes;
     const uint64_t* cache_bitmap;
     const int32_t* cache_prefix;
-    const double* cache_inv_pc;
+    int64_t cache_size;
     int32_t* s_nbr;
     float* s_w;
     int32_t* s_cnt;
     int32_t* row_eligible;
     uint64_t* mark;
+    const unsigned long long* slots;   // batch hash map node -> local id (holds this layer's dst nodes)
+    uint32_t hmask, hshift;
+    // CACHE_ONLY: per-batch plan and the CSR-aligned membership flags
+    int64_t num_entries;
+    int32_t* plan_cnt;         // [rows] aligned 64-entry chunks touched by each dst row
+    int32_t* plan_g0;          // [rows] id of the first of them
+    int32_t* plan_sums;        // [row tiles + 1]
+    int32_t* plan_desc;        // [chunks] ids of the aligned chunks to flag
+    uint64_t* flags;           // [ceil(nnz / 64)] bit e & 63 of word e >> 6: entry e points into the cache
+    int64_t bitmap_words;
 };
 
 // Floyd's subset draw inside a group of G consecutive lanes (G a power of two
@@ -74,9 +85,11 @@ __device__ __forceinline__ void floyd_in_group(uint32_t m, int k, uint32_t key0,
     *pos = rank;
 }
 
-__device__ __forceinline__ void mark_node(uint64_t* mark, uint32_t u)
+// A sampled id becomes a new src node unless it already owns a local id.
+__device__ __forceinline__ void mark_if_new(const SampleArgs& a, uint32_t u)
 {
-    atomicOr(reinterpret_cast<unsigned long long*>(&mark[u >> 6]), 1ull << (u & 63u));
+    if (hash_lookup(a.slots, a.hmask, a.hshift, u) < 0)
+        atomicOr(reinterpret_cast<unsigned long long*>(&a.mark[u >> 6]), 1ull << (u & 63u));
 }
 
 // ---------------------------------------------------------------------------
@@ -118,7 +131,7 @@ __global__ void __launch_bounds__(kBlock) k_sample_uniform(SampleArgs a)
             const int32_t u = a.indices[start + val];
             a.s_nbr[row * k + pos] = u;
             a.s_w[row * k + pos] = 1.0f;
-            mark_node(a.mark, (uint32_t) u);
+            mark_if_new(a, (uint32_t) u);
         }
         if (live && s == 0) {
             a.s_cnt[row] = cnt;
@@ -128,164 +141,266 @@ __global__ void __launch_bounds__(kBlock) k_sample_uniform(SampleArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// CACHE_ONLY: one wave per row, rows handed out through an atomic queue.
-// The row is streamed in chunks of 64 entries (kUnroll chunks in flight); each
-// chunk's cache-membership ballot is kept in LDS together with the running
-// count, so that after the draw the chosen ranks are mapped back to CSR
-// positions without a second pass.  Rows longer than one LDS segment are
-// counted first and then resolved segment by segment.
-constexpr int kUnroll = 4;
-constexpr int kSegChunks = 256;                        // chunks (of 64 entries) per LDS segment
-constexpr int kSegEntries = kSegChunks * kWave;        // 16384 entries
-constexpr int kWavesPerBlock = kBlock / kWave;
-
-struct RowScan {
-    uint64_t* masks;      // LDS, [kSegChunks]
-    uint32_t* prefix;     // LDS, [kSegChunks] eligible entries before the chunk, within the segment
-};
-
-// Streams `len` entries starting at `idx`; returns the number of cached ones.
-// With kStore the chunk ballots and prefixes go to LDS.
-template <bool kStore>
-__device__ __forceinline__ uint32_t scan_segment(const int32_t* idx, int32_t len, const uint64_t* bitmap,
-                                                 const RowScan& rs)
-{
-    uint32_t running = 0;
-    for (int32_t base = 0; base < len; base += kUnroll * kWave) {
-        const int lane = opaque_lane_id();
-        int32_t u[kUnroll];
-        bool in[kUnroll];
-#pragma unroll
-        for (int i = 0; i < kUnroll; ++i) {
-            const int32_t e = base + i * kWave + lane;
-            in[i] = e < len;
-            u[i] = in[i] ? idx[e] : 0;
-        }
-        uint64_t ballots[kUnroll];
-#pragma unroll
-        for (int i = 0; i < kUnroll; ++i) {
-            const bool hit = in[i] && bitmap_test(bitmap, (uint32_t) u[i]);
-            ballots[i] = __ballot(hit);
-        }
-        // lane i (< kUnroll) records chunk i: its ballot and the count of eligible entries before it
-        uint64_t my_mask = ballots[0];
-        uint32_t my_prefix = running;
-        uint32_t acc = running;
-#pragma unroll
-        for (int i = 0; i < kUnroll; ++i) {
-            if (lane == i) { my_mask = ballots[i]; my_prefix = acc; }
-            acc += (uint32_t) __popcll(ballots[i]);
-        }
-        if (kStore) {
-            if (lane < kUnroll && base + lane * kWave < len) {
-                rs.masks[(base >> 6) + lane] = my_mask;
-                rs.prefix[(base >> 6) + lane] = my_prefix;
-            }
-        }
-        running = acc;
-    }
-    return running;
-}
-
-// Next row of the work queue, the same value in every lane.  Lane 0 performs the atomic and
-// the result is broadcast through a scalar register.  The lane test uses an opaque id so that
-// the branch stays inside the caller's loop (see opaque()).
-__device__ __forceinline__ int32_t claim_row(int32_t* queue)
-{
-    int32_t v = 0;
-    if (opaque_lane_id() == 0) v = atomicAdd(queue, 1);
-    return __builtin_amdgcn_readfirstlane(v);
-}
+// CACHE_ONLY in two balanced phases.
+//
+// The CSR entry array is cut into aligned chunks of 64 entries; flags[g] holds, for chunk g,
+// one bit per entry: "this neighbor is in the cache".
+//   plan     per dst row, the aligned chunks its segment touches; prefix sum; the chunk ids
+//            are written out as a flat work list (k_plan_count, k_plan_expand)
+//   flag     one wave step = a few chunks of the list: coalesced 256-byte index loads, one
+//            cache-bitmap test per entry, a ballot per chunk stored as one 64-bit word.  Every
+//            chunk costs the same, so the stream is balanced whatever the degree skew
+//            (k_flag_chunks; the bitmap is staged in LDS when it fits)
+//   select   per dst row (a group of lanes): read the row's flag words, trim the two boundary
+//            words to the row, count N_C(v), draw, map the chosen ranks back to CSR positions,
+//            emit ids and Section 3.4 weights (k_select_rows)
+// A chunk shared by two dst rows is flagged twice with the same value.
 
 template <typename OffT>
-__global__ void __launch_bounds__(kBlock) k_sample_cache_only(SampleArgs a)
+__device__ __forceinline__ void row_extent(const SampleArgs& a, int32_t vi, int64_t* start, int64_t* end)
 {
-    __shared__ uint64_t lds_masks[kWavesPerBlock][kSegChunks];
-    __shared__ uint32_t lds_prefix[kWavesPerBlock][kSegChunks];
-    const int wave = (int) (threadIdx.x >> 6);
-    RowScan rs{lds_masks[wave], lds_prefix[wave]};
+    *start = 0;
+    *end = 0;
+    if (vi >= 0 && (int64_t) vi < a.num_nodes) {
+        *start = load_off<OffT>(a.indptr, vi);
+        *end = load_off<OffT>(a.indptr, (int64_t) vi + 1);
+    }
+}
+
+__device__ __forceinline__ int32_t chunks_touched(int64_t start, int64_t end)
+{
+    return end > start ? (int32_t) (((end - 1) >> 6) - (start >> 6) + 1) : 0;
+}
+
+// Plan tiles are kPlanTile rows (one row per thread): many small blocks keep the expansion parallel.
+constexpr int kPlanTile = kBlock;
+
+template <typename OffT>
+__global__ void __launch_bounds__(kBlock) k_plan_count(SampleArgs a)
+{
+    __shared__ int32_t smem[kBlock / kWave + 1];
+    const int32_t R = a.st->num_dst[a.layer_index];
+    const int64_t r = (int64_t) blockIdx.x * kPlanTile + threadIdx.x;
+    if ((int64_t) blockIdx.x * kPlanTile >= R) return;
+    int32_t c = 0;
+    if (r < R) {
+        int64_t start, end;
+        row_extent<OffT>(a, a.dst_nodes[r], &start, &end);
+        c = chunks_touched(start, end);
+        a.plan_cnt[r] = c;
+        a.plan_g0[r] = (int32_t) (start >> 6);
+    }
+    const int32_t sum = block_sum(c, smem);
+    if (threadIdx.x == 0) a.plan_sums[blockIdx.x] = sum;
+}
+
+__global__ void __launch_bounds__(kBlock) k_plan_expand(SampleArgs a)
+{
+    __shared__ int32_t smem[kBlock / kWave + 1];
+    __shared__ int32_t s_off[kPlanTile + 1];
+    __shared__ int32_t s_g0[kPlanTile];
+    const int32_t R = a.st->num_dst[a.layer_index];
+    const int64_t base = (int64_t) blockIdx.x * kPlanTile;
+    if (base >= R) return;
+    // chunks of all earlier tiles
+    int32_t before = 0;
+    for (int32_t t = (int32_t) threadIdx.x; t < (int32_t) blockIdx.x; t += kBlock) before += a.plan_sums[t];
+    before = block_sum(before, smem);
+    const int64_t r = base + threadIdx.x;
+    const int32_t c = (r < R) ? a.plan_cnt[r] : 0;
+    s_g0[threadIdx.x] = (r < R) ? a.plan_g0[r] : 0;
+    int32_t total;
+    s_off[threadIdx.x] = block_exclusive_scan(c, smem, &total);
+    if (threadIdx.x == 0) s_off[kPlanTile] = total;
+    const int32_t last_tile = (R - 1) / kPlanTile;
+    if ((int32_t) blockIdx.x == last_tile && threadIdx.x == 0) a.st->plan_chunks = before + total;
+    __syncthreads();
+    // one thread per work-list entry: its row is the last one whose offset is <= j
+    for (int32_t j = (int32_t) threadIdx.x; j < total; j += kBlock) {
+        int32_t lo = 0, hi = kPlanTile;
+        while (hi - lo > 1) {
+            const int32_t mid = (lo + hi) >> 1;
+            if (s_off[mid] <= j) lo = mid; else hi = mid;
+        }
+        a.plan_desc[before + j] = s_g0[lo] + (j - s_off[lo]);
+    }
+}
+
+constexpr int kFlagUnroll = 16;     // chunks a wave keeps in flight
+constexpr int kFlagBatch = 64;      // work-list entries a wave fetches at once (one per lane)
+
+// kLds: the cache bitmap is first copied into dynamic LDS (rounded up to 16 bytes).
+template <bool kLds>
+__global__ void k_flag_chunks(SampleArgs a, int use_plan, int64_t all_chunks)
+{
+    extern __shared__ uint4 lds_bitmap16[];
+    if (kLds) {
+        const uint4* src = reinterpret_cast<const uint4*>(a.cache_bitmap);
+        const int64_t n16 = (a.bitmap_words + 1) / 2;
+        constexpr int kFill = 4;
+        for (int64_t base = 0; base < n16; base += (int64_t) blockDim.x * kFill) {
+            uint4 v[kFill];
+#pragma unroll
+            for (int i = 0; i < kFill; ++i) {
+                const int64_t q = base + (int64_t) i * blockDim.x + threadIdx.x;
+                v[i] = src[q < n16 ? q : n16 - 1];
+            }
+#pragma unroll
+            for (int i = 0; i < kFill; ++i) {
+                const int64_t q = base + (int64_t) i * blockDim.x + threadIdx.x;
+                if (q < n16) lds_bitmap16[q] = v[i];
+            }
+        }
+        __syncthreads();
+    }
+    const uint32_t* lds32 = reinterpret_cast<const uint32_t*>(lds_bitmap16);
+    const int64_t Q = use_plan ? (int64_t) a.st->plan_chunks : all_chunks;
+    const int waves_per_block = (int) (blockDim.x >> 6);
+    const int64_t wave_global = (int64_t) blockIdx.x * waves_per_block +
+                                __builtin_amdgcn_readfirstlane((int) (threadIdx.x >> 6));
+    const int64_t num_waves = (int64_t) gridDim.x * waves_per_block;
+    for (int64_t c0 = wave_global * kFlagBatch; c0 < Q; c0 += num_waves * kFlagBatch) {
+        const int lane = opaque_lane_id();
+        // lane l holds the chunk id of work-list entry c0 + l
+        int32_t my_chunk = -1;
+        if (c0 + lane < Q) my_chunk = use_plan ? a.plan_desc[c0 + lane] : (int32_t) (c0 + lane);
+        for (int sub = 0; sub < kFlagBatch; sub += kFlagUnroll) {
+            if (c0 + sub >= Q) break;                               // scalar condition
+            int32_t u[kFlagUnroll];
+            bool in[kFlagUnroll];
+#pragma unroll
+            for (int i = 0; i < kFlagUnroll; ++i) {
+                const int64_t g = (int64_t) __builtin_amdgcn_readlane(my_chunk, sub + i);
+                const int64_t e = g * 64 + lane;
+                in[i] = g >= 0 && e < a.num_entries;
+                u[i] = a.indices[in[i] ? e : 0];                    // unconditional load, clamped address
+            }
+            uint64_t mine = 0;
+#pragma unroll
+            for (int i = 0; i < kFlagUnroll; ++i) {
+                bool hit;
+                if (kLds) hit = in[i] && ((lds32[(uint32_t) u[i] >> 5] >> ((uint32_t) u[i] & 31u)) & 1u);
+                else      hit = in[i] && bitmap_test(a.cache_bitmap, (uint32_t) u[i]);
+                const uint64_t ballot = __ballot(hit);
+                if (lane == sub + i) mine = ballot;
+            }
+            // lanes sub .. sub+kFlagUnroll-1 store the words of their chunks
+            if (lane >= sub && lane < sub + kFlagUnroll && my_chunk >= 0) a.flags[my_chunk] = mine;
+        }
+    }
+}
+
+// group-wide helpers for G consecutive lanes (G a power of two)
+template <int G>
+__device__ __forceinline__ int32_t group_inclusive_scan(int32_t v, int s)
+{
+#pragma unroll
+    for (int d = 1; d < G; d <<= 1) {
+        const int32_t up = __shfl_up(v, d, G);
+        if (s >= d) v += up;
+    }
+    return v;
+}
+
+template <typename OffT, int G>
+__global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a)
+{
     const int32_t R = a.st->num_dst[a.layer_index];
     const int k = a.fanout;
-
-    // Rows are dealt round-robin to the waves of the grid.  (A single atomic row counter was
-    // measured first: same-address atomics serialise at roughly 12 ns each, which alone cost
-    // 1 ms for 85K rows.)  Row index, node and row extent are wave-uniform scalars
-    // (readfirstlane): every loop below branches on scalar conditions and the wave stays
-    // converged around the ballots and the LDS exchange.
-    const int32_t wave_global = (int32_t) blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(wave);
-    const int32_t num_waves = (int32_t) gridDim.x * kWavesPerBlock;
-    for (int32_t row = wave_global; row < R; row += num_waves) {
+    constexpr int kRowsPerWave = kWave / G;
+    const int64_t wave_global = (int64_t) blockIdx.x * (kBlock / kWave) +
+                                __builtin_amdgcn_readfirstlane((int) (threadIdx.x >> 6));
+    const int64_t num_waves = (int64_t) gridDim.x * (kBlock / kWave);
+    for (int64_t row0 = wave_global * kRowsPerWave; row0 < R; row0 += num_waves * kRowsPerWave) {
         const int lane = opaque_lane_id();
-
-        const int32_t vi = __builtin_amdgcn_readfirstlane(a.dst_nodes[row]);
-        int64_t start = 0, deg = 0;
-        if (vi >= 0 && (int64_t) vi < a.num_nodes) {
-            const int64_t b = load_off<OffT>(a.indptr, vi);
-            const int64_t e = load_off<OffT>(a.indptr, (int64_t) vi + 1);
-            start = ((int64_t) __builtin_amdgcn_readfirstlane((int) (b >> 32)) << 32) |
-                    (uint32_t) __builtin_amdgcn_readfirstlane((int) (uint32_t) b);
-            deg = (int64_t) __builtin_amdgcn_readfirstlane((int) (e - b));
+        const int s = lane & (G - 1);
+        const int64_t row = row0 + (lane / G);
+        const bool live = row < R;
+        int32_t vi = -1;
+        int64_t start = 0, end = 0;
+        if (live) {
+            vi = a.dst_nodes[row];
+            row_extent<OffT>(a, vi, &start, &end);
         }
-        const int32_t* row_idx = a.indices + start;
-        const int64_t num_seg = (deg + kSegEntries - 1) / kSegEntries;
+        const int32_t nw = chunks_touched(start, end);       // flag words of this row
+        const int64_t g0 = start >> 6;
+        const uint64_t head_mask = ~0ull << (start & 63);
+        const int tail_bits = (int) (end & 63);
+        const uint64_t tail_mask = tail_bits ? ((1ull << tail_bits) - 1ull) : ~0ull;
 
-        uint32_t m = 0;                                        // N_C(v)
-        if (num_seg > 1) {
-            for (int64_t sg = 0; sg < num_seg; ++sg) {
-                const int64_t off = sg * kSegEntries;
-                const int32_t len = (int32_t) ((deg - off < kSegEntries) ? (deg - off) : kSegEntries);
-                m += scan_segment<false>(row_idx + off, len, a.cache_bitmap, rs);
+        // pass 1: N_C(v) = set bits of the row's flag words, trimmed to [start, end)
+        uint32_t m = 0;
+        uint64_t w_first = 0;
+        int32_t incl_first = 0;
+        for (int32_t it = 0; __any(it * G + s < nw); ++it) {
+            const int32_t j = it * G + s;
+            uint64_t w = 0;
+            if (j < nw) {
+                w = a.flags[g0 + j];
+                if (j == 0) w &= head_mask;
+                if (j == nw - 1) w &= tail_mask;
             }
+            const int32_t incl = group_inclusive_scan<G>(__popcll(w), s);
+            if (it == 0) { w_first = w; incl_first = incl; }
+            m += (uint32_t) __shfl(incl, G - 1, G);
         }
 
-        uint32_t val = 0;
-        int pos = 0;
-        int cnt = 0;
-        bool drawn = false;
-        uint32_t seen = 0;                                     // eligible entries in earlier segments
-        for (int64_t sg = 0; sg < num_seg; ++sg) {
-            const int64_t off = sg * kSegEntries;
-            const int32_t len = (int32_t) ((deg - off < kSegEntries) ? (deg - off) : kSegEntries);
-            const uint32_t here = scan_segment<true>(row_idx + off, len, a.cache_bitmap, rs);
-            if (num_seg == 1) m = here;
-            if (!drawn) {
-                drawn = true;
-                floyd_in_group<kWave>(m > (uint32_t) k ? m : (uint32_t) k + 1u, k, a.key0, a.key1, a.layer_number,
-                                      (uint32_t) vi, lane, &val, &pos);
-                cnt = (m > (uint32_t) k) ? k : (int) m;
-                if (m <= (uint32_t) k) { val = (uint32_t) lane; pos = lane; }
-            }
-            // make the LDS writes of this wave visible to all of its lanes
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            if (opaque_lane_id() < cnt && val >= seen && val < seen + here) {
-                const uint32_t local = val - seen;
-                // last chunk whose prefix is <= local
-                const int chunks = (len + kWave - 1) / kWave;
-                int lo = 0, hi = chunks;                       // answer in [lo, hi)
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if (rs.prefix[mid] <= local) lo = mid; else hi = mid;
+        uint32_t val;
+        int pos;
+        floyd_in_group<G>(m > (uint32_t) k ? m : (uint32_t) k + 1u, k, a.key0, a.key1, a.layer_number,
+                          (uint32_t) vi, s, &val, &pos);
+        const int cnt = (m > (uint32_t) k) ? k : (int) m;
+        if (m <= (uint32_t) k) { val = (uint32_t) s; pos = s; }
+
+        // pass 2: lane s < cnt finds the flag word that holds its rank and the bit inside it
+        int64_t entry = -1;
+        uint32_t run = 0;
+        for (int32_t it = 0; __any(it * G + s < nw); ++it) {
+            const int32_t j = it * G + s;
+            uint64_t w = w_first;
+            int32_t incl = incl_first;
+            if (it > 0) {                                   // only rows longer than G words reload
+                w = 0;
+                if (j < nw) {
+                    w = a.flags[g0 + j];
+                    if (j == nw - 1) w &= tail_mask;
                 }
-                const int bit = select_bit64(rs.masks[lo], (int) (local - rs.prefix[lo]));
-                const int32_t u = row_idx[off + (int64_t) lo * kWave + bit];
-                const int32_t slot = bitmap_rank(a.cache_bitmap, a.cache_prefix, (uint32_t) u);
-                const double inv_pc = a.cache_inv_pc[slot];
-                double w;
-                if (a.wmode == GNS_W_UNBIASED) w = inv_pc * (double) m / (double) cnt;
-                else                           w = inv_pc * (double) cnt / (double) k;
-                a.s_nbr[(int64_t) row * k + pos] = u;
-                a.s_w[(int64_t) row * k + pos] = (float) w;
-                mark_node(a.mark, (uint32_t) u);
+                incl = group_inclusive_scan<G>(__popcll(w), s);
             }
-            seen += here;
-            // the next segment overwrites the LDS arrays: wait until every lane has read them
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
+            const uint32_t step_total = (uint32_t) __shfl(incl, G - 1, G);
+            const bool mine = s < cnt && entry < 0 && val >= run && val < run + step_total;
+            const uint32_t local = val - run;
+            // owner = number of lanes whose inclusive count is <= local
+            int owner = 0;
+            for (int t = 0; t < G; ++t) owner += ((uint32_t) __shfl(incl, t, G) <= local) ? 1 : 0;
+            owner = owner < G ? owner : G - 1;
+            const uint64_t w_owner = __shfl(w, owner, G);
+            const int32_t incl_owner = __shfl(incl, owner, G);
+            if (mine) {
+                const int32_t before = incl_owner - __popcll(w_owner);
+                const int bit = select_bit64(w_owner, (int) local - before);
+                entry = (g0 + (j - s) + owner) * 64 + bit;
+            }
+            run += step_total;
         }
-        if (lane == 0) {
-            a.s_cnt[row] = (m > (uint32_t) k) ? k : (int32_t) m;
+
+        if (live && s < cnt) {
+            const int32_t u = a.indices[entry];
+            // Section 3.4: p_u = deg(u)/nnz, p^C_u = 1 - (1 - p_u)^|C| (expm1/log1p keep tiny p_u exact),
+            // coefficient p^C_u * k / min(k, N_C(v)), weight = 1 / coefficient
+            int64_t ub, ue;
+            row_extent<OffT>(a, u, &ub, &ue);
+            const double p = (double) (ue - ub) / (double) a.num_entries;
+            const double pc = (p >= 1.0) ? 1.0 : -expm1((double) a.cache_size * log1p(-p));
+            double wgt;
+            if (a.wmode == GNS_W_UNBIASED) wgt = (double) m / ((double) cnt * pc);
+            else                           wgt = 1.0 / (pc * (double) k / (double) cnt);
+            a.s_nbr[row * k + pos] = u;
+            a.s_w[row * k + pos] = (float) wgt;
+            mark_if_new(a, (uint32_t) u);
+        }
+        if (live && s == 0) {
+            a.s_cnt[row] = cnt;
             a.row_eligible[row] = (int32_t) m;
         }
     }
@@ -309,37 +424,65 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, uint64_t seed, const
     a.dst_nodes = dst_nodes;
     a.cache_bitmap = ws_ptr<uint64_t>(c, L.cache_bitmap);
     a.cache_prefix = ws_ptr<int32_t>(c, L.cache_prefix);
-    a.cache_inv_pc = ws_ptr<double>(c, L.cache_inv_pc);
+    a.cache_size = c->config.cache_size;
     a.s_nbr = ws_ptr<int32_t>(c, L.s_nbr);
     a.s_w = ws_ptr<float>(c, L.s_w);
     a.s_cnt = ws_ptr<int32_t>(c, L.s_cnt);
     a.row_eligible = row_eligible;
     a.mark = ws_ptr<uint64_t>(c, L.mark_bitmap);
+    a.slots = ws_ptr<unsigned long long>(c, L.hash_slots);
+    a.hmask = L.hash_cap - 1;
+    a.hshift = 32u - (uint32_t) __builtin_ctz(L.hash_cap);
+    a.num_entries = c->graph.num_entries;
+    a.plan_cnt = ws_ptr<int32_t>(c, L.plan_cnt);
+    a.plan_g0 = ws_ptr<int32_t>(c, L.plan_g0);
+    a.plan_sums = ws_ptr<int32_t>(c, L.sums_plan);
+    a.plan_desc = ws_ptr<int32_t>(c, L.plan_desc);
+    a.flags = ws_ptr<uint64_t>(c, L.edge_flags);
+    a.bitmap_words = L.words;
 
     const int64_t rows_max = L.rows[layer_index];
     const bool i64 = c->graph.indptr_is_i64 != 0;
+    const int G = (a.fanout <= 8) ? 8 : (a.fanout <= 16) ? 16 : 64;
+    const int64_t rows_per_block = kBlock / G;
+    int64_t row_blocks = (rows_max + rows_per_block - 1) / rows_per_block;
+    const int64_t cap = (int64_t) c->num_cus * 8;
+    if (row_blocks > cap) row_blocks = cap;
+    if (row_blocks < 1) row_blocks = 1;
+    const dim3 rb((unsigned) row_blocks), tb(kBlock);
+
+#define GNS_LAUNCH_BY_G(KERNEL)                                                                              \
+    do {                                                                                                     \
+        if (G == 8) {                                                                                        \
+            if (i64) hipLaunchKernelGGL((KERNEL<int64_t, 8>), rb, tb, 0, s, a);                              \
+            else     hipLaunchKernelGGL((KERNEL<int32_t, 8>), rb, tb, 0, s, a);                              \
+        } else if (G == 16) {                                                                                \
+            if (i64) hipLaunchKernelGGL((KERNEL<int64_t, 16>), rb, tb, 0, s, a);                             \
+            else     hipLaunchKernelGGL((KERNEL<int32_t, 16>), rb, tb, 0, s, a);                             \
+        } else {                                                                                             \
+            if (i64) hipLaunchKernelGGL((KERNEL<int64_t, 64>), rb, tb, 0, s, a);                             \
+            else     hipLaunchKernelGGL((KERNEL<int32_t, 64>), rb, tb, 0, s, a);                             \
+        }                                                                                                    \
+    } while (0)
+
     if (c->config.policy[layer_index] == GNS_UNIFORM) {
-        const int G = (a.fanout <= 16) ? 16 : 64;
-        const int64_t groups_per_block = kBlock / G;
-        int64_t blocks = (rows_max + groups_per_block - 1) / groups_per_block;
-        const int64_t cap = (int64_t) c->num_cus * 8;
-        if (blocks > cap) blocks = cap;
-        if (blocks < 1) blocks = 1;
-        if (G == 16) {
-            if (i64) hipLaunchKernelGGL((k_sample_uniform<int64_t, 16>), dim3((unsigned) blocks), dim3(kBlock), 0, s, a);
-            else     hipLaunchKernelGGL((k_sample_uniform<int32_t, 16>), dim3((unsigned) blocks), dim3(kBlock), 0, s, a);
-        } else {
-            if (i64) hipLaunchKernelGGL((k_sample_uniform<int64_t, 64>), dim3((unsigned) blocks), dim3(kBlock), 0, s, a);
-            else     hipLaunchKernelGGL((k_sample_uniform<int32_t, 64>), dim3((unsigned) blocks), dim3(kBlock), 0, s, a);
-        }
-    } else {
-        int64_t blocks = (rows_max + kWavesPerBlock - 1) / kWavesPerBlock;
-        const int64_t cap = (int64_t) c->num_cus * 8;
-        if (blocks > cap) blocks = cap;
-        if (blocks < 1) blocks = 1;
-        if (i64) hipLaunchKernelGGL((k_sample_cache_only<int64_t>), dim3((unsigned) blocks), dim3(kBlock), 0, s, a);
-        else     hipLaunchKernelGGL((k_sample_cache_only<int32_t>), dim3((unsigned) blocks), dim3(kBlock), 0, s, a);
+        GNS_LAUNCH_BY_G(k_sample_uniform);
+        return hipGetLastError();
     }
+
+    // CACHE_ONLY: plan -> flag -> select
+    const unsigned plan_blocks = (unsigned) ((rows_max + kPlanTile - 1) / kPlanTile);
+    if (i64) hipLaunchKernelGGL((k_plan_count<int64_t>), dim3(plan_blocks), tb, 0, s, a);
+    else     hipLaunchKernelGGL((k_plan_count<int32_t>), dim3(plan_blocks), tb, 0, s, a);
+    hipLaunchKernelGGL(k_plan_expand, dim3(plan_blocks), tb, 0, s, a);
+    const size_t lds_bytes = (size_t) ((L.words + 1) / 2) * 16;
+    if (lds_bytes <= c->lds_bitmap_limit) {
+        hipLaunchKernelGGL((k_flag_chunks<true>), dim3((unsigned) c->num_cus), dim3(1024), lds_bytes, s, a, 1, (int64_t) 0);
+    } else {
+        hipLaunchKernelGGL((k_flag_chunks<false>), dim3((unsigned) c->num_cus * 8), tb, 0, s, a, 1, (int64_t) 0);
+    }
+    GNS_LAUNCH_BY_G(k_select_rows);
+#undef GNS_LAUNCH_BY_G
     return hipGetLastError();
 }
 

@@ -265,3 +265,58 @@ def test_config1_tiny_graph():
 
 def test_config2_medium_graph():
     _config_parity(2, batches=2)
+
+
+def test_async_pipeline_on_forked_contexts():
+    """Three mini-batches in flight on three streams (the created context and two
+    forks sharing its cache), no host synchronisation between sampling, gather and
+    aggregation (counts stay on the device); every batch must still match the oracle."""
+    ip, ix = _small(n=4000, avg=16, seed=11)
+    n = ip.numel() - 1
+    F = 32
+    feat = _feat(n, F, seed=5)
+    fanouts, policies, csize, bs = (6, 4, 3), (U, U, C), 250, 96
+    gns = GpuGns(ip, ix, feat, fanouts=fanouts, policies=policies, cache_size=csize, max_seeds=bs)
+    forks, fork_ws = [], []
+    try:
+        ref_cache = oracle.sample_cache(ip.numpy(), 21, 3, csize)
+        compare_cache(gns.sample_cache(21, 3), ref_cache)
+        ctxs = [gns.ctx]
+        for _ in range(2):
+            ws = torch.empty(B.gns_fork_workspace_bytes(gns.ctx), dtype=torch.uint8, device=gns.device)
+            fork_ws.append(ws)
+            child = B.gns_fork(gns.ctx, ws)
+            forks.append(child)
+            ctxs.append(child)
+        streams = [torch.cuda.Stream() for _ in ctxs]
+        bufs = [B.BlockBuffers(gns.graph, gns.config, gns.device) for _ in ctxs]
+        last = len(fanouts) - 1
+        xin = [torch.zeros((b.array[last].cap_src, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        out = [torch.zeros((b.array[last].cap_dst, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        for rnd in range(2):
+            seeds = [synth.uniform_seed_batch(n, bs - 7 * i, 300 + 10 * rnd + i).cuda() for i in range(len(ctxs))]
+            torch.cuda.synchronize()
+            for i, ctx in enumerate(ctxs):
+                with torch.cuda.stream(streams[i]):
+                    B.gns_sample_blocks_async(ctx, 900 + 10 * rnd + i, seeds[i], bufs[i].array, streams[i])
+                    assert bufs[i].array[last].num_dst == -1 - last
+                    B.gns_gather_features(ctx, bufs[i].tensors[last]["src_nodes"], -1, xin[i], streams[i])
+                    B.gns_aggregate(ctx, bufs[i].array[last], xin[i], F, out[i], streams[i])
+            for i, ctx in enumerate(ctxs):
+                B.gns_sample_blocks_wait(ctx, bufs[i].array, streams[i])
+            torch.cuda.synchronize()
+            for i in range(len(ctxs)):
+                ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), ref_cache[1], csize, 900 + 10 * rnd + i,
+                                           seeds[i].cpu().numpy(), list(fanouts), list(policies))
+                compare_blocks([bufs[i].views(j) for j in range(len(fanouts))], ref)
+                x_ref = oracle.gather(feat.numpy(), ref[last].src_nodes)
+                assert xin[i][:ref[last].num_src].cpu().numpy().tobytes() == x_ref.tobytes()
+                o_ref = oracle.aggregate(ref[last].indptr, ref[last].indices, ref[last].weights, x_ref)
+                from gpu_harness import compare_aggregate, aggregate_scale
+                compare_aggregate(out[i][:ref[last].num_dst].cpu().numpy(), o_ref, aggregate_scale(ref[last], x_ref))
+        with pytest.raises(B.GnsError):                       # the cache belongs to the created context
+            B.gns_sample_cache(forks[0], 1, 0)
+    finally:
+        for f in forks:
+            B.gns_destroy(f)
+        gns.close()
