@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--cpu-batches", type=int, default=32, help="mini-batches the CPU oracle is timed on (0: skip)")
     ap.add_argument("--stages", action="store_true", help="add an untimed pass that times every stage")
     ap.add_argument("--threads", type=int, default=0, help="1: one host thread per slot")
+    ap.add_argument("--flag-mode", type=int, default=0,
+                    help="0: membership flags per mini-batch (CSR-segment scan); 1: once per cache draw")
     ap.add_argument("--slots", type=int, default=4,
                     help="mini-batches kept in flight (one context + stream each; they share the cache)")
     args = ap.parse_args()
@@ -65,7 +67,7 @@ def main():
     deg = (g.indptr[1:] - g.indptr[:-1]).to(torch.int64)
 
     graph = B.make_graph(g.indptr, g.indices, feat_dev=feat)
-    config = B.make_config(fanouts, policies, cache_size, batch)
+    config = B.make_config(fanouts, policies, cache_size, batch, flag_mode=args.flag_mode)
     ws = B.alloc_workspace(graph, config, dev)
     ctx = B.gns_create(graph, config, ws)
     last = L - 1

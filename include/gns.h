@@ -85,6 +85,16 @@ typedef struct {
     const float* feat_host_pinned; /* pinned host fp32[n x F] readable from the device, or NULL */
 } gns_graph;
 
+/* How a CACHE_ONLY layer learns which entries of a dst row point into the cache
+ * (Section 3.3).  Both give the identical sample.
+ *  GNS_FLAGS_PER_BATCH: every mini-batch streams the CSR segments of its dst rows and
+ *      tests each entry against the cache bitmap (the "overlap" computation).
+ *  GNS_FLAGS_PER_CACHE: gns_sample_cache tests every CSR entry once and keeps one bit
+ *      per entry; mini-batches only read their rows' bits.  This is the induced subgraph
+ *      S of Section 3.3 (built once, right after the cache is drawn) in bit form; it
+ *      costs num_entries/8 bytes of workspace and one pass over the graph per cache. */
+enum { GNS_FLAGS_PER_BATCH = 0, GNS_FLAGS_PER_CACHE = 1 };
+
 typedef struct {
     int32_t num_layers;               /* L, 1..GNS_MAX_LAYERS                                       */
     int32_t fanout[GNS_MAX_LAYERS];   /* k per layer; index 0 is layer L (next to the seeds), index
@@ -93,6 +103,8 @@ typedef struct {
     int64_t cache_size;               /* |C|; 0 if no layer uses the cache                          */
     int32_t wmode;                    /* GNS_W_PRINTED / GNS_W_UNBIASED                             */
     int32_t max_seeds;                /* largest mini-batch |B| the context must accept             */
+    int32_t flag_mode;                /* GNS_FLAGS_PER_BATCH / GNS_FLAGS_PER_CACHE                  */
+    int32_t reserved;                 /* must be 0                                                  */
 } gns_config;
 
 /* One layer's block: a CSR over (dst rows) x (src columns) in local ids.

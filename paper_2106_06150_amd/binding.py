@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libgns.so")
 GNS_OK, GNS_EINVAL, GNS_ECAPACITY, GNS_ESTATE, GNS_EHIP, GNS_ENOMEM, GNS_ENOTIMPL = range(7)
 GNS_UNIFORM, GNS_CACHE_ONLY, GNS_CACHE_FIRST = 0, 1, 2
 GNS_W_PRINTED, GNS_W_UNBIASED = 0, 1
+GNS_FLAGS_PER_BATCH, GNS_FLAGS_PER_CACHE = 0, 1
 GNS_MAX_LAYERS = 8
 GNS_MAX_FANOUT = 64
 
@@ -31,7 +32,8 @@ class gns_graph(ctypes.Structure):
 class gns_config(ctypes.Structure):
     _fields_ = [("num_layers", ctypes.c_int32), ("fanout", ctypes.c_int32 * GNS_MAX_LAYERS),
                 ("policy", ctypes.c_int32 * GNS_MAX_LAYERS), ("cache_size", ctypes.c_int64),
-                ("wmode", ctypes.c_int32), ("max_seeds", ctypes.c_int32)]
+                ("wmode", ctypes.c_int32), ("max_seeds", ctypes.c_int32),
+                ("flag_mode", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class gns_block(ctypes.Structure):
@@ -133,7 +135,7 @@ def make_graph(indptr, indices, feat_dev=None, feat_host_pinned=None, feat_dim=N
     return g
 
 
-def make_config(fanouts, policies, cache_size, max_seeds, wmode=GNS_W_PRINTED):
+def make_config(fanouts, policies, cache_size, max_seeds, wmode=GNS_W_PRINTED, flag_mode=GNS_FLAGS_PER_BATCH):
     c = gns_config()
     c.num_layers = len(fanouts)
     for i, (k, p) in enumerate(zip(fanouts, policies)):
@@ -142,6 +144,7 @@ def make_config(fanouts, policies, cache_size, max_seeds, wmode=GNS_W_PRINTED):
     c.cache_size = cache_size
     c.wmode = wmode
     c.max_seeds = max_seeds
+    c.flag_mode = flag_mode
     return c
 
 

@@ -40,6 +40,8 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     if (cfg->num_layers < 1 || cfg->num_layers > GNS_MAX_LAYERS) GNS_BAD("num_layers out of range");
     if (cfg->max_seeds < 1) GNS_BAD("max_seeds must be >= 1");
     if (cfg->wmode != GNS_W_PRINTED && cfg->wmode != GNS_W_UNBIASED) GNS_BAD("unknown weight mode");
+    if (cfg->flag_mode != GNS_FLAGS_PER_BATCH && cfg->flag_mode != GNS_FLAGS_PER_CACHE) GNS_BAD("unknown flag mode");
+    if (cfg->reserved != 0) GNS_BAD("reserved config field must be 0");
     for (int i = 0; i < cfg->num_layers; ++i) {
         if (cfg->fanout[i] < 1 || cfg->fanout[i] > GNS_MAX_FANOUT) GNS_BAD("fanout out of range");
         if (cfg->policy[i] != GNS_UNIFORM && cfg->policy[i] != GNS_CACHE_ONLY && cfg->policy[i] != GNS_CACHE_FIRST)
@@ -131,6 +133,111 @@ static gns_status ctx_fail(gns_ctx* c, gns_status st, const char* what, hipError
 
 using namespace gns;
 
+// Every launch of one mini-batch, in order, on stream s (also the body that is captured).
+static gns_status enqueue_batch(gns_ctx* c, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
+                                gns_block* blocks, hipStream_t s)
+{
+    const int nl = c->config.num_layers;
+    hipError_t e = launch_batch_begin(c, seed, seeds_dev, num_seeds, s);
+    if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "batch begin", e);
+    const int32_t* dst = seeds_dev;
+    for (int i = 0; i < nl; ++i) {
+        {
+            StageTimer t(c, GNS_STAGE_SAMPLE + i, s);
+            e = launch_sample_layer(c, i, dst, blocks[i].row_eligible, s);
+        }
+        if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample layer", e);
+        {
+            StageTimer t(c, GNS_STAGE_FINISH + i, s);
+            e = launch_finish_layer(c, i, dst, &blocks[i], s);
+        }
+        if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "finish layer", e);
+        dst = blocks[i].src_nodes;
+    }
+    e = hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s);
+    if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample_blocks readback", e);
+    return GNS_OK;
+}
+
+static void graph_release(gns_ctx* c)
+{
+    if (c->graph_exec) (void) hipGraphExecDestroy(c->graph_exec);
+    if (c->batch_graph) (void) hipGraphDestroy(c->batch_graph);
+    c->graph_exec = nullptr;
+    c->batch_graph = nullptr;
+    c->graph_first = nullptr;
+    c->graph_valid = false;
+}
+
+// The batch's launch sequence does not depend on the data (grids are sized for the worst
+// case and counts stay on the device), so it is captured once per set of caller buffers and
+// replayed with hipGraphLaunch; only the first kernel's seed / seed-count arguments change.
+static gns_status launch_batch_graph(gns_ctx* c, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
+                                     gns_block* blocks, hipStream_t s)
+{
+    const int nl = c->config.num_layers;
+    bool same = c->graph_valid && c->gk_seeds == seeds_dev;
+    for (int i = 0; same && i < nl; ++i) {
+        const gns_block& a = c->gk_blocks[i];
+        const gns_block& b = blocks[i];
+        same = a.indptr == b.indptr && a.indices == b.indices && a.src_nodes == b.src_nodes &&
+               a.row_eligible == b.row_eligible && a.weights == b.weights;
+    }
+    hipError_t e;
+    if (!same) {
+        graph_release(c);
+        e = hipStreamBeginCapture(c->cap_stream, hipStreamCaptureModeRelaxed);
+        if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "begin capture", e);
+        const gns_status st = enqueue_batch(c, seed, seeds_dev, num_seeds, blocks, c->cap_stream);
+        e = hipStreamEndCapture(c->cap_stream, &c->batch_graph);
+        if (st != GNS_OK) { graph_release(c); return st; }
+        if (e != hipSuccess) { graph_release(c); return ctx_fail(c, GNS_EHIP, "end capture", e); }
+        e = hipGraphInstantiate(&c->graph_exec, c->batch_graph, nullptr, nullptr, 0);
+        if (e != hipSuccess) { graph_release(c); return ctx_fail(c, GNS_EHIP, "graph instantiate", e); }
+        // find the first kernel's node
+        size_t count = 0;
+        e = hipGraphGetNodes(c->batch_graph, nullptr, &count);
+        if (e != hipSuccess || count == 0 || count > 256) { graph_release(c); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
+        hipGraphNode_t nodes[256];
+        e = hipGraphGetNodes(c->batch_graph, nodes, &count);
+        if (e != hipSuccess) { graph_release(c); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
+        for (size_t i = 0; i < count && !c->graph_first; ++i) {
+            hipGraphNodeType type;
+            if (hipGraphNodeGetType(nodes[i], &type) != hipSuccess || type != hipGraphNodeTypeKernel) continue;
+            hipKernelNodeParams kp;
+            if (hipGraphKernelNodeGetParams(nodes[i], &kp) != hipSuccess) continue;
+            if (kp.func == batch_first_kernel()) c->graph_first = nodes[i];
+        }
+        if (!c->graph_first) { graph_release(c); return ctx_fail(c, GNS_EHIP, "first kernel node not found in the captured graph"); }
+        c->gk_seeds = seeds_dev;
+        for (int i = 0; i < nl; ++i) c->gk_blocks[i] = blocks[i];
+        c->graph_valid = true;
+    }
+    // new scalars for this batch
+    hipKernelNodeParams kp;
+    e = hipGraphKernelNodeGetParams(c->graph_first, &kp);
+    if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "get first kernel params", e);
+    c->ga_slots = ws_ptr<unsigned long long>(c, c->lay.hash_slots);
+    c->ga_cap = (size_t) c->lay.hash_cap;
+    c->ga_state = c->d_state;
+    c->ga_num_seeds = num_seeds;
+    c->ga_key0 = (uint32_t) seed;
+    c->ga_key1 = (uint32_t) (seed >> 32);
+    c->ga_ptrs[0] = &c->ga_slots;
+    c->ga_ptrs[1] = &c->ga_cap;
+    c->ga_ptrs[2] = &c->ga_state;
+    c->ga_ptrs[3] = &c->ga_num_seeds;
+    c->ga_ptrs[4] = &c->ga_key0;
+    c->ga_ptrs[5] = &c->ga_key1;
+    kp.kernelParams = c->ga_ptrs;
+    kp.extra = nullptr;
+    e = hipGraphExecKernelNodeSetParams(c->graph_exec, c->graph_first, &kp);
+    if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "set first kernel params", e);
+    e = hipGraphLaunch(c->graph_exec, s);
+    if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "graph launch", e);
+    return GNS_OK;
+}
+
 extern "C" {
 
 size_t gns_workspace_bytes(const gns_graph* graph, const gns_config* config)
@@ -192,6 +299,7 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
         if (e != hipSuccess) snprintf(g_create_err, sizeof(g_create_err), "%s: %s", what, hipGetErrorString(e));
         else snprintf(g_create_err, sizeof(g_create_err), "%s", what);
         if (c->h_state) (void) hipHostFree(c->h_state);
+        if (c->cap_stream) (void) hipStreamDestroy(c->cap_stream);
         delete c;
         return st;
     };
@@ -207,6 +315,10 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
     c->lds_bitmap_limit = prop.sharedMemPerBlock > 1024 ? prop.sharedMemPerBlock - 1024 : 0;
     e = hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(DeviceState), hipHostMallocDefault);
     if (e != hipSuccess) { c->h_state = nullptr; return bail(GNS_EHIP, "hipHostMalloc", e); }
+    if (!getenv("GNS_NO_GRAPH")) {
+        e = hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking);
+        if (e != hipSuccess) { c->cap_stream = nullptr; return bail(GNS_EHIP, "hipStreamCreate", e); }
+    }
 
     // zero the state, the mark bitmap and the cache bitmap; validate the graph
     e = launch_fill_u32(reinterpret_cast<uint32_t*>(c->d_state), (sizeof(DeviceState) + 64) / 4, 0u, s);
@@ -318,13 +430,23 @@ gns_status gns_fork(gns_ctx* parent, void* workspace, size_t workspace_bytes, vo
     c->prof_capacity = c->prof_count = 0;
     c->prof_mask = 0;
     c->err[0] = 0;
+    c->batch_graph = nullptr;
+    c->graph_exec = nullptr;
+    c->graph_first = nullptr;
+    c->graph_valid = false;
+    c->cap_stream = nullptr;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (root->cap_stream && hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking) != hipSuccess) {
+        delete c;
+        return ctx_fail(parent, GNS_EHIP, "hipStreamCreate");
+    }
     hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(DeviceState), hipHostMallocDefault);
     if (e == hipSuccess) e = launch_fill_u32(reinterpret_cast<uint32_t*>(c->d_state), (sizeof(DeviceState) + 64) / 4, 0u, s);
     if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, c->lay.mark_bitmap), (size_t) c->lay.words, 0ull, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
         if (c->h_state) (void) hipHostFree(c->h_state);
+        if (c->cap_stream) (void) hipStreamDestroy(c->cap_stream);
         delete c;
         return ctx_fail(parent, GNS_EHIP, "fork init", e);
     }
@@ -336,6 +458,8 @@ gns_status gns_destroy(gns_ctx* ctx)
 {
     if (!ctx) return GNS_OK;
     profile_release(ctx);
+    graph_release(ctx);
+    if (ctx->cap_stream) (void) hipStreamDestroy(ctx->cap_stream);
     if (ctx->h_state) (void) hipHostFree(ctx->h_state);
     delete ctx;
     return GNS_OK;
@@ -383,24 +507,10 @@ gns_status gns_sample_blocks_async(gns_ctx* ctx, uint64_t seed, const int32_t* s
         }
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = launch_batch_begin(c, seeds_dev, num_seeds, s);
-    if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "batch begin", e);
-    const int32_t* dst = seeds_dev;
-    for (int i = 0; i < nl; ++i) {
-        {
-            StageTimer t(c, GNS_STAGE_SAMPLE + i, s);
-            e = launch_sample_layer(c, i, seed, dst, blocks[i].row_eligible, s);
-        }
-        if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample layer", e);
-        {
-            StageTimer t(c, GNS_STAGE_FINISH + i, s);
-            e = launch_finish_layer(c, i, dst, &blocks[i], s);
-        }
-        if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "finish layer", e);
-        dst = blocks[i].src_nodes;
-    }
-    e = hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s);
-    if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample_blocks readback", e);
+    gns_status st = GNS_OK;
+    if (c->prof_mask == 0 && c->cap_stream) st = launch_batch_graph(c, seed, seeds_dev, num_seeds, blocks, s);
+    else                                     st = enqueue_batch(c, seed, seeds_dev, num_seeds, blocks, s);
+    if (st != GNS_OK) return st;
     for (int i = 0; i < nl; ++i) {
         blocks[i].num_dst = GNS_DEVICE_COUNTS(i);
         blocks[i].num_src = -1;

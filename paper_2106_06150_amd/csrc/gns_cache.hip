@@ -329,6 +329,8 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
     hipLaunchKernelGGL(k_cache_index_phase3, dim3((unsigned) x.tiles), dim3(kBlock), 0, s, x);
     GNS_HIP_TRY(hipGetLastError(), "cache index launch");
 
+    if (c->config.flag_mode == GNS_FLAGS_PER_CACHE)
+        GNS_HIP_TRY(launch_flag_all_entries(c, s), "flag all entries");
     if (c->graph.feat_dim > 0) {
         // fill the device table of cached feature rows (slot order) straight from the full store
         c->cache_valid = false;   // gather below must not consult the table being written

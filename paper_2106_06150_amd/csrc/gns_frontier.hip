@@ -57,7 +57,10 @@ hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s)
 }
 
 // ---------------------------------------------------------------------------
-__global__ void k_batch_clear(unsigned long long* slots, size_t cap, DeviceState* st, int32_t num_seeds)
+// First kernel of a mini-batch: empties the hash map and publishes the batch's scalars
+// (number of seeds, Philox key) in the device state, from where every later kernel reads them.
+__global__ void k_batch_clear(unsigned long long* slots, size_t cap, DeviceState* st, int32_t num_seeds,
+                              uint32_t key0, uint32_t key1)
 {
     size_t i = (size_t) blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t) gridDim.x * blockDim.x;
@@ -65,30 +68,35 @@ __global__ void k_batch_clear(unsigned long long* slots, size_t cap, DeviceState
         st->num_dst[0] = num_seeds;
         for (int l = 0; l < GNS_MAX_LAYERS; ++l) { st->num_edges[l] = 0; st->num_dst[l + 1] = 0; }
         st->bad_seed = 0;
+        st->key0 = key0;
+        st->key1 = key1;
     }
     for (; i < cap; i += stride) slots[i] = kEmptySlot;
 }
 
+const void* batch_first_kernel() { return reinterpret_cast<const void*>(&k_batch_clear); }
+
 __global__ void k_seed_insert(unsigned long long* slots, uint32_t mask, uint32_t shift, const int32_t* seeds,
-                              int32_t num_seeds, int64_t n, DeviceState* st)
+                              int64_t n, DeviceState* st)
 {
     const int32_t i = (int32_t) (blockIdx.x * blockDim.x + threadIdx.x);
-    if (i >= num_seeds) return;
+    if (i >= st->num_dst[0]) return;
     const int32_t u = seeds[i];
     if (u < 0 || (int64_t) u >= n) { st->bad_seed = 1; return; }
     if (!hash_insert(slots, mask, shift, (uint32_t) u, (uint32_t) i)) st->bad_seed = 1;
 }
 
-hipError_t launch_batch_begin(gns_ctx* c, const int32_t* seeds, int32_t num_seeds, hipStream_t s)
+hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, hipStream_t s)
 {
     const Layout& L = c->lay;
     unsigned long long* slots = ws_ptr<unsigned long long>(c, L.hash_slots);
     hipLaunchKernelGGL(k_batch_clear, dim3(fill_grid(L.hash_cap)), dim3(kBlock), 0, s, slots, (size_t) L.hash_cap,
-                       c->d_state, num_seeds);
+                       c->d_state, num_seeds, (uint32_t) seed, (uint32_t) (seed >> 32));
     const uint32_t mask = L.hash_cap - 1;
     const uint32_t shift = 32u - (uint32_t) __builtin_ctz(L.hash_cap);
-    hipLaunchKernelGGL(k_seed_insert, dim3((num_seeds + kBlock - 1) / kBlock), dim3(kBlock), 0, s, slots, mask, shift,
-                       seeds, num_seeds, c->graph.num_nodes, c->d_state);
+    const int32_t max_seeds = c->config.max_seeds;      // the grid covers the largest batch; the count is on the device
+    hipLaunchKernelGGL(k_seed_insert, dim3((max_seeds + kBlock - 1) / kBlock), dim3(kBlock), 0, s, slots, mask, shift,
+                       seeds, c->graph.num_nodes, c->d_state);
     return hipGetLastError();
 }
 

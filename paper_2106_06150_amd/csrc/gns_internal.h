@@ -14,6 +14,7 @@ namespace gns {
 struct DeviceState {
     int32_t num_dst[GNS_MAX_LAYERS + 1];  // rows of layer index i (num_dst[i+1] = num_src of layer i)
     int32_t num_edges[GNS_MAX_LAYERS];
+    uint32_t key0, key1;                  // Philox key of the current batch (lo32(seed), hi32(seed))
     int32_t bad_seed;                     // set if a seed was out of range or repeated
     int32_t chunk_distinct;               // cache draw: first occurrences found in the current chunk
     int32_t plan_chunks;                  // CACHE_ONLY sampler: aligned chunks in the current work list
@@ -76,6 +77,22 @@ struct gns_ctx {
     int64_t nonzero_degree_nodes;
     int num_cus;
     size_t lds_bitmap_limit;         // largest cache bitmap (bytes) the flag kernel stages in LDS
+    // The launch sequence of one mini-batch, captured once per (seeds pointer, block buffers) and
+    // replayed; only the first kernel's arguments (seed, number of seeds) change between replays.
+    hipStream_t cap_stream;          // used for capture only, never for execution
+    hipGraph_t batch_graph;
+    hipGraphExec_t graph_exec;
+    hipGraphNode_t graph_first;      // the k_batch_clear node
+    bool graph_valid;
+    const int32_t* gk_seeds;         // capture key
+    gns_block gk_blocks[GNS_MAX_LAYERS];
+    // argument storage of the first kernel (pointed to by the node's parameter list)
+    unsigned long long* ga_slots;
+    size_t ga_cap;
+    gns::DeviceState* ga_state;
+    int32_t ga_num_seeds;
+    uint32_t ga_key0, ga_key1;
+    void* ga_ptrs[6];
     // optional stage timing (benchmarks only)
     uint32_t prof_mask;
     int32_t prof_capacity;
@@ -117,11 +134,13 @@ hipError_t launch_count_nonzero_rows(gns_ctx* c, hipStream_t s, int32_t* d_out);
 gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream_t s);
 
 // gns_sampler.hip
-hipError_t launch_sample_layer(gns_ctx* c, int layer_index, uint64_t seed, const int32_t* dst_nodes,
+hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes,
                                int32_t* row_eligible, hipStream_t s);
+hipError_t launch_flag_all_entries(gns_ctx* c, hipStream_t s);
 
 // gns_frontier.hip
-hipError_t launch_batch_begin(gns_ctx* c, const int32_t* seeds, int32_t num_seeds, hipStream_t s);
+hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, hipStream_t s);
+const void* batch_first_kernel();
 hipError_t launch_finish_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s);
 hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);

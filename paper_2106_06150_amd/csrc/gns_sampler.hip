@@ -27,7 +27,6 @@ struct SampleArgs {
     uint32_t layer_number;     // the paper's l = L - layer_index
     int fanout;
     int wmode;
-    uint32_t key0, key1;       // Philox key = (lo32(seed), hi32(seed))
     int64_t num_nodes;
     const void* indptr;
     const int32_t* indices;
@@ -124,7 +123,7 @@ __global__ void __launch_bounds__(kBlock) k_sample_uniform(SampleArgs a)
         uint32_t val;
         int pos;
         // run the draw with a safe size in every lane, then keep it only where it applies
-        floyd_in_group<G>(m > (uint32_t) k ? m : (uint32_t) k + 1u, k, a.key0, a.key1, a.layer_number, v, s, &val, &pos);
+        floyd_in_group<G>(m > (uint32_t) k ? m : (uint32_t) k + 1u, k, a.st->key0, a.st->key1, a.layer_number, v, s, &val, &pos);
         const int cnt = (m > (uint32_t) k) ? k : (int) m;
         if (m <= (uint32_t) k) { val = (uint32_t) s; pos = s; }
         if (live && s < cnt) {
@@ -347,7 +346,7 @@ __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a)
 
         uint32_t val;
         int pos;
-        floyd_in_group<G>(m > (uint32_t) k ? m : (uint32_t) k + 1u, k, a.key0, a.key1, a.layer_number,
+        floyd_in_group<G>(m > (uint32_t) k ? m : (uint32_t) k + 1u, k, a.st->key0, a.st->key1, a.layer_number,
                           (uint32_t) vi, s, &val, &pos);
         const int cnt = (m > (uint32_t) k) ? k : (int) m;
         if (m <= (uint32_t) k) { val = (uint32_t) s; pos = s; }
@@ -406,18 +405,37 @@ __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a)
     }
 }
 
-hipError_t launch_sample_layer(gns_ctx* c, int layer_index, uint64_t seed, const int32_t* dst_nodes,
-                               int32_t* row_eligible, hipStream_t s)
+static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, int32_t* row_eligible,
+                             SampleArgs* out);
+
+static void launch_flag_kernel(gns_ctx* c, const SampleArgs& a, int use_plan, int64_t all_chunks, hipStream_t s)
+{
+    const size_t lds_bytes = (size_t) ((c->lay.words + 1) / 2) * 16;
+    if (lds_bytes <= c->lds_bitmap_limit)
+        hipLaunchKernelGGL((k_flag_chunks<true>), dim3((unsigned) c->num_cus), dim3(1024), lds_bytes, s, a, use_plan, all_chunks);
+    else
+        hipLaunchKernelGGL((k_flag_chunks<false>), dim3((unsigned) c->num_cus * 8), dim3(kBlock), 0, s, a, use_plan, all_chunks);
+}
+
+// GNS_FLAGS_PER_CACHE: one pass over every aligned chunk of the CSR entry array.
+hipError_t launch_flag_all_entries(gns_ctx* c, hipStream_t s)
+{
+    SampleArgs a;
+    fill_sample_args(c, 0, nullptr, nullptr, &a);
+    launch_flag_kernel(c, a, 0, (c->graph.num_entries + 63) / 64, s);
+    return hipGetLastError();
+}
+
+static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, int32_t* row_eligible,
+                             SampleArgs* out)
 {
     const Layout& L = c->lay;
-    SampleArgs a;
+    SampleArgs& a = *out;
     a.st = c->d_state;
     a.layer_index = layer_index;
     a.layer_number = (uint32_t) (c->config.num_layers - layer_index);
     a.fanout = c->config.fanout[layer_index];
     a.wmode = c->config.wmode;
-    a.key0 = (uint32_t) seed;
-    a.key1 = (uint32_t) (seed >> 32);
     a.num_nodes = c->graph.num_nodes;
     a.indptr = c->graph.indptr;
     a.indices = c->graph.indices;
@@ -440,6 +458,14 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, uint64_t seed, const
     a.plan_desc = ws_ptr<int32_t>(c, L.plan_desc);
     a.flags = ws_ptr<uint64_t>(c, L.edge_flags);
     a.bitmap_words = L.words;
+}
+
+hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes,
+                               int32_t* row_eligible, hipStream_t s)
+{
+    const Layout& L = c->lay;
+    SampleArgs a;
+    fill_sample_args(c, layer_index, dst_nodes, row_eligible, &a);
 
     const int64_t rows_max = L.rows[layer_index];
     const bool i64 = c->graph.indptr_is_i64 != 0;
@@ -470,16 +496,13 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, uint64_t seed, const
         return hipGetLastError();
     }
 
-    // CACHE_ONLY: plan -> flag -> select
-    const unsigned plan_blocks = (unsigned) ((rows_max + kPlanTile - 1) / kPlanTile);
-    if (i64) hipLaunchKernelGGL((k_plan_count<int64_t>), dim3(plan_blocks), tb, 0, s, a);
-    else     hipLaunchKernelGGL((k_plan_count<int32_t>), dim3(plan_blocks), tb, 0, s, a);
-    hipLaunchKernelGGL(k_plan_expand, dim3(plan_blocks), tb, 0, s, a);
-    const size_t lds_bytes = (size_t) ((L.words + 1) / 2) * 16;
-    if (lds_bytes <= c->lds_bitmap_limit) {
-        hipLaunchKernelGGL((k_flag_chunks<true>), dim3((unsigned) c->num_cus), dim3(1024), lds_bytes, s, a, 1, (int64_t) 0);
-    } else {
-        hipLaunchKernelGGL((k_flag_chunks<false>), dim3((unsigned) c->num_cus * 8), tb, 0, s, a, 1, (int64_t) 0);
+    // CACHE_ONLY: (plan -> flag ->) select
+    if (c->config.flag_mode == GNS_FLAGS_PER_BATCH) {
+        const unsigned plan_blocks = (unsigned) ((rows_max + kPlanTile - 1) / kPlanTile);
+        if (i64) hipLaunchKernelGGL((k_plan_count<int64_t>), dim3(plan_blocks), tb, 0, s, a);
+        else     hipLaunchKernelGGL((k_plan_count<int32_t>), dim3(plan_blocks), tb, 0, s, a);
+        hipLaunchKernelGGL(k_plan_expand, dim3(plan_blocks), tb, 0, s, a);
+        launch_flag_kernel(c, a, 1, 0, s);
     }
     GNS_LAUNCH_BY_G(k_select_rows);
 #undef GNS_LAUNCH_BY_G

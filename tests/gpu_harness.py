@@ -12,7 +12,7 @@ AGG_RTOL = 1e-5        # aggregates: error relative to (1/n_v) * sum |w_e x_e| p
 
 class GpuGns:
     def __init__(self, indptr, indices, feat=None, *, fanouts, policies, cache_size, max_seeds,
-                 wmode=B.GNS_W_PRINTED, feat_on_host=False, device="cuda:0"):
+                 wmode=B.GNS_W_PRINTED, feat_on_host=False, device="cuda:0", flag_mode=0):
         self.device = torch.device(device)
         self.indptr_cpu = indptr
         self.indices_cpu = indices
@@ -27,7 +27,7 @@ class GpuGns:
             else:
                 self.feat_dev = feat.to(self.device)
         self.graph = B.make_graph(self.indptr, self.indices, self.feat_dev, self.feat_host)
-        self.config = B.make_config(fanouts, policies, cache_size, max_seeds, wmode)
+        self.config = B.make_config(fanouts, policies, cache_size, max_seeds, wmode, flag_mode)
         self.fanouts, self.policies, self.cache_size, self.wmode = list(fanouts), list(policies), cache_size, wmode
         self.workspace = B.alloc_workspace(self.graph, self.config, self.device)
         self.ctx = B.gns_create(self.graph, self.config, self.workspace)

@@ -31,14 +31,16 @@ def _feat(n, F, seed=0):
     return torch.randn((n, F), dtype=torch.float32, generator=g)
 
 
+@pytest.mark.parametrize("flag_mode", [0, 1])
 @pytest.mark.parametrize("offsets", [torch.int32, torch.int64])
 @pytest.mark.parametrize("fanouts,policies", [((10, 5), (U, C)), ((15, 10, 5), (U, U, C)), ((3, 2, 1), (C, C, C)),
                                               ((4, 4), (U, U)), ((20, 17), (U, C))])
-def test_small_graph_parity(offsets, fanouts, policies):
+def test_small_graph_parity(offsets, fanouts, policies, flag_mode):
     ip, ix = _small()
     n = ip.numel() - 1
     feat = _feat(n, 64)
-    gns = GpuGns(ip.to(offsets), ix, feat, fanouts=fanouts, policies=policies, cache_size=300, max_seeds=200)
+    gns = GpuGns(ip.to(offsets), ix, feat, fanouts=fanouts, policies=policies, cache_size=300, max_seeds=200,
+                 flag_mode=flag_mode)
     try:
         for trial in range(3):
             seeds = synth.uniform_seed_batch(n, 200 - 37 * trial, 100 + trial)
@@ -92,12 +94,13 @@ def _star_graph(n, hub_degree, extra_avg, seed):
     return torch.from_numpy(indptr), torch.from_numpy(col.astype(np.int32))
 
 
-@pytest.mark.parametrize("hub_degree", [16384, 16385, 40000])
-def test_hub_row_longer_than_one_segment(hub_degree):
+@pytest.mark.parametrize("flag_mode", [0, 1])
+@pytest.mark.parametrize("hub_degree", [1000, 16385, 40000])
+def test_hub_row_spanning_many_flag_words(hub_degree, flag_mode):
     n = 60000
     ip, ix = _star_graph(n, hub_degree, 6, hub_degree)
     assert int(ip[1] - ip[0]) == hub_degree
-    gns = GpuGns(ip, ix, None, fanouts=(5, 7), policies=(C, C), cache_size=3000, max_seeds=16)
+    gns = GpuGns(ip, ix, None, fanouts=(5, 7), policies=(C, C), cache_size=3000, max_seeds=16, flag_mode=flag_mode)
     try:
         seeds = torch.tensor([0, 5, 17, 9, 33], dtype=torch.int32)       # the hub is a seed
         full_parity(gns, cache_seed=2, epoch=0, batch_seed=3, seeds=seeds)
@@ -238,7 +241,7 @@ def test_cache_nearly_all_nodes():
         gns.close()
 
 
-def _config_parity(cfg_id, batches, device_gen="cpu"):
+def _config_parity(cfg_id, batches, device_gen="cpu", flag_mode=0):
     c = synth.CONFIGS[cfg_id]
     sd = synth.config_seeds(cfg_id)
     g = synth.make_config_graph(cfg_id, device=device_gen)
@@ -248,7 +251,7 @@ def _config_parity(cfg_id, batches, device_gen="cpu"):
     L = len(c["fanouts"])
     policies = [U] * (L - 1) + [C]
     gns = GpuGns(indptr, indices, feat, fanouts=c["fanouts"], policies=policies, cache_size=cache_size,
-                 max_seeds=c["batch"], feat_on_host=c["feat_on_host"])
+                 max_seeds=c["batch"], feat_on_host=c["feat_on_host"], flag_mode=flag_mode)
     try:
         for b in range(batches):
             seeds = synth.uniform_seed_batch(c["n"], c["batch"], sd["batch"] + b)
@@ -263,8 +266,9 @@ def test_config1_tiny_graph():
     _config_parity(1, batches=3)
 
 
-def test_config2_medium_graph():
-    _config_parity(2, batches=2)
+@pytest.mark.parametrize("flag_mode", [0, 1])
+def test_config2_medium_graph(flag_mode):
+    _config_parity(2, batches=2, flag_mode=flag_mode)
 
 
 def test_async_pipeline_on_forked_contexts():

@@ -34,7 +34,7 @@ def test_header_functions_are_exported():
 
 def test_struct_sizes_match_the_header_layout():
     assert ctypes.sizeof(B.gns_graph) == 64
-    assert ctypes.sizeof(B.gns_config) == 4 + 32 + 32 + 4 + 8 + 4 + 4
+    assert ctypes.sizeof(B.gns_config) == 4 + 32 + 32 + 4 + 8 + 4 + 4 + 4 + 4
     assert ctypes.sizeof(B.gns_block) == 72
 
 
