@@ -3,17 +3,25 @@
 
 A step is one mini-batch through the whole path: (periodic cache draw) ->
 gns_sample_blocks -> gns_gather_features (input nodes) -> gns_aggregate (input
-layer).  The workload is the medium power-law graph (1M nodes, ~20M undirected
+layer).  Default workload: the medium power-law graph (1M nodes, ~20M undirected
 edges, 128-dim fp32 features in HBM, 1% degree-proportional cache redrawn every
 20 mini-batches, fan-outs 15/10/5, batch 1024), seeded and synthetic.
 
-Prints one JSON line: whole-job mini-batches/s with inputs resident in HBM, the
-roofline figures of the dominant kernel (HIP-event timed inside the timed
-region), and the CPU oracle's rate on a bounded sample of the same batches.
+Two passes over the same K steps:
+  A  the timed region of the contract: K steps spread over --slots contexts
+     (one stream each, sharing the cache), no host synchronisation inside a
+     step -> `value`, `ms_per_step`;
+  B  the same K steps on one stream with every kernel stage bracketed by HIP
+     events -> per-stage times and the `roofline` object of the kernel that
+     takes the most time (one stream, so that its launch duration is the same
+     quantity rocprofv3 --kernel-trace reports).
+Then an untimed replay counts algorithmic bytes, and the CPU oracle is timed on
+a bounded sample of the same mini-batches.  Prints one JSON line.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 from concurrent.futures import ThreadPoolExecutor
@@ -24,6 +32,19 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 
+def profile_traffic(kernel, cfg_id):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel factors stated there), or None."""
+    path = os.path.join(ROOT, "profiles", "pmc_config%d_hbm_traffic.txt" % cfg_id)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        m = re.match(r"\s*(\S+)\s+.*traffic_bytes_per_launch=(\d+)", line)
+        if m and m.group(1) == kernel:
+            return int(m.group(2))
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -31,12 +52,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--config", type=int, default=2, help="workload id (see synth.CONFIGS)")
     ap.add_argument("--cpu-batches", type=int, default=32, help="mini-batches the CPU oracle is timed on (0: skip)")
-    ap.add_argument("--stages", action="store_true", help="add an untimed pass that times every stage")
-    ap.add_argument("--threads", type=int, default=0, help="1: one host thread per slot")
-    ap.add_argument("--flag-mode", type=int, default=0,
-                    help="0: membership flags per mini-batch (CSR-segment scan); 1: once per cache draw")
     ap.add_argument("--slots", type=int, default=4,
-                    help="mini-batches kept in flight (one context + stream each; they share the cache)")
+                    help="mini-batches kept in flight in pass A (one context + stream each; they share the cache)")
+    ap.add_argument("--flag-mode", type=int, default=0,
+                    help="0: cache-membership flags per mini-batch (CSR-segment scan); 1: once per cache draw")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference point for rocprofv3 byte counters)")
+    ap.add_argument("--skip-pass-a", action="store_true", help="profiling aid: only the single-stream pass")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported"
@@ -55,23 +77,26 @@ def main():
     n, F, batch = c["n"], c["feat"], c["batch"]
     fanouts = list(c["fanouts"])
     L = len(fanouts)
+    last = L - 1
     policies = [B.GNS_UNIFORM] * (L - 1) + [B.GNS_CACHE_ONLY]
     cache_size = int(n * c["cache_frac"])
     refresh = c.get("refresh_every", 20)
+    K, W = args.steps, args.warmup
+    total = W + K
 
-    # ---- inputs (generated on the device, resident in HBM before timing starts)
+    # ---- inputs: generated on the device, resident in HBM (or pinned host memory for the feature-heavy
+    #      workloads) before any timing starts
     g = synth.make_config_graph(cfg_id, device=dev)
-    feat = synth.node_features(n, F, sd["feat"], device=dev)
-    total = args.warmup + args.steps
+    on_host = bool(c.get("feat_on_host"))
+    feat = synth.node_features(n, F, sd["feat"], device=dev, pin=on_host)
     seeds = [synth.uniform_seed_batch(n, batch, sd["batch"] + b, device=dev) for b in range(total)]
-    deg = (g.indptr[1:] - g.indptr[:-1]).to(torch.int64)
+    off_bytes = 8 if g.indptr.dtype == torch.int64 else 4
 
-    graph = B.make_graph(g.indptr, g.indices, feat_dev=feat)
+    graph = B.make_graph(g.indptr, g.indices, feat_dev=None if on_host else feat,
+                         feat_host_pinned=feat if on_host else None)
     config = B.make_config(fanouts, policies, cache_size, batch, flag_mode=args.flag_mode)
     ws = B.alloc_workspace(graph, config, dev)
     ctx = B.gns_create(graph, config, ws)
-    last = L - 1
-    # one slot = context + stream + output buffers; slot 0 is the created context, the others are forks
     S = max(1, args.slots)
     ctxs, fork_ws = [ctx], []
     for _ in range(S - 1):
@@ -82,146 +107,133 @@ def main():
     bufs = [B.BlockBuffers(graph, config, dev) for _ in range(S)]
     x_in = [torch.empty((bufs[i].array[last].cap_src, F), dtype=torch.float32, device=dev) for i in range(S)]
     h_out = [torch.empty((bufs[i].array[last].cap_dst, F), dtype=torch.float32, device=dev) for i in range(S)]
-    blocks = bufs[0]
 
-    def step(b):
-        """One mini-batch, enqueued on its slot's stream without any host synchronisation."""
+    def refresh_cache(b):
+        torch.cuda.synchronize()                          # no batch may be in flight while the cache changes
+        B.gns_sample_cache(ctx, sd["cache"], b // refresh, streams[0])
+
+    def step(b, i):
+        """One mini-batch enqueued on slot i's stream; counts stay on the device, nothing synchronises."""
         if b % refresh == 0:
-            torch.cuda.synchronize()                      # no batch may be in flight while the cache changes
-            B.gns_sample_cache(ctx, sd["cache"], b // refresh, streams[0])
-        i = b % S
+            refresh_cache(b)
         st = streams[i]
         B.gns_sample_blocks_async(ctxs[i], sd["batch"] + b, seeds[b], bufs[i].array, st)
         B.gns_gather_features(ctxs[i], bufs[i].tensors[last]["src_nodes"], -1, x_in[i], st)
         B.gns_aggregate(ctxs[i], bufs[i].array[last], x_in[i], F, h_out[i], st)
 
-    def step_sync(b):
-        """The same mini-batch on slot 0 with host-visible counts (used for the byte accounting)."""
-        if b % refresh == 0:
-            torch.cuda.synchronize()
-            B.gns_sample_cache(ctx, sd["cache"], b // refresh, streams[0])
-        B.gns_sample_blocks(ctx, sd["batch"] + b, seeds[b], blocks.array, streams[0])
-        blk = blocks.array[last]
-        B.gns_gather_features(ctx, blocks.tensors[last]["src_nodes"], blk.num_src, x_in[0], streams[0])
-        B.gns_aggregate(ctx, blk, x_in[0], F, h_out[0], streams[0])
-
     torch.cuda.synchronize()
-    for b in range(args.warmup):
-        step(b)
+    if args.calib_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)     # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    for b in range(W):
+        step(b, b % S)
     torch.cuda.synchronize()
 
-    def run_range(lo, hi):
-        """Steps lo..hi-1.  With --threads, each slot is driven by its own host thread (kernel
-        launches are host-bound); the threads meet at every cache refresh."""
-        if not args.threads or S == 1:
-            for b in range(lo, hi):
-                step(b)
-            return
-        import threading
-        barrier = threading.Barrier(S)
+    # ---- pass A: the timed region
+    if args.skip_pass_a:
+        elapsed = float("nan")
+    else:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for b in range(W, total):
+            step(b, b % S)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
 
-        def worker(i):
-            for b in range(lo, hi):
-                if b % refresh == 0:
-                    barrier.wait()
-                    if i == 0:
-                        torch.cuda.synchronize()
-                        B.gns_sample_cache(ctx, sd["cache"], b // refresh, streams[0])
-                    barrier.wait()
-                if b % S != i:
-                    continue
-                st = streams[i]
-                B.gns_sample_blocks_async(ctxs[i], sd["batch"] + b, seeds[b], bufs[i].array, st)
-                B.gns_gather_features(ctxs[i], bufs[i].tensors[last]["src_nodes"], -1, x_in[i], st)
-                B.gns_aggregate(ctxs[i], bufs[i].array[last], x_in[i], F, h_out[i], st)
-
-        ths = [threading.Thread(target=worker, args=(i,)) for i in range(S)]
-        for t in ths:
-            t.start()
-        for t in ths:
-            t.join()
-
-    # ---- timed region: on slot 0 the input-layer sampler is bracketed by HIP events
-    dom_stage = B.GNS_STAGE_SAMPLE + last
-    B.gns_profile_begin(ctx, 1 << dom_stage, args.steps)
+    # ---- pass B: one stream, every stage bracketed by HIP events on that stream
+    stages = {"sample_layer_%d" % (L - i): B.GNS_STAGE_SAMPLE + i for i in range(L)}
+    stages.update({"finish_layer_%d" % (L - i): B.GNS_STAGE_FINISH + i for i in range(L)})
+    stages.update({"plan": B.GNS_STAGE_PLAN, "flag": B.GNS_STAGE_FLAG, "select": B.GNS_STAGE_SELECT,
+                   "gather": B.GNS_STAGE_GATHER, "aggregate": B.GNS_STAGE_AGGREGATE})
+    mask = 0
+    for sid in stages.values():
+        mask |= 1 << sid
+    B.gns_profile_begin(ctx, mask, K * (2 * L + 6))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run_range(args.warmup, total)
+    for b in range(W, total):
+        step(b, 0)
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    dom_ms, dom_launches = B.gns_profile_collect(ctx, dom_stage)
+    elapsed_b = time.perf_counter() - t0
+    stage_us, stage_launches = {}, {}
+    for name, sid in stages.items():
+        ms, cnt = B.gns_profile_collect(ctx, sid)
+        if cnt:
+            stage_us[name] = round(1e3 * ms / cnt, 2)
+            stage_launches[name] = cnt
     B.gns_profile_begin(ctx, 0, 0)
-    elapsed = t1 - t0
-    ms_per_step = 1e3 * elapsed / args.steps
 
-    # ---- untimed replay of the same steps: algorithmic bytes of the dominant kernel, shape statistics
-    off_bytes = 8 if g.indptr.dtype == torch.int64 else 4
-    alg_bytes = 0.0
-    alg_bytes_subgraph = 0.0
-    stats = dict(rows=0, scanned_entries=0, edges=0, input_nodes=0, cached_input=0, eligible=0)
-    stage_ms = {}
-    if args.stages:
-        mask = 0
-        for i in range(L):
-            mask |= (1 << (B.GNS_STAGE_SAMPLE + i)) | (1 << (B.GNS_STAGE_FINISH + i))
-        mask |= (1 << B.GNS_STAGE_GATHER) | (1 << B.GNS_STAGE_AGGREGATE)
-        B.gns_profile_begin(ctx, mask, args.steps * (2 * L + 2))
-    for b in range(args.warmup, total):
-        step_sync(b)
+    # ---- untimed replay with host-visible counts: algorithmic bytes per launch, shape statistics
+    start_all = g.indptr[:-1].to(torch.int64)
+    end_all = g.indptr[1:].to(torch.int64)
+    acc = dict(rows=0, scanned_entries=0, chunks=0, edges=0, input_nodes=0, cached_input=0, eligible=0)
+    blocks = bufs[0]
+    for b in range(W, total):
+        if b % refresh == 0:
+            refresh_cache(b)
+        B.gns_sample_blocks(ctx, sd["batch"] + b, seeds[b], blocks.array, streams[0])
         torch.cuda.synchronize()
         blk = blocks.array[last]
         v = blocks.views(last)
         rows = blk.num_dst
         dst_nodes = v["src_nodes"][:rows].to(torch.int64)
-        scanned = int(deg[dst_nodes].sum())
-        elig = int(v["row_eligible"].sum())
-        # CSR segments streamed + per-row dst id and two offsets + per-row count/eligible out
-        # + 8 B per emitted edge (id + weight) + the membership bitmap once
-        alg_bytes += scanned * 4 + rows * (4 + 2 * off_bytes + 8) + blk.num_edges * 8 + (n + 7) // 8
-        alg_bytes_subgraph += elig * 4 + rows * (4 + 2 * off_bytes + 8) + blk.num_edges * 8
-        stats["rows"] += rows
-        stats["scanned_entries"] += scanned
-        stats["edges"] += blk.num_edges
-        stats["input_nodes"] += blk.num_src
-        stats["cached_input"] += blk.num_src - rows
-        stats["eligible"] += elig
+        st_, en_ = start_all[dst_nodes], end_all[dst_nodes]
+        deg_ = en_ - st_
+        acc["rows"] += rows
+        acc["scanned_entries"] += int(deg_.sum())
+        acc["chunks"] += int(torch.where(deg_ > 0, ((en_ - 1) >> 6) - (st_ >> 6) + 1, torch.zeros_like(deg_)).sum())
+        acc["edges"] += blk.num_edges
+        acc["input_nodes"] += blk.num_src
+        acc["cached_input"] += blk.num_src - rows
+        acc["eligible"] += int(v["row_eligible"].sum())
     torch.cuda.synchronize()
-    if args.stages:
-        for i in range(L):
-            for name, base in (("sample", B.GNS_STAGE_SAMPLE), ("finish", B.GNS_STAGE_FINISH)):
-                ms, cnt = B.gns_profile_collect(ctx, base + i)
-                stage_ms["%s_layer_index_%d" % (name, i)] = round(1e3 * ms / max(cnt, 1), 2)
-        for name, st in (("gather", B.GNS_STAGE_GATHER), ("aggregate", B.GNS_STAGE_AGGREGATE)):
-            ms, cnt = B.gns_profile_collect(ctx, st)
-            stage_ms[name] = round(1e3 * ms / max(cnt, 1), 2)
-        B.gns_profile_begin(ctx, 0, 0)
-
-    for c_ in ctxs[1:]:
-        B.gns_destroy(c_)
-    achieved = (alg_bytes / args.steps) / (1e6 * dom_ms / max(dom_launches, 1))   # GB/s
+    avg = {k: v / K for k, v in acc.items()}
+    # algorithmic bytes per launch of each single-kernel stage (averages over the K steps)
+    alg = {
+        # CSR segments streamed once + the work list read + one flag word written per chunk + the bitmap once
+        "flag": avg["scanned_entries"] * 4 + avg["chunks"] * (4 + 8) + (n + 7) // 8,
+        # per row: dst id, two offsets, count + eligible out; the row's flag words; per edge: index read,
+        # two offsets of the sampled node, id + weight written
+        "select": avg["rows"] * (4 + 2 * off_bytes + 8) + avg["chunks"] * 8 + avg["edges"] * (4 + 2 * off_bytes + 8),
+        "gather": avg["input_nodes"] * (F * 4 * 2 + 4),
+        "aggregate": avg["input_nodes"] * F * 4 + avg["rows"] * (F * 4 + 4) + avg["edges"] * 8,
+    }
+    kernel_of = {"flag": "k_flag_chunks", "select": "k_select_rows", "gather": "k_gather", "aggregate": "k_aggregate"}
+    candidates = [s_ for s_ in alg if s_ in stage_us]
+    dom = max(candidates, key=lambda s_: stage_us[s_])
+    achieved = alg[dom] / (1e3 * stage_us[dom])               # bytes / us / 1e3 = GB/s
     roofline = {
-        "kernel": "k_sample_cache_only (input-layer sampler)",
+        "kernel": kernel_of[dom],
+        "stage": dom,
         "bound": "hbm",
         "achieved": round(achieved, 2),
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 5),
-        "traffic": None,
-        "avg_launch_us": round(1e3 * dom_ms / max(dom_launches, 1), 2),
-        "launches": dom_launches,
-        "algorithmic_bytes_per_launch": int(alg_bytes / args.steps),
-        "induced_subgraph_bytes_per_launch": int(alg_bytes_subgraph / args.steps),
+        "traffic": profile_traffic(kernel_of[dom], cfg_id),
+        "avg_launch_us": stage_us[dom],
+        "launches": stage_launches[dom],
+        "algorithmic_bytes_per_launch": int(alg[dom]),
+        "timed_in": "pass B (same K steps, one stream, HIP events on that stream)",
+        "other_kernels_GBps": {kernel_of[s_]: round(alg[s_] / (1e3 * stage_us[s_]), 1) for s_ in candidates if s_ != dom},
     }
+    if dom == "flag":
+        # what a layout that stores only the cached neighbors (Section 3.3's induced subgraph) would read
+        roofline["induced_subgraph_bytes_per_launch"] = int(avg["eligible"] * 4 + avg["chunks"] * 8)
 
-    # ---- CPU oracle on a bounded sample of the same batches
+    # ---- CPU oracle on a bounded sample of the same mini-batches
     cpu = None
     if args.cpu_batches > 0:
         import oracle
         ip = g.indptr.cpu().numpy()
         ix = g.indices.cpu().numpy()
-        xf = feat.cpu().numpy()
-        nb = min(args.cpu_batches, args.steps)
-        ids = list(range(args.warmup, args.warmup + nb))
+        xf = feat.numpy() if on_host else feat.cpu().numpy()
+        nb = min(args.cpu_batches, K)
+        ids = list(range(W, W + nb))
         seeds_cpu = {b: seeds[b].cpu().numpy() for b in ids}
         _, bitmap, _ = oracle.sample_cache(ip, sd["cache"], 0, cache_size)
 
@@ -242,31 +254,36 @@ def main():
                "sample": "%d of the timed mini-batches (sample+gather+aggregate, cache draw excluded), one batch per "
                          "thread; single-thread rate %.3f mini-batches/s" % (nb, single)}
 
+    for c_ in ctxs[1:]:
+        B.gns_destroy(c_)
+    B.gns_destroy(ctx)
     out = {
         "metric": "sampled mini-batches/sec (fanout %s, batch %d) + gather/aggregate HBM GB/s"
                   % ("/".join(map(str, fanouts)), batch),
-        "value": round(args.steps / elapsed, 2),
+        "value": round(K / elapsed, 2),
         "unit": "mini-batches/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(1e3 * elapsed / K, 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "i32+f32",
         "data": "synthetic",
-        "config": {"workload": "config %d: Chung-Lu graph n=%d nnz=%d gamma=%.1f, F=%d fp32 in HBM, cache %d nodes "
+        "config": {"workload": "config %d: Chung-Lu graph n=%d nnz=%d gamma=%.1f, F=%d fp32 in %s, cache %d nodes "
                                "redrawn every %d mini-batches, fanouts %s, batch %d"
-                               % (cfg_id, n, g.nnz, c["gamma"], F, cache_size, refresh, fanouts, batch),
+                               % (cfg_id, n, g.nnz, c["gamma"], F,
+                                  "pinned host memory (cached rows in HBM)" if on_host else "HBM",
+                                  cache_size, refresh, fanouts, batch),
                    "max_degree": g.max_degree, "batches_in_flight": S,
-                   "avg_per_batch": {k: round(v / args.steps, 1) for k, v in stats.items()}},
+                   "cache_flags": "per mini-batch (CSR-segment scan)" if args.flag_mode == 0 else "per cache draw",
+                   "avg_per_batch": {k: round(v, 1) for k, v in avg.items()}},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "single_stream": {"value": round(K / elapsed_b, 2), "ms_per_step": round(1e3 * elapsed_b / K, 4),
+                          "stage_us": stage_us},
     }
-    if stage_ms:
-        out["stage_us"] = stage_ms
-    B.gns_destroy(ctx)
     print(json.dumps(out))
 
 

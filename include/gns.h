@@ -226,7 +226,8 @@ gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_sr
 
 /* Stage timing for benchmarks (no part of the method).  Stages: GNS_STAGE_SAMPLE + i
  * = the sampler kernel of layer index i; GNS_STAGE_FINISH + i = the union / relabel
- * kernels of layer index i; GNS_STAGE_GATHER; GNS_STAGE_AGGREGATE.
+ * kernels of layer index i; GNS_STAGE_GATHER; GNS_STAGE_AGGREGATE; GNS_STAGE_PLAN / FLAG /
+ * SELECT = the parts of a CACHE_ONLY layer's sampler (also counted in its GNS_STAGE_SAMPLE).
  * gns_profile_begin(ctx, stage_mask, capacity) makes the following calls bracket
  * every launch of a stage whose bit is set in stage_mask with a pair of HIP events on
  * the caller's stream (at most `capacity` pairs are kept, later ones are dropped;
@@ -238,6 +239,9 @@ gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_sr
 #define GNS_STAGE_FINISH 8
 #define GNS_STAGE_GATHER 16
 #define GNS_STAGE_AGGREGATE 17
+#define GNS_STAGE_PLAN 18   /* CACHE_ONLY, GNS_FLAGS_PER_BATCH: the two work-list kernels          */
+#define GNS_STAGE_FLAG 19   /* CACHE_ONLY, GNS_FLAGS_PER_BATCH: the CSR-segment scan (one kernel)  */
+#define GNS_STAGE_SELECT 20 /* CACHE_ONLY: the per-row selection kernel                            */
 gns_status gns_profile_begin(gns_ctx* ctx, uint32_t stage_mask, int32_t capacity);
 gns_status gns_profile_collect(gns_ctx* ctx, int32_t stage, double* total_ms, int32_t* launches);
 

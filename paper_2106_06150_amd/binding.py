@@ -93,6 +93,7 @@ EXPORTED = ["gns_workspace_bytes", "gns_block_capacity", "gns_create", "gns_dest
             "gns_fork", "gns_fork_workspace_bytes"]
 
 GNS_STAGE_SAMPLE, GNS_STAGE_FINISH, GNS_STAGE_GATHER, GNS_STAGE_AGGREGATE = 0, 8, 16, 17
+GNS_STAGE_PLAN, GNS_STAGE_FLAG, GNS_STAGE_SELECT = 18, 19, 20
 
 
 class GnsError(RuntimeError):

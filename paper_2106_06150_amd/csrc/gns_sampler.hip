@@ -225,7 +225,7 @@ __global__ void __launch_bounds__(kBlock) k_plan_expand(SampleArgs a)
     }
 }
 
-constexpr int kFlagUnroll = 16;     // chunks a wave keeps in flight
+constexpr int kFlagUnroll = 32;     // chunks a wave keeps in flight
 constexpr int kFlagBatch = 64;      // work-list entries a wave fetches at once (one per lane)
 
 // kLds: the cache bitmap is first copied into dynamic LDS (rounded up to 16 bytes).
@@ -498,12 +498,17 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
 
     // CACHE_ONLY: (plan -> flag ->) select
     if (c->config.flag_mode == GNS_FLAGS_PER_BATCH) {
-        const unsigned plan_blocks = (unsigned) ((rows_max + kPlanTile - 1) / kPlanTile);
-        if (i64) hipLaunchKernelGGL((k_plan_count<int64_t>), dim3(plan_blocks), tb, 0, s, a);
-        else     hipLaunchKernelGGL((k_plan_count<int32_t>), dim3(plan_blocks), tb, 0, s, a);
-        hipLaunchKernelGGL(k_plan_expand, dim3(plan_blocks), tb, 0, s, a);
+        {
+            StageTimer t(c, GNS_STAGE_PLAN, s);
+            const unsigned plan_blocks = (unsigned) ((rows_max + kPlanTile - 1) / kPlanTile);
+            if (i64) hipLaunchKernelGGL((k_plan_count<int64_t>), dim3(plan_blocks), tb, 0, s, a);
+            else     hipLaunchKernelGGL((k_plan_count<int32_t>), dim3(plan_blocks), tb, 0, s, a);
+            hipLaunchKernelGGL(k_plan_expand, dim3(plan_blocks), tb, 0, s, a);
+        }
+        StageTimer t(c, GNS_STAGE_FLAG, s);
         launch_flag_kernel(c, a, 1, 0, s);
     }
+    StageTimer t(c, GNS_STAGE_SELECT, s);
     GNS_LAUNCH_BY_G(k_select_rows);
 #undef GNS_LAUNCH_BY_G
     return hipGetLastError();

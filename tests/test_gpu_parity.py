@@ -241,12 +241,24 @@ def test_cache_nearly_all_nodes():
         gns.close()
 
 
-def _config_parity(cfg_id, batches, device_gen="cpu", flag_mode=0):
+def _config_parity(cfg_id, batches, device_gen="cpu", flag_mode=0, check_features=True):
+    """Whole path on one of the five workloads against the oracle.  The big graphs are generated
+    on the GPU (same recipe) and copied to the host for the oracle."""
+    import time
+    t0 = time.time()
     c = synth.CONFIGS[cfg_id]
     sd = synth.config_seeds(cfg_id)
     g = synth.make_config_graph(cfg_id, device=device_gen)
     indptr, indices = g.indptr.cpu(), g.indices.cpu()
-    feat = synth.node_features(c["n"], c["feat"], sd["feat"])
+    print("cfg%d: n=%d nnz=%d max_degree=%d (generated in %.1fs)" % (cfg_id, c["n"], g.nnz, g.max_degree, time.time() - t0),
+          flush=True)
+    del g
+    feat = None
+    if check_features:
+        feat = synth.node_features(c["n"], c["feat"], sd["feat"], device=device_gen, pin=c["feat_on_host"])
+        if not c["feat_on_host"]:
+            feat = feat.cpu()
+    print("cfg%d: features ready after %.1fs" % (cfg_id, time.time() - t0), flush=True)
     cache_size = int(c["n"] * c["cache_frac"])
     L = len(c["fanouts"])
     policies = [U] * (L - 1) + [C]
@@ -256,8 +268,8 @@ def _config_parity(cfg_id, batches, device_gen="cpu", flag_mode=0):
         for b in range(batches):
             seeds = synth.uniform_seed_batch(c["n"], c["batch"], sd["batch"] + b)
             views, ref = full_parity(gns, cache_seed=sd["cache"], epoch=b, batch_seed=sd["batch"] + b, seeds=seeds)
-            print("cfg%d batch %d: rows/src/edges per layer %s" % (
-                cfg_id, b, [(r.num_dst, r.num_src, r.num_edges) for r in ref]), flush=True)
+            print("cfg%d batch %d after %.1fs: rows/src/edges per layer %s" % (
+                cfg_id, b, time.time() - t0, [(r.num_dst, r.num_src, r.num_edges) for r in ref]), flush=True)
     finally:
         gns.close()
 
@@ -324,3 +336,15 @@ def test_async_pipeline_on_forked_contexts():
         for f in forks:
             B.gns_destroy(f)
         gns.close()
+
+
+def test_config3_products_shaped_graph():
+    _config_parity(3, batches=1, device_gen="cuda")
+
+
+def test_config4_int64_offsets_and_host_features():
+    _config_parity(4, batches=1, device_gen="cuda", flag_mode=1)
+
+
+def test_config5_giant_graph():
+    _config_parity(5, batches=1, device_gen="cuda", flag_mode=0)
