@@ -86,10 +86,13 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     // per-batch scratch (every forked context has its own copy of these sections)
     L.state = take(sizeof(DeviceState) + 64);
     L.mark_bitmap = take((size_t) L.words * 8);
-    L.hash_slots = take((size_t) L.hash_cap * 8);
-    L.s_nbr = take((size_t) L.max_edges * 4);
-    L.s_w = take((size_t) L.max_edges * 4);
-    L.s_cnt = take((size_t) L.max_rows * 4);
+    L.hash_slots[0] = take((size_t) L.hash_cap * 8);
+    L.hash_slots[1] = take((size_t) L.hash_cap * 8);
+    for (int par = 0; par < 2; ++par) {
+        L.s_nbr[par] = take((size_t) L.max_edges * 4);
+        L.s_w[par] = take((size_t) L.max_edges * 4);
+        L.s_cnt[par] = take((size_t) L.max_rows * 4);
+    }
     L.sums_rows = take((size_t) (L.row_tiles + 1) * 4);
     const int64_t word_or_draw_tiles = L.word_tiles > L.draw_tiles ? L.word_tiles : L.draw_tiles;
     L.sums_words = take((size_t) (word_or_draw_tiles + 1) * 4);
@@ -138,102 +141,105 @@ static gns_status enqueue_batch(gns_ctx* c, uint64_t seed, const int32_t* seeds_
                                 gns_block* blocks, hipStream_t s)
 {
     const int nl = c->config.num_layers;
-    hipError_t e = launch_batch_begin(c, seed, seeds_dev, num_seeds, s);
+    hipError_t e = launch_batch_begin(c, seed, seeds_dev, num_seeds, c->batch_id + 1, s);
     if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "batch begin", e);
     const int32_t* dst = seeds_dev;
+    const int32_t* prev_dst = nullptr;
     for (int i = 0; i < nl; ++i) {
         {
             StageTimer t(c, GNS_STAGE_SAMPLE + i, s);
-            e = launch_sample_layer(c, i, dst, blocks[i].row_eligible, s);
+            e = launch_sample_layer(c, i, dst, blocks[i].row_eligible, prev_dst, i ? &blocks[i - 1] : nullptr, s);
         }
         if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample layer", e);
         {
             StageTimer t(c, GNS_STAGE_FINISH + i, s);
             e = launch_finish_layer(c, i, dst, &blocks[i], s);
+            if (e == hipSuccess && i == nl - 1) e = launch_relabel(c, i, dst, &blocks[i], s);
         }
         if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "finish layer", e);
+        prev_dst = dst;
         dst = blocks[i].src_nodes;
     }
-    e = hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s);
-    if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample_blocks readback", e);
     return GNS_OK;
 }
 
-static void graph_release(gns_ctx* c)
+static void graph_release(gns_ctx* c, int par)
 {
-    if (c->graph_exec) (void) hipGraphExecDestroy(c->graph_exec);
-    if (c->batch_graph) (void) hipGraphDestroy(c->batch_graph);
-    c->graph_exec = nullptr;
-    c->batch_graph = nullptr;
-    c->graph_first = nullptr;
-    c->graph_valid = false;
+    BatchGraph& g = c->bg[par];
+    if (g.exec) (void) hipGraphExecDestroy(g.exec);
+    if (g.graph) (void) hipGraphDestroy(g.graph);
+    g.exec = nullptr;
+    g.graph = nullptr;
+    g.first = nullptr;
+    g.valid = false;
 }
 
 // The batch's launch sequence does not depend on the data (grids are sized for the worst
 // case and counts stay on the device), so it is captured once per set of caller buffers and
-// replayed with hipGraphLaunch; only the first kernel's seed / seed-count arguments change.
+// hash-map parity, and replayed with hipGraphLaunch; only the first kernel's scalar arguments
+// (seed, seed count, batch id) change between replays.
 static gns_status launch_batch_graph(gns_ctx* c, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
                                      gns_block* blocks, hipStream_t s)
 {
     const int nl = c->config.num_layers;
-    bool same = c->graph_valid && c->gk_seeds == seeds_dev;
+    const int par = c->hash_parity;
+    BatchGraph& g = c->bg[par];
+    bool same = g.valid && g.seeds == seeds_dev;
     for (int i = 0; same && i < nl; ++i) {
-        const gns_block& a = c->gk_blocks[i];
+        const gns_block& a = g.blocks[i];
         const gns_block& b = blocks[i];
         same = a.indptr == b.indptr && a.indices == b.indices && a.src_nodes == b.src_nodes &&
                a.row_eligible == b.row_eligible && a.weights == b.weights;
     }
     hipError_t e;
     if (!same) {
-        graph_release(c);
+        graph_release(c, par);
         e = hipStreamBeginCapture(c->cap_stream, hipStreamCaptureModeRelaxed);
         if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "begin capture", e);
         const gns_status st = enqueue_batch(c, seed, seeds_dev, num_seeds, blocks, c->cap_stream);
-        e = hipStreamEndCapture(c->cap_stream, &c->batch_graph);
-        if (st != GNS_OK) { graph_release(c); return st; }
-        if (e != hipSuccess) { graph_release(c); return ctx_fail(c, GNS_EHIP, "end capture", e); }
-        e = hipGraphInstantiate(&c->graph_exec, c->batch_graph, nullptr, nullptr, 0);
-        if (e != hipSuccess) { graph_release(c); return ctx_fail(c, GNS_EHIP, "graph instantiate", e); }
+        e = hipStreamEndCapture(c->cap_stream, &g.graph);
+        if (st != GNS_OK) { graph_release(c, par); return st; }
+        if (e != hipSuccess) { graph_release(c, par); return ctx_fail(c, GNS_EHIP, "end capture", e); }
+        e = hipGraphInstantiate(&g.exec, g.graph, nullptr, nullptr, 0);
+        if (e != hipSuccess) { graph_release(c, par); return ctx_fail(c, GNS_EHIP, "graph instantiate", e); }
         // find the first kernel's node
         size_t count = 0;
-        e = hipGraphGetNodes(c->batch_graph, nullptr, &count);
-        if (e != hipSuccess || count == 0 || count > 256) { graph_release(c); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
+        e = hipGraphGetNodes(g.graph, nullptr, &count);
+        if (e != hipSuccess || count == 0 || count > 256) { graph_release(c, par); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
         hipGraphNode_t nodes[256];
-        e = hipGraphGetNodes(c->batch_graph, nodes, &count);
-        if (e != hipSuccess) { graph_release(c); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
-        for (size_t i = 0; i < count && !c->graph_first; ++i) {
+        e = hipGraphGetNodes(g.graph, nodes, &count);
+        if (e != hipSuccess) { graph_release(c, par); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
+        for (size_t i = 0; i < count && !g.first; ++i) {
             hipGraphNodeType type;
             if (hipGraphNodeGetType(nodes[i], &type) != hipSuccess || type != hipGraphNodeTypeKernel) continue;
             hipKernelNodeParams kp;
             if (hipGraphKernelNodeGetParams(nodes[i], &kp) != hipSuccess) continue;
-            if (kp.func == batch_first_kernel()) c->graph_first = nodes[i];
+            if (kp.func == batch_first_kernel()) g.first = nodes[i];
         }
-        if (!c->graph_first) { graph_release(c); return ctx_fail(c, GNS_EHIP, "first kernel node not found in the captured graph"); }
-        c->gk_seeds = seeds_dev;
-        for (int i = 0; i < nl; ++i) c->gk_blocks[i] = blocks[i];
-        c->graph_valid = true;
+        if (!g.first) { graph_release(c, par); return ctx_fail(c, GNS_EHIP, "first kernel node not found in the captured graph"); }
+        g.seeds = seeds_dev;
+        for (int i = 0; i < nl; ++i) g.blocks[i] = blocks[i];
+        g.valid = true;
     }
     // new scalars for this batch
     hipKernelNodeParams kp;
-    e = hipGraphKernelNodeGetParams(c->graph_first, &kp);
+    e = hipGraphKernelNodeGetParams(g.first, &kp);
     if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "get first kernel params", e);
-    c->ga_slots = ws_ptr<unsigned long long>(c, c->lay.hash_slots);
-    c->ga_cap = (size_t) c->lay.hash_cap;
-    c->ga_state = c->d_state;
+    fill_begin_args(c, seeds_dev, &c->ga_begin);
     c->ga_num_seeds = num_seeds;
     c->ga_key0 = (uint32_t) seed;
     c->ga_key1 = (uint32_t) (seed >> 32);
-    c->ga_ptrs[0] = &c->ga_slots;
-    c->ga_ptrs[1] = &c->ga_cap;
-    c->ga_ptrs[2] = &c->ga_state;
-    c->ga_ptrs[3] = &c->ga_num_seeds;
-    c->ga_ptrs[4] = &c->ga_key0;
-    c->ga_ptrs[5] = &c->ga_key1;
+    c->ga_batch_id = c->batch_id + 1;
+    c->ga_ptrs[0] = c->ga_begin.bytes;
+    c->ga_ptrs[1] = &c->ga_num_seeds;
+    c->ga_ptrs[2] = &c->ga_key0;
+    c->ga_ptrs[3] = &c->ga_key1;
+    c->ga_ptrs[4] = &c->ga_batch_id;
     kp.kernelParams = c->ga_ptrs;
     kp.extra = nullptr;
-    e = hipGraphExecKernelNodeSetParams(c->graph_exec, c->graph_first, &kp);
+    e = hipGraphExecKernelNodeSetParams(g.exec, g.first, &kp);
     if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "set first kernel params", e);
-    e = hipGraphLaunch(c->graph_exec, s);
+    e = hipGraphLaunch(g.exec, s);
     if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "graph launch", e);
     return GNS_OK;
 }
@@ -324,6 +330,8 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
     e = launch_fill_u32(reinterpret_cast<uint32_t*>(c->d_state), (sizeof(DeviceState) + 64) / 4, 0u, s);
     if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.mark_bitmap), (size_t) L.words, 0ull, s);
     if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.cache_bitmap), (size_t) L.words, 0ull, s);
+    for (int par = 0; par < 2 && e == hipSuccess; ++par)
+        e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.hash_slots[par]), (size_t) L.hash_cap, ~0ull, s);
     if (e != hipSuccess) return bail(GNS_EHIP, "workspace init", e);
     int32_t* d_info = ws_ptr<int32_t>(c, L.sums_words);   // scratch, 4 ints
     e = launch_count_nonzero_rows(c, s, d_info);
@@ -430,10 +438,9 @@ gns_status gns_fork(gns_ctx* parent, void* workspace, size_t workspace_bytes, vo
     c->prof_capacity = c->prof_count = 0;
     c->prof_mask = 0;
     c->err[0] = 0;
-    c->batch_graph = nullptr;
-    c->graph_exec = nullptr;
-    c->graph_first = nullptr;
-    c->graph_valid = false;
+    memset(c->bg, 0, sizeof(c->bg));
+    c->hash_parity = 0;
+    c->batch_id = 0;
     c->cap_stream = nullptr;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (root->cap_stream && hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking) != hipSuccess) {
@@ -443,6 +450,8 @@ gns_status gns_fork(gns_ctx* parent, void* workspace, size_t workspace_bytes, vo
     hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(DeviceState), hipHostMallocDefault);
     if (e == hipSuccess) e = launch_fill_u32(reinterpret_cast<uint32_t*>(c->d_state), (sizeof(DeviceState) + 64) / 4, 0u, s);
     if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, c->lay.mark_bitmap), (size_t) c->lay.words, 0ull, s);
+    for (int par = 0; par < 2 && e == hipSuccess; ++par)
+        e = launch_fill_u64(ws_ptr<unsigned long long>(c, c->lay.hash_slots[par]), (size_t) c->lay.hash_cap, ~0ull, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
         if (c->h_state) (void) hipHostFree(c->h_state);
@@ -458,7 +467,8 @@ gns_status gns_destroy(gns_ctx* ctx)
 {
     if (!ctx) return GNS_OK;
     profile_release(ctx);
-    graph_release(ctx);
+    graph_release(ctx, 0);
+    graph_release(ctx, 1);
     if (ctx->cap_stream) (void) hipStreamDestroy(ctx->cap_stream);
     if (ctx->h_state) (void) hipHostFree(ctx->h_state);
     delete ctx;
@@ -511,6 +521,8 @@ gns_status gns_sample_blocks_async(gns_ctx* ctx, uint64_t seed, const int32_t* s
     if (c->prof_mask == 0 && c->cap_stream) st = launch_batch_graph(c, seed, seeds_dev, num_seeds, blocks, s);
     else                                     st = enqueue_batch(c, seed, seeds_dev, num_seeds, blocks, s);
     if (st != GNS_OK) return st;
+    c->batch_id += 1;
+    c->hash_parity ^= 1;             // this batch has left the other map empty
     for (int i = 0; i < nl; ++i) {
         blocks[i].num_dst = GNS_DEVICE_COUNTS(i);
         blocks[i].num_src = -1;
@@ -524,14 +536,16 @@ gns_status gns_sample_blocks_wait(gns_ctx* ctx, gns_block* blocks, void* hip_str
     if (!ctx) return GNS_EINVAL;
     gns_ctx* c = ctx;
     if (!blocks) return ctx_fail(c, GNS_EINVAL, "null blocks");
-    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(hip_stream));
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample_blocks wait", e);
     for (int i = 0; i < c->config.num_layers; ++i) {
         blocks[i].num_dst = c->h_state->num_dst[i];
         blocks[i].num_src = c->h_state->num_dst[i + 1];
         blocks[i].num_edges = c->h_state->num_edges[i];
     }
-    if (c->h_state->bad_seed) return ctx_fail(c, GNS_EINVAL, "seeds must be distinct node ids in [0, num_nodes)");
+    if (c->batch_id != 0 && c->h_state->bad_seed == c->batch_id) return ctx_fail(c, GNS_EINVAL, "seeds must be distinct node ids in [0, num_nodes)");
     return GNS_OK;
 }
 

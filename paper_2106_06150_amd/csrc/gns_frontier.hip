@@ -15,8 +15,7 @@
 //            compacted to its CSR position
 // Sorted order comes from walking the bitmap, so the result does not depend on
 // the order in which threads ran.
-#include "gns_internal.h"
-#include "gns_device.hpp"
+#include "gns_kernels.hpp"
 
 namespace gns {
 
@@ -57,72 +56,68 @@ hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s)
 }
 
 // ---------------------------------------------------------------------------
-// First kernel of a mini-batch: empties the hash map and publishes the batch's scalars
-// (number of seeds, Philox key) in the device state, from where every later kernel reads them.
-__global__ void k_batch_clear(unsigned long long* slots, size_t cap, DeviceState* st, int32_t num_seeds,
-                              uint32_t key0, uint32_t key1)
+// First kernel of a mini-batch: publishes the batch's scalars (number of seeds, Philox key) in
+// the device state and inserts the seeds, with their local ids, into this batch's hash map.  The
+// map is already empty: the context keeps two, and every batch empties the other one for its
+// successor (see k_relabel_last).  A bad seed is reported by stamping the batch id, so no flag
+// needs resetting while other blocks may be setting it.
+struct BeginArgs {
+    unsigned long long* slots;
+    DeviceState* st;
+    const int32_t* seeds;
+    int64_t num_nodes;
+    uint32_t hmask, hshift;
+};
+
+__global__ void __launch_bounds__(kBlock) k_batch_begin(BeginArgs a, int32_t num_seeds, uint32_t key0, uint32_t key1,
+                                                        uint32_t batch_id)
 {
-    size_t i = (size_t) blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t) gridDim.x * blockDim.x;
-    if (i == 0) {
-        st->num_dst[0] = num_seeds;
-        for (int l = 0; l < GNS_MAX_LAYERS; ++l) { st->num_edges[l] = 0; st->num_dst[l + 1] = 0; }
-        st->bad_seed = 0;
-        st->key0 = key0;
-        st->key1 = key1;
+    const int64_t t = (int64_t) blockIdx.x * blockDim.x + threadIdx.x;
+    if (t == 0) {
+        a.st->num_dst[0] = num_seeds;
+        for (int l = 0; l < GNS_MAX_LAYERS; ++l) { a.st->num_edges[l] = 0; a.st->num_dst[l + 1] = 0; }
+        a.st->key0 = key0;
+        a.st->key1 = key1;
     }
-    for (; i < cap; i += stride) slots[i] = kEmptySlot;
+    for (int64_t q = t; q < num_seeds; q += (int64_t) gridDim.x * blockDim.x) {
+        const int32_t u = a.seeds[q];
+        const bool ok = u >= 0 && (int64_t) u < a.num_nodes &&
+                        hash_insert(a.slots, a.hmask, a.hshift, (uint32_t) u, (uint32_t) q);
+        if (!ok) a.st->bad_seed = batch_id;
+    }
 }
 
-const void* batch_first_kernel() { return reinterpret_cast<const void*>(&k_batch_clear); }
+const void* batch_first_kernel() { return reinterpret_cast<const void*>(&k_batch_begin); }
 
-__global__ void k_seed_insert(unsigned long long* slots, uint32_t mask, uint32_t shift, const int32_t* seeds,
-                              int64_t n, DeviceState* st)
-{
-    const int32_t i = (int32_t) (blockIdx.x * blockDim.x + threadIdx.x);
-    if (i >= st->num_dst[0]) return;
-    const int32_t u = seeds[i];
-    if (u < 0 || (int64_t) u >= n) { st->bad_seed = 1; return; }
-    if (!hash_insert(slots, mask, shift, (uint32_t) u, (uint32_t) i)) st->bad_seed = 1;
-}
+static inline unsigned long long* batch_hash(gns_ctx* c) { return ws_ptr<unsigned long long>(c, c->lay.hash_slots[c->hash_parity]); }
 
-hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, hipStream_t s)
+void fill_begin_args(gns_ctx* c, const int32_t* seeds, BeginArgsHost* out)
 {
     const Layout& L = c->lay;
-    unsigned long long* slots = ws_ptr<unsigned long long>(c, L.hash_slots);
-    hipLaunchKernelGGL(k_batch_clear, dim3(fill_grid(L.hash_cap)), dim3(kBlock), 0, s, slots, (size_t) L.hash_cap,
-                       c->d_state, num_seeds, (uint32_t) seed, (uint32_t) (seed >> 32));
-    const uint32_t mask = L.hash_cap - 1;
-    const uint32_t shift = 32u - (uint32_t) __builtin_ctz(L.hash_cap);
-    const int32_t max_seeds = c->config.max_seeds;      // the grid covers the largest batch; the count is on the device
-    hipLaunchKernelGGL(k_seed_insert, dim3((max_seeds + kBlock - 1) / kBlock), dim3(kBlock), 0, s, slots, mask, shift,
-                       seeds, c->graph.num_nodes, c->d_state);
+    BeginArgs* a = reinterpret_cast<BeginArgs*>(out->bytes);
+    static_assert(sizeof(BeginArgs) <= sizeof(out->bytes), "BeginArgsHost too small");
+    a->slots = batch_hash(c);
+    a->st = c->d_state;
+    a->seeds = seeds;
+    a->num_nodes = c->graph.num_nodes;
+    a->hmask = L.hash_cap - 1;
+    a->hshift = 32u - (uint32_t) __builtin_ctz(L.hash_cap);
+}
+
+hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, uint32_t batch_id,
+                              hipStream_t s)
+{
+    BeginArgsHost h;
+    fill_begin_args(c, seeds, &h);
+    const BeginArgs a = *reinterpret_cast<const BeginArgs*>(h.bytes);
+    // the grid is sized for the largest batch: the same launch serves every replay
+    const unsigned grid = (unsigned) ((c->config.max_seeds + kBlock - 1) / kBlock);
+    hipLaunchKernelGGL(k_batch_begin, dim3(grid), dim3(kBlock), 0, s, a, num_seeds, (uint32_t) seed,
+                       (uint32_t) (seed >> 32), batch_id);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
-struct FinishArgs {
-    DeviceState* st;
-    int layer_index;
-    int fanout;
-    const int32_t* dst_nodes;      // [R]
-    const int32_t* s_nbr;          // [R x fanout]
-    const float* s_w;              // [R x fanout]
-    const int32_t* s_cnt;          // [R]
-    uint64_t* mark;                // [words]
-    int64_t words;
-    unsigned long long* slots;
-    uint32_t hmask, hshift;
-    int32_t* sums_rows;            // [row_tiles + 1]
-    int32_t* sums_marks;           // [mark_tiles + 1]
-    int32_t row_tiles_max;         // grid split point: blocks [0, row_tiles_max) work on rows
-    int32_t mark_tiles;            // tiles of kMarkTile bitmap words
-    int32_t* indptr;               // block outputs
-    int32_t* indices;
-    float* weights;
-    int32_t* src_nodes;
-};
-
 __global__ void __launch_bounds__(kBlock) k_finish_phase1(FinishArgs a)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
@@ -223,38 +218,21 @@ __global__ void __launch_bounds__(kBlock) k_finish_phase3(FinishArgs a)
     }
 }
 
-__global__ void __launch_bounds__(kBlock) k_relabel(FinishArgs a, int64_t max_slots)
-{
-    const int32_t R = a.st->num_dst[a.layer_index];
-    const int64_t limit = (int64_t) R * a.fanout;
-    int64_t t = (int64_t) blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t) gridDim.x * blockDim.x;
-    for (; t < limit && t < max_slots; t += stride) {
-        const int32_t row = (int32_t) (t / a.fanout);
-        const int32_t s = (int32_t) (t - (int64_t) row * a.fanout);
-        if (s < a.s_cnt[row]) {
-            const int32_t u = a.s_nbr[t];
-            const int32_t o = a.indptr[row] + s;
-            a.indices[o] = hash_lookup(a.slots, a.hmask, a.hshift, (uint32_t) u);
-            a.weights[o] = a.s_w[t];
-        }
-    }
-}
-
-hipError_t launch_finish_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s)
+void fill_finish_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, const gns_block* blk, FinishArgs* out)
 {
     const Layout& L = c->lay;
-    FinishArgs a;
+    FinishArgs& a = *out;
+    const int par = layer_index & 1;                 // sampler scratch is double-buffered by layer parity
     a.st = c->d_state;
     a.layer_index = layer_index;
     a.fanout = c->config.fanout[layer_index];
     a.dst_nodes = dst_nodes;
-    a.s_nbr = ws_ptr<int32_t>(c, L.s_nbr);
-    a.s_w = ws_ptr<float>(c, L.s_w);
-    a.s_cnt = ws_ptr<int32_t>(c, L.s_cnt);
+    a.s_nbr = ws_ptr<int32_t>(c, L.s_nbr[par]);
+    a.s_w = ws_ptr<float>(c, L.s_w[par]);
+    a.s_cnt = ws_ptr<int32_t>(c, L.s_cnt[par]);
     a.mark = ws_ptr<uint64_t>(c, L.mark_bitmap);
     a.words = L.words;
-    a.slots = ws_ptr<unsigned long long>(c, L.hash_slots);
+    a.slots = batch_hash(c);
     a.hmask = L.hash_cap - 1;
     a.hshift = 32u - (uint32_t) __builtin_ctz(L.hash_cap);
     a.sums_rows = ws_ptr<int32_t>(c, L.sums_rows);
@@ -265,15 +243,48 @@ hipError_t launch_finish_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
     a.indices = blk->indices;
     a.weights = blk->weights;
     a.src_nodes = blk->src_nodes;
+    a.max_slots = L.rows[layer_index] * (int64_t) a.fanout;
+}
 
-    const unsigned grid = (unsigned) (a.row_tiles_max + a.mark_tiles);
-    hipLaunchKernelGGL(k_finish_phase1, dim3(grid), dim3(kBlock), 0, s, a);
-    hipLaunchKernelGGL(k_finish_phase3, dim3(grid), dim3(kBlock), 0, s, a);
-    const int64_t max_slots = L.rows[layer_index] * (int64_t) a.fanout;
+int relabel_grid(const gns_ctx* c, int layer_index)
+{
+    const int64_t max_slots = c->lay.rows[layer_index] * (int64_t) c->config.fanout[layer_index];
     int64_t rb = (max_slots + kBlock - 1) / kBlock;
     if (rb > (int64_t) c->num_cus * 16) rb = (int64_t) c->num_cus * 16;
     if (rb < 1) rb = 1;
-    hipLaunchKernelGGL(k_relabel, dim3((unsigned) rb), dim3(kBlock), 0, s, a, max_slots);
+    return (int) rb;
+}
+
+// Phases 1 and 3 of a layer (the relabel rides with the next layer's first kernel).
+hipError_t launch_finish_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s)
+{
+    FinishArgs a;
+    fill_finish_args(c, layer_index, dst_nodes, blk, &a);
+    const unsigned grid = (unsigned) (a.row_tiles_max + a.mark_tiles);
+    hipLaunchKernelGGL(k_finish_phase1, dim3(grid), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL(k_finish_phase3, dim3(grid), dim3(kBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+// The last layer's relabel has no following sampler to ride with; it also leaves the context's
+// other hash map empty for the next mini-batch (nothing in this batch touches that map).
+__global__ void __launch_bounds__(kBlock) k_relabel_last(FinishArgs a, unsigned long long* other_slots, size_t cap)
+{
+    relabel_body(a, blockIdx.x, gridDim.x);
+    size_t i = (size_t) blockIdx.x * kBlock + threadIdx.x;
+    const size_t stride = (size_t) gridDim.x * kBlock;
+    for (; i < cap; i += stride) other_slots[i] = kEmptySlot;
+}
+
+hipError_t launch_relabel(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s)
+{
+    FinishArgs a;
+    fill_finish_args(c, layer_index, dst_nodes, blk, &a);
+    unsigned long long* other = ws_ptr<unsigned long long>(c, c->lay.hash_slots[c->hash_parity ^ 1]);
+    unsigned grid = (unsigned) relabel_grid(c, layer_index);
+    const unsigned fill = fill_grid(c->lay.hash_cap);
+    if (grid < fill) grid = fill;
+    hipLaunchKernelGGL(k_relabel_last, dim3(grid), dim3(kBlock), 0, s, a, other, (size_t) c->lay.hash_cap);
     return hipGetLastError();
 }
 

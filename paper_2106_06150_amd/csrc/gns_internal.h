@@ -15,7 +15,8 @@ struct DeviceState {
     int32_t num_dst[GNS_MAX_LAYERS + 1];  // rows of layer index i (num_dst[i+1] = num_src of layer i)
     int32_t num_edges[GNS_MAX_LAYERS];
     uint32_t key0, key1;                  // Philox key of the current batch (lo32(seed), hi32(seed))
-    int32_t bad_seed;                     // set if a seed was out of range or repeated
+    uint32_t bad_seed;                    // id of the last batch that had a seed out of range or repeated
+    int32_t pad0;
     int32_t chunk_distinct;               // cache draw: first occurrences found in the current chunk
     int32_t plan_chunks;                  // CACHE_ONLY sampler: aligned chunks in the current work list
     unsigned long long cut_draw;          // cache draw: stream index of the draw that completed the cache
@@ -27,9 +28,10 @@ struct Layout {
     // cache-draw scratch
     size_t draw_keys, draw_vals, draw_node, draw_slot;
     // frontier structures
-    size_t mark_bitmap, hash_slots;
+    size_t mark_bitmap;
+    size_t hash_slots[2];     // consecutive batches alternate: each one leaves the other map empty for the next
     // per-layer sampler scratch (fixed stride fanout)
-    size_t s_nbr, s_w, s_cnt;
+    size_t s_nbr[2], s_w[2], s_cnt[2];     // double-buffered by layer parity
     // CACHE_ONLY sampler: per-row chunk counts, chunk work list, CSR-aligned membership flags
     size_t plan_cnt, plan_g0, plan_desc, edge_flags;
     int64_t max_chunks;
@@ -56,6 +58,19 @@ struct Layout {
 }  // namespace gns
 
 namespace gns {
+// Opaque host-side storage for the first kernel's argument block (filled by fill_begin_args).
+struct BeginArgsHost {
+    alignas(8) unsigned char bytes[64];
+};
+// One captured launch sequence (there is one per hash-map parity).
+struct BatchGraph {
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+    hipGraphNode_t first;            // the k_batch_begin node
+    bool valid;
+    const int32_t* seeds;            // capture key: seeds pointer and block buffers
+    gns_block blocks[GNS_MAX_LAYERS];
+};
 struct ProfileRecord {
     int32_t stage;
     hipEvent_t start, stop;
@@ -80,19 +95,14 @@ struct gns_ctx {
     // The launch sequence of one mini-batch, captured once per (seeds pointer, block buffers) and
     // replayed; only the first kernel's arguments (seed, number of seeds) change between replays.
     hipStream_t cap_stream;          // used for capture only, never for execution
-    hipGraph_t batch_graph;
-    hipGraphExec_t graph_exec;
-    hipGraphNode_t graph_first;      // the k_batch_clear node
-    bool graph_valid;
-    const int32_t* gk_seeds;         // capture key
-    gns_block gk_blocks[GNS_MAX_LAYERS];
+    gns::BatchGraph bg[2];
+    int hash_parity;                 // which hash map the next mini-batch uses
+    uint32_t batch_id;               // id of the last mini-batch enqueued on this context (from 1)
     // argument storage of the first kernel (pointed to by the node's parameter list)
-    unsigned long long* ga_slots;
-    size_t ga_cap;
-    gns::DeviceState* ga_state;
+    gns::BeginArgsHost ga_begin;
     int32_t ga_num_seeds;
-    uint32_t ga_key0, ga_key1;
-    void* ga_ptrs[6];
+    uint32_t ga_key0, ga_key1, ga_batch_id;
+    void* ga_ptrs[5];
     // optional stage timing (benchmarks only)
     uint32_t prof_mask;
     int32_t prof_capacity;
@@ -134,13 +144,17 @@ hipError_t launch_count_nonzero_rows(gns_ctx* c, hipStream_t s, int32_t* d_out);
 gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream_t s);
 
 // gns_sampler.hip
-hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes,
-                               int32_t* row_eligible, hipStream_t s);
+// prev_dst / prev_blk: the previous layer, whose relabel shares this layer's first launch (null for layer index 0)
+hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, int32_t* row_eligible,
+                               const int32_t* prev_dst, const gns_block* prev_blk, hipStream_t s);
 hipError_t launch_flag_all_entries(gns_ctx* c, hipStream_t s);
 
 // gns_frontier.hip
-hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, hipStream_t s);
+hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, uint32_t batch_id,
+                              hipStream_t s);
 const void* batch_first_kernel();
+void fill_begin_args(gns_ctx* c, const int32_t* seeds, BeginArgsHost* out);
+hipError_t launch_relabel(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s);
 hipError_t launch_finish_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s);
 hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);

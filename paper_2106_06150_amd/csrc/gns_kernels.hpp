@@ -1,0 +1,55 @@
+// Kernel argument blocks and device bodies shared between the sampler and the frontier kernels.
+#pragma once
+#include "gns_internal.h"
+#include "gns_device.hpp"
+
+namespace gns {
+
+struct FinishArgs {
+    DeviceState* st;
+    int layer_index;
+    int fanout;
+    const int32_t* dst_nodes;      // [R]
+    const int32_t* s_nbr;          // [R x fanout]
+    const float* s_w;              // [R x fanout]
+    const int32_t* s_cnt;          // [R]
+    uint64_t* mark;                // [words]
+    int64_t words;
+    unsigned long long* slots;
+    uint32_t hmask, hshift;
+    int32_t* sums_rows;            // [row_tiles + 1]
+    int32_t* sums_marks;           // [mark_tiles + 1]
+    int32_t row_tiles_max;         // grid split point: blocks [0, row_tiles_max) work on rows
+    int32_t mark_tiles;            // tiles of kMarkTile bitmap words
+    int32_t* indptr;               // block outputs
+    int32_t* indices;
+    float* weights;
+    int32_t* src_nodes;
+    int64_t max_slots;             // worst-case rows * fanout of this layer
+};
+
+// Relabel: every sampled edge of a finished layer looks its neighbor's local id up in the batch's
+// hash map and is compacted to its CSR position.  `block` of `nblocks` blocks of kBlock threads.
+// It only needs that layer's phase 3, so it shares a launch with the next layer's first kernel.
+__device__ __forceinline__ void relabel_body(const FinishArgs& a, int64_t block, int64_t nblocks)
+{
+    const int32_t R = a.st->num_dst[a.layer_index];
+    const int64_t limit = (int64_t) R * a.fanout;
+    int64_t t = block * kBlock + threadIdx.x;
+    const int64_t stride = nblocks * kBlock;
+    for (; t < limit && t < a.max_slots; t += stride) {
+        const int32_t row = (int32_t) (t / a.fanout);
+        const int32_t s = (int32_t) (t - (int64_t) row * a.fanout);
+        if (s < a.s_cnt[row]) {
+            const int32_t u = a.s_nbr[t];
+            const int32_t o = a.indptr[row] + s;
+            a.indices[o] = hash_lookup(a.slots, a.hmask, a.hshift, (uint32_t) u);
+            a.weights[o] = a.s_w[t];
+        }
+    }
+}
+
+void fill_finish_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, const gns_block* blk, FinishArgs* out);
+int relabel_grid(const gns_ctx* c, int layer_index);
+
+}  // namespace gns

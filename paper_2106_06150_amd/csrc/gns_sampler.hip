@@ -16,8 +16,7 @@
 // i < s_cnt[r], row_eligible[r]; every emitted id that has no local id yet
 // (it is not a dst node of this layer) also sets its bit in the node-indexed
 // mark bitmap that the frontier stage turns into the src list.
-#include "gns_internal.h"
-#include "gns_device.hpp"
+#include "gns_kernels.hpp"
 
 namespace gns {
 
@@ -94,16 +93,20 @@ __device__ __forceinline__ void mark_if_new(const SampleArgs& a, uint32_t u)
 // ---------------------------------------------------------------------------
 // UNIFORM: G lanes per row, rows assigned round-robin to groups.
 template <typename OffT, int G>
-__global__ void __launch_bounds__(kBlock) k_sample_uniform(SampleArgs a)
+__global__ void __launch_bounds__(kBlock) k_sample_uniform(SampleArgs a, FinishArgs prev, int relabel_blocks)
 {
+    // the first relabel_blocks blocks finish the previous layer's block instead (see relabel_body)
+    if ((int) blockIdx.x < relabel_blocks) { relabel_body(prev, blockIdx.x, relabel_blocks); return; }
+    const int64_t block = (int64_t) blockIdx.x - relabel_blocks;
+    const int64_t nblocks = (int64_t) gridDim.x - relabel_blocks;
     const int32_t R = a.st->num_dst[a.layer_index];
     const int k = a.fanout;
     constexpr int kRowsPerWave = kWave / G;
     // The loop bounds live in scalar registers (readfirstlane) so that the whole wave
     // provably iterates together: the draw below exchanges data between lanes.
-    const int64_t wave_global = (int64_t) blockIdx.x * (kBlock / kWave) +
+    const int64_t wave_global = block * (kBlock / kWave) +
                                 __builtin_amdgcn_readfirstlane((int) (threadIdx.x >> 6));
-    const int64_t num_waves = (int64_t) gridDim.x * (kBlock / kWave);
+    const int64_t num_waves = nblocks * (kBlock / kWave);
     for (int64_t row0 = wave_global * kRowsPerWave; row0 < R; row0 += num_waves * kRowsPerWave) {
         const int lane = opaque_lane_id();
         const int s = lane & (G - 1);
@@ -175,12 +178,14 @@ __device__ __forceinline__ int32_t chunks_touched(int64_t start, int64_t end)
 constexpr int kPlanTile = kBlock;
 
 template <typename OffT>
-__global__ void __launch_bounds__(kBlock) k_plan_count(SampleArgs a)
+__global__ void __launch_bounds__(kBlock) k_plan_count(SampleArgs a, FinishArgs prev, int relabel_blocks)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
+    if ((int) blockIdx.x < relabel_blocks) { relabel_body(prev, blockIdx.x, relabel_blocks); return; }
+    const int64_t tile = (int64_t) blockIdx.x - relabel_blocks;
     const int32_t R = a.st->num_dst[a.layer_index];
-    const int64_t r = (int64_t) blockIdx.x * kPlanTile + threadIdx.x;
-    if ((int64_t) blockIdx.x * kPlanTile >= R) return;
+    const int64_t r = tile * kPlanTile + threadIdx.x;
+    if (tile * kPlanTile >= R) return;
     int32_t c = 0;
     if (r < R) {
         int64_t start, end;
@@ -190,7 +195,7 @@ __global__ void __launch_bounds__(kBlock) k_plan_count(SampleArgs a)
         a.plan_g0[r] = (int32_t) (start >> 6);
     }
     const int32_t sum = block_sum(c, smem);
-    if (threadIdx.x == 0) a.plan_sums[blockIdx.x] = sum;
+    if (threadIdx.x == 0) a.plan_sums[tile] = sum;
 }
 
 __global__ void __launch_bounds__(kBlock) k_plan_expand(SampleArgs a)
@@ -302,14 +307,17 @@ __device__ __forceinline__ int32_t group_inclusive_scan(int32_t v, int s)
 }
 
 template <typename OffT, int G>
-__global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a)
+__global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs prev, int relabel_blocks)
 {
+    if ((int) blockIdx.x < relabel_blocks) { relabel_body(prev, blockIdx.x, relabel_blocks); return; }
+    const int64_t block = (int64_t) blockIdx.x - relabel_blocks;
+    const int64_t nblocks = (int64_t) gridDim.x - relabel_blocks;
     const int32_t R = a.st->num_dst[a.layer_index];
     const int k = a.fanout;
     constexpr int kRowsPerWave = kWave / G;
-    const int64_t wave_global = (int64_t) blockIdx.x * (kBlock / kWave) +
+    const int64_t wave_global = block * (kBlock / kWave) +
                                 __builtin_amdgcn_readfirstlane((int) (threadIdx.x >> 6));
-    const int64_t num_waves = (int64_t) gridDim.x * (kBlock / kWave);
+    const int64_t num_waves = nblocks * (kBlock / kWave);
     for (int64_t row0 = wave_global * kRowsPerWave; row0 < R; row0 += num_waves * kRowsPerWave) {
         const int lane = opaque_lane_id();
         const int s = lane & (G - 1);
@@ -443,12 +451,13 @@ static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nod
     a.cache_bitmap = ws_ptr<uint64_t>(c, L.cache_bitmap);
     a.cache_prefix = ws_ptr<int32_t>(c, L.cache_prefix);
     a.cache_size = c->config.cache_size;
-    a.s_nbr = ws_ptr<int32_t>(c, L.s_nbr);
-    a.s_w = ws_ptr<float>(c, L.s_w);
-    a.s_cnt = ws_ptr<int32_t>(c, L.s_cnt);
+    const int par = layer_index & 1;     // double-buffered: the previous layer's relabel may still read the other half
+    a.s_nbr = ws_ptr<int32_t>(c, L.s_nbr[par]);
+    a.s_w = ws_ptr<float>(c, L.s_w[par]);
+    a.s_cnt = ws_ptr<int32_t>(c, L.s_cnt[par]);
     a.row_eligible = row_eligible;
     a.mark = ws_ptr<uint64_t>(c, L.mark_bitmap);
-    a.slots = ws_ptr<unsigned long long>(c, L.hash_slots);
+    a.slots = ws_ptr<unsigned long long>(c, L.hash_slots[c->hash_parity]);
     a.hmask = L.hash_cap - 1;
     a.hshift = 32u - (uint32_t) __builtin_ctz(L.hash_cap);
     a.num_entries = c->graph.num_entries;
@@ -460,12 +469,21 @@ static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nod
     a.bitmap_words = L.words;
 }
 
-hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes,
-                               int32_t* row_eligible, hipStream_t s)
+hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, int32_t* row_eligible,
+                               const int32_t* prev_dst, const gns_block* prev_blk, hipStream_t s)
 {
     const Layout& L = c->lay;
     SampleArgs a;
     fill_sample_args(c, layer_index, dst_nodes, row_eligible, &a);
+
+    // The previous layer's relabel rides in front of this layer's first kernel: both only need
+    // that layer's phase 3, and they touch disjoint memory (sampler scratch alternates by layer).
+    FinishArgs prev = {};
+    int rl = 0;
+    if (prev_blk) {
+        fill_finish_args(c, layer_index - 1, prev_dst, prev_blk, &prev);
+        rl = relabel_grid(c, layer_index - 1);
+    }
 
     const int64_t rows_max = L.rows[layer_index];
     const bool i64 = c->graph.indptr_is_i64 != 0;
@@ -475,24 +493,25 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
     const int64_t cap = (int64_t) c->num_cus * 8;
     if (row_blocks > cap) row_blocks = cap;
     if (row_blocks < 1) row_blocks = 1;
-    const dim3 rb((unsigned) row_blocks), tb(kBlock);
+    const dim3 tb(kBlock);
 
-#define GNS_LAUNCH_BY_G(KERNEL)                                                                              \
+#define GNS_LAUNCH_BY_G(KERNEL, RL)                                                                          \
     do {                                                                                                     \
+        const dim3 rb((unsigned) (row_blocks + (RL)));                                                       \
         if (G == 8) {                                                                                        \
-            if (i64) hipLaunchKernelGGL((KERNEL<int64_t, 8>), rb, tb, 0, s, a);                              \
-            else     hipLaunchKernelGGL((KERNEL<int32_t, 8>), rb, tb, 0, s, a);                              \
+            if (i64) hipLaunchKernelGGL((KERNEL<int64_t, 8>), rb, tb, 0, s, a, prev, (RL));                  \
+            else     hipLaunchKernelGGL((KERNEL<int32_t, 8>), rb, tb, 0, s, a, prev, (RL));                  \
         } else if (G == 16) {                                                                                \
-            if (i64) hipLaunchKernelGGL((KERNEL<int64_t, 16>), rb, tb, 0, s, a);                             \
-            else     hipLaunchKernelGGL((KERNEL<int32_t, 16>), rb, tb, 0, s, a);                             \
+            if (i64) hipLaunchKernelGGL((KERNEL<int64_t, 16>), rb, tb, 0, s, a, prev, (RL));                 \
+            else     hipLaunchKernelGGL((KERNEL<int32_t, 16>), rb, tb, 0, s, a, prev, (RL));                 \
         } else {                                                                                             \
-            if (i64) hipLaunchKernelGGL((KERNEL<int64_t, 64>), rb, tb, 0, s, a);                             \
-            else     hipLaunchKernelGGL((KERNEL<int32_t, 64>), rb, tb, 0, s, a);                             \
+            if (i64) hipLaunchKernelGGL((KERNEL<int64_t, 64>), rb, tb, 0, s, a, prev, (RL));                 \
+            else     hipLaunchKernelGGL((KERNEL<int32_t, 64>), rb, tb, 0, s, a, prev, (RL));                 \
         }                                                                                                    \
     } while (0)
 
     if (c->config.policy[layer_index] == GNS_UNIFORM) {
-        GNS_LAUNCH_BY_G(k_sample_uniform);
+        GNS_LAUNCH_BY_G(k_sample_uniform, rl);
         return hipGetLastError();
     }
 
@@ -501,15 +520,16 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
         {
             StageTimer t(c, GNS_STAGE_PLAN, s);
             const unsigned plan_blocks = (unsigned) ((rows_max + kPlanTile - 1) / kPlanTile);
-            if (i64) hipLaunchKernelGGL((k_plan_count<int64_t>), dim3(plan_blocks), tb, 0, s, a);
-            else     hipLaunchKernelGGL((k_plan_count<int32_t>), dim3(plan_blocks), tb, 0, s, a);
+            if (i64) hipLaunchKernelGGL((k_plan_count<int64_t>), dim3(plan_blocks + (unsigned) rl), tb, 0, s, a, prev, rl);
+            else     hipLaunchKernelGGL((k_plan_count<int32_t>), dim3(plan_blocks + (unsigned) rl), tb, 0, s, a, prev, rl);
             hipLaunchKernelGGL(k_plan_expand, dim3(plan_blocks), tb, 0, s, a);
         }
+        rl = 0;                          // done with the plan kernel
         StageTimer t(c, GNS_STAGE_FLAG, s);
         launch_flag_kernel(c, a, 1, 0, s);
     }
     StageTimer t(c, GNS_STAGE_SELECT, s);
-    GNS_LAUNCH_BY_G(k_select_rows);
+    GNS_LAUNCH_BY_G(k_select_rows, rl);
 #undef GNS_LAUNCH_BY_G
     return hipGetLastError();
 }

@@ -241,11 +241,22 @@ def test_cache_nearly_all_nodes():
         gns.close()
 
 
+def _release_cached_memory():
+    """Hand torch's cached device and pinned-host blocks back: the giant workloads need tens of
+    GB of each, and blocks cached for an earlier test's shapes would be counted twice."""
+    import gc
+    gc.collect()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    torch._C._host_emptyCache()
+
+
 def _config_parity(cfg_id, batches, device_gen="cpu", flag_mode=0, check_features=True):
     """Whole path on one of the five workloads against the oracle.  The big graphs are generated
     on the GPU (same recipe) and copied to the host for the oracle."""
     import time
     t0 = time.time()
+    _release_cached_memory()
     c = synth.CONFIGS[cfg_id]
     sd = synth.config_seeds(cfg_id)
     g = synth.make_config_graph(cfg_id, device=device_gen)
@@ -265,13 +276,22 @@ def _config_parity(cfg_id, batches, device_gen="cpu", flag_mode=0, check_feature
     gns = GpuGns(indptr, indices, feat, fanouts=c["fanouts"], policies=policies, cache_size=cache_size,
                  max_seeds=c["batch"], feat_on_host=c["feat_on_host"], flag_mode=flag_mode)
     try:
+        epoch = None
+        if "split" in c:                      # batches of one shuffled epoch over the training split
+            split = synth.training_split(c["n"], c["split"], sd["split"])
+            epoch = synth.epoch_batches(split, c["batch"], sd["split"] + 1)
         for b in range(batches):
-            seeds = synth.uniform_seed_batch(c["n"], c["batch"], sd["batch"] + b)
+            if epoch is not None:
+                seeds = epoch[-1] if b == batches - 1 else epoch[b]      # the last one is the ragged tail
+            else:
+                seeds = synth.uniform_seed_batch(c["n"], c["batch"], sd["batch"] + b)
             views, ref = full_parity(gns, cache_seed=sd["cache"], epoch=b, batch_seed=sd["batch"] + b, seeds=seeds)
             print("cfg%d batch %d after %.1fs: rows/src/edges per layer %s" % (
                 cfg_id, b, time.time() - t0, [(r.num_dst, r.num_src, r.num_edges) for r in ref]), flush=True)
     finally:
         gns.close()
+        del gns, feat, indptr, indices
+        _release_cached_memory()
 
 
 def test_config1_tiny_graph():
@@ -339,7 +359,7 @@ def test_async_pipeline_on_forked_contexts():
 
 
 def test_config3_products_shaped_graph():
-    _config_parity(3, batches=1, device_gen="cuda")
+    _config_parity(3, batches=2, device_gen="cuda")
 
 
 def test_config4_int64_offsets_and_host_features():
@@ -347,4 +367,4 @@ def test_config4_int64_offsets_and_host_features():
 
 
 def test_config5_giant_graph():
-    _config_parity(5, batches=1, device_gen="cuda", flag_mode=0)
+    _config_parity(5, batches=2, device_gen="cuda", flag_mode=0)
