@@ -233,7 +233,44 @@ __global__ void __launch_bounds__(kBlock) k_plan_expand(SampleArgs a)
 constexpr int kFlagUnroll = 32;     // chunks a wave keeps in flight
 constexpr int kFlagBatch = 64;      // work-list entries a wave fetches at once (one per lane)
 
+// Membership words of kFlagUnroll chunks, chunk ids in lanes sub .. sub+kFlagUnroll-1 of my_chunk
+// (every one a valid chunk id).  Lane l tests entry l of each chunk; the ballot of chunk sub+i
+// lands in lane sub+i of (*lo, *hi).  Three passes over the unrolled set -- all index loads, all
+// bitmap reads, all tests -- so that the loads of the whole set are in flight together.
+//   kCareful: the set may hold the last chunk of the entry array, whose tail lanes lie beyond
+//   num_entries; those lanes re-read the last entry and are masked out of the ballot.
+template <bool kLds, bool kCareful>
+__device__ __forceinline__ void flag_chunk_set(const SampleArgs& a, const uint32_t* lds32, int32_t my_chunk, int sub,
+                                               int lane, uint32_t* lo, uint32_t* hi)
+{
+    const int64_t last_chunk = (a.num_entries - 1) >> 6;
+    const int last_lanes = (int) (a.num_entries - (last_chunk << 6));          // 1..64 entries in the last chunk
+    const int lane_clamped = lane < last_lanes ? lane : last_lanes - 1;
+    const uint64_t last_mask = last_lanes == 64 ? ~0ull : ((1ull << last_lanes) - 1ull);
+    uint32_t u[kFlagUnroll];
+#pragma unroll
+    for (int i = 0; i < kFlagUnroll; ++i) {
+        const int32_t g = __builtin_amdgcn_readlane(my_chunk, sub + i);
+        const int32_t* row = a.indices + ((int64_t) g << 6);                   // wave-uniform base
+        const int off = (kCareful && g == last_chunk) ? lane_clamped : lane;
+        u[i] = (uint32_t) row[off];
+    }
+    uint32_t w[kFlagUnroll];
+#pragma unroll
+    for (int i = 0; i < kFlagUnroll; ++i) {
+        if (kLds) w[i] = lds32[u[i] >> 5];
+        else      w[i] = reinterpret_cast<const uint32_t*>(a.cache_bitmap)[u[i] >> 5];
+    }
+#pragma unroll
+    for (int i = 0; i < kFlagUnroll; ++i) {
+        uint64_t ballot = __ballot((w[i] >> (u[i] & 31u)) & 1u);
+        if (kCareful && __builtin_amdgcn_readlane(my_chunk, sub + i) == last_chunk) ballot &= last_mask;
+        if (lane == sub + i) { *lo = (uint32_t) ballot; *hi = (uint32_t) (ballot >> 32); }
+    }
+}
+
 // kLds: the cache bitmap is first copied into dynamic LDS (rounded up to 16 bytes).
+// Every wave takes an equal, contiguous share of the work list.
 template <bool kLds>
 __global__ void k_flag_chunks(SampleArgs a, int use_plan, int64_t all_chunks)
 {
@@ -259,38 +296,30 @@ __global__ void k_flag_chunks(SampleArgs a, int use_plan, int64_t all_chunks)
     }
     const uint32_t* lds32 = reinterpret_cast<const uint32_t*>(lds_bitmap16);
     const int64_t Q = use_plan ? (int64_t) a.st->plan_chunks : all_chunks;
+    if (Q <= 0 || a.num_entries <= 0) return;
     const int waves_per_block = (int) (blockDim.x >> 6);
     const int64_t wave_global = (int64_t) blockIdx.x * waves_per_block +
                                 __builtin_amdgcn_readfirstlane((int) (threadIdx.x >> 6));
     const int64_t num_waves = (int64_t) gridDim.x * waves_per_block;
-    for (int64_t c0 = wave_global * kFlagBatch; c0 < Q; c0 += num_waves * kFlagBatch) {
+    const int64_t share = (Q + num_waves - 1) / num_waves;
+    const int64_t begin = wave_global * share;
+    const int64_t end = (begin + share < Q) ? begin + share : Q;
+    const int64_t last_chunk = (a.num_entries - 1) >> 6;
+    const bool last_is_partial = (a.num_entries & 63) != 0;
+    for (int64_t c0 = begin; c0 < end; c0 += kFlagBatch) {
         const int lane = opaque_lane_id();
-        // lane l holds the chunk id of work-list entry c0 + l
-        int32_t my_chunk = -1;
-        if (c0 + lane < Q) my_chunk = use_plan ? a.plan_desc[c0 + lane] : (int32_t) (c0 + lane);
-        for (int sub = 0; sub < kFlagBatch; sub += kFlagUnroll) {
-            if (c0 + sub >= Q) break;                               // scalar condition
-            int32_t u[kFlagUnroll];
-            bool in[kFlagUnroll];
-#pragma unroll
-            for (int i = 0; i < kFlagUnroll; ++i) {
-                const int64_t g = (int64_t) __builtin_amdgcn_readlane(my_chunk, sub + i);
-                const int64_t e = g * 64 + lane;
-                in[i] = g >= 0 && e < a.num_entries;
-                u[i] = a.indices[in[i] ? e : 0];                    // unconditional load, clamped address
-            }
-            uint64_t mine = 0;
-#pragma unroll
-            for (int i = 0; i < kFlagUnroll; ++i) {
-                bool hit;
-                if (kLds) hit = in[i] && ((lds32[(uint32_t) u[i] >> 5] >> ((uint32_t) u[i] & 31u)) & 1u);
-                else      hit = in[i] && bitmap_test(a.cache_bitmap, (uint32_t) u[i]);
-                const uint64_t ballot = __ballot(hit);
-                if (lane == sub + i) mine = ballot;
-            }
-            // lanes sub .. sub+kFlagUnroll-1 store the words of their chunks
-            if (lane >= sub && lane < sub + kFlagUnroll && my_chunk >= 0) a.flags[my_chunk] = mine;
+        const int here = (int) ((end - c0 < kFlagBatch) ? end - c0 : kFlagBatch);     // scalar, >= 1
+        // Lane l holds the chunk id of work-list entry c0 + l; lanes past the share repeat its last
+        // entry (their result is not stored), so that every unrolled set is made of valid chunks.
+        const int64_t q = c0 + (lane < here ? lane : here - 1);
+        const int32_t my_chunk = use_plan ? a.plan_desc[q] : (int32_t) q;
+        const bool careful = last_is_partial && __ballot((int64_t) my_chunk == last_chunk) != 0ull;
+        uint32_t lo = 0, hi = 0;
+        for (int sub = 0; sub < here; sub += kFlagUnroll) {                            // scalar bounds
+            if (careful) flag_chunk_set<kLds, true>(a, lds32, my_chunk, sub, lane, &lo, &hi);
+            else         flag_chunk_set<kLds, false>(a, lds32, my_chunk, sub, lane, &lo, &hi);
         }
+        if (lane < here) a.flags[my_chunk] = ((uint64_t) hi << 32) | lo;
     }
 }
 
