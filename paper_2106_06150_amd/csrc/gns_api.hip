@@ -86,6 +86,7 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     // per-batch scratch (every forked context has its own copy of these sections)
     L.state = take(sizeof(DeviceState) + 64);
     L.mark_bitmap = take((size_t) L.words * 8);
+    L.row_ext = take((size_t) L.rows[cfg->num_layers] * 16);
     L.hash_slots[0] = take((size_t) L.hash_cap * 8);
     L.hash_slots[1] = take((size_t) L.hash_cap * 8);
     for (int par = 0; par < 2; ++par) {
@@ -118,6 +119,7 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
         L.draw_node = take((size_t) L.draw_chunk * 4);
         L.draw_slot = take((size_t) L.draw_chunk * 4);
         L.edge_flags = take((size_t) (g->num_entries / 64 + 1) * 8);
+        L.node_pc = take((size_t) n * 8);
     }
     L.total = off;
     *out = L;

@@ -49,6 +49,17 @@ __device__ __forceinline__ int64_t load_off(const void* indptr, int64_t i)
     return (int64_t) reinterpret_cast<const OffT*>(indptr)[i];
 }
 
+// Same with the offset width chosen at run time (kernels that touch offsets only in passing).
+__device__ __forceinline__ int64_t load_off_rt(const void* indptr, int is_i64, int64_t i)
+{
+    return is_i64 ? load_off<int64_t>(indptr, i) : load_off<int32_t>(indptr, i);
+}
+
+// CSR extent [start, end) of one dst row's node, kept per row of the batch's node list.
+struct alignas(16) RowExtent {
+    int64_t start, end;
+};
+
 // ---------------------------------------------------------------------------
 // Open-addressing hash map node id -> local id, one 64-bit slot per entry
 // (low word = key, high word = value), linear probing, load factor <= 1/2.

@@ -67,6 +67,9 @@ struct BeginArgs {
     const int32_t* seeds;
     int64_t num_nodes;
     uint32_t hmask, hshift;
+    RowExtent* row_ext;
+    const void* g_indptr;
+    int g_i64;
 };
 
 __global__ void __launch_bounds__(kBlock) k_batch_begin(BeginArgs a, int32_t num_seeds, uint32_t key0, uint32_t key1,
@@ -81,8 +84,14 @@ __global__ void __launch_bounds__(kBlock) k_batch_begin(BeginArgs a, int32_t num
     }
     for (int64_t q = t; q < num_seeds; q += (int64_t) gridDim.x * blockDim.x) {
         const int32_t u = a.seeds[q];
-        const bool ok = u >= 0 && (int64_t) u < a.num_nodes &&
-                        hash_insert(a.slots, a.hmask, a.hshift, (uint32_t) u, (uint32_t) q);
+        const bool in_range = u >= 0 && (int64_t) u < a.num_nodes;
+        RowExtent ext = {0, 0};
+        if (in_range) {
+            ext.start = load_off_rt(a.g_indptr, a.g_i64, u);
+            ext.end = load_off_rt(a.g_indptr, a.g_i64, (int64_t) u + 1);
+        }
+        a.row_ext[q] = ext;
+        const bool ok = in_range && hash_insert(a.slots, a.hmask, a.hshift, (uint32_t) u, (uint32_t) q);
         if (!ok) a.st->bad_seed = batch_id;
     }
 }
@@ -102,6 +111,9 @@ void fill_begin_args(gns_ctx* c, const int32_t* seeds, BeginArgsHost* out)
     a->num_nodes = c->graph.num_nodes;
     a->hmask = L.hash_cap - 1;
     a->hshift = 32u - (uint32_t) __builtin_ctz(L.hash_cap);
+    a->row_ext = ws_ptr<RowExtent>(c, L.row_ext);
+    a->g_indptr = c->graph.indptr;
+    a->g_i64 = c->graph.indptr_is_i64;
 }
 
 hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, uint32_t batch_id,
@@ -212,7 +224,11 @@ __global__ void __launch_bounds__(kBlock) k_finish_phase3(FinishArgs a)
             const int bit = select_bit64(s_word[lo], j - s_off[lo]);
             const uint32_t node = (uint32_t) ((base + lo) * 64 + bit);
             const int32_t pos = R + before + j;
+            RowExtent ext;
+            ext.start = load_off_rt(a.g_indptr, a.g_i64, node);
+            ext.end = load_off_rt(a.g_indptr, a.g_i64, (int64_t) node + 1);
             a.src_nodes[pos] = (int32_t) node;
+            a.row_ext[pos] = ext;
             hash_insert(a.slots, a.hmask, a.hshift, node, (uint32_t) pos);
         }
     }
@@ -244,6 +260,9 @@ void fill_finish_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, con
     a.weights = blk->weights;
     a.src_nodes = blk->src_nodes;
     a.max_slots = L.rows[layer_index] * (int64_t) a.fanout;
+    a.row_ext = ws_ptr<RowExtent>(c, L.row_ext);
+    a.g_indptr = c->graph.indptr;
+    a.g_i64 = c->graph.indptr_is_i64;
 }
 
 int relabel_grid(const gns_ctx* c, int layer_index)

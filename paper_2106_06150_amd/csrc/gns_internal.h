@@ -25,10 +25,12 @@ struct DeviceState {
 struct Layout {
     // persistent cache structures
     size_t cache_bitmap, cache_prefix, cache_nodes, cache_feat;
+    size_t node_pc;           // [n] doubles: p^C_u of Section 3.4, filled for the nodes of the current cache
     // cache-draw scratch
     size_t draw_keys, draw_vals, draw_node, draw_slot;
     // frontier structures
     size_t mark_bitmap;
+    size_t row_ext;           // [max nodes of a batch] CSR extent of every node of the batch's list (append-only)
     size_t hash_slots[2];     // consecutive batches alternate: each one leaves the other map empty for the next
     // per-layer sampler scratch (fixed stride fanout)
     size_t s_nbr[2], s_w[2], s_cnt[2];     // double-buffered by layer parity
@@ -60,7 +62,7 @@ struct Layout {
 namespace gns {
 // Opaque host-side storage for the first kernel's argument block (filled by fill_begin_args).
 struct BeginArgsHost {
-    alignas(8) unsigned char bytes[64];
+    alignas(8) unsigned char bytes[96];
 };
 // One captured launch sequence (there is one per hash-map parity).
 struct BatchGraph {

@@ -26,6 +26,9 @@ struct FinishArgs {
     float* weights;
     int32_t* src_nodes;
     int64_t max_slots;             // worst-case rows * fanout of this layer
+    RowExtent* row_ext;            // [nodes of the batch] phase 3 appends the new nodes' CSR extents
+    const void* g_indptr;          // the graph's offsets
+    int g_i64;
 };
 
 // Relabel: every sampled edge of a finished layer looks its neighbor's local id up in the batch's

@@ -30,6 +30,8 @@ struct SampleArgs {
     const void* indptr;
     const int32_t* indices;
     const int32_t* dst_nodes;
+    const RowExtent* row_ext;  // CSR extent of every dst row's node (written when the node joined the batch)
+    const double* node_pc;     // p^C_u for the nodes of the cache
     const uint64_t* cache_bitmap;
     const int32_t* cache_prefix;
     int64_t cache_size;
@@ -92,7 +94,7 @@ __device__ __forceinline__ void mark_if_new(const SampleArgs& a, uint32_t u)
 
 // ---------------------------------------------------------------------------
 // UNIFORM: G lanes per row, rows assigned round-robin to groups.
-template <typename OffT, int G>
+template <int G>
 __global__ void __launch_bounds__(kBlock) k_sample_uniform(SampleArgs a, FinishArgs prev, int relabel_blocks)
 {
     // the first relabel_blocks blocks finish the previous layer's block instead (see relabel_body)
@@ -116,12 +118,10 @@ __global__ void __launch_bounds__(kBlock) k_sample_uniform(SampleArgs a, FinishA
         uint32_t m = 0;
         uint32_t v = 0;
         if (live) {
-            const int32_t vi = a.dst_nodes[row];
-            if (vi >= 0 && (int64_t) vi < a.num_nodes) {
-                v = (uint32_t) vi;
-                start = load_off<OffT>(a.indptr, vi);
-                m = (uint32_t) (load_off<OffT>(a.indptr, (int64_t) vi + 1) - start);
-            }
+            const RowExtent ext = a.row_ext[row];
+            v = (uint32_t) a.dst_nodes[row];
+            start = ext.start;
+            m = (uint32_t) (ext.end - ext.start);
         }
         uint32_t val;
         int pos;
@@ -158,17 +158,6 @@ __global__ void __launch_bounds__(kBlock) k_sample_uniform(SampleArgs a, FinishA
 //            emit ids and Section 3.4 weights (k_select_rows)
 // A chunk shared by two dst rows is flagged twice with the same value.
 
-template <typename OffT>
-__device__ __forceinline__ void row_extent(const SampleArgs& a, int32_t vi, int64_t* start, int64_t* end)
-{
-    *start = 0;
-    *end = 0;
-    if (vi >= 0 && (int64_t) vi < a.num_nodes) {
-        *start = load_off<OffT>(a.indptr, vi);
-        *end = load_off<OffT>(a.indptr, (int64_t) vi + 1);
-    }
-}
-
 __device__ __forceinline__ int32_t chunks_touched(int64_t start, int64_t end)
 {
     return end > start ? (int32_t) (((end - 1) >> 6) - (start >> 6) + 1) : 0;
@@ -177,7 +166,6 @@ __device__ __forceinline__ int32_t chunks_touched(int64_t start, int64_t end)
 // Plan tiles are kPlanTile rows (one row per thread): many small blocks keep the expansion parallel.
 constexpr int kPlanTile = kBlock;
 
-template <typename OffT>
 __global__ void __launch_bounds__(kBlock) k_plan_count(SampleArgs a, FinishArgs prev, int relabel_blocks)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
@@ -188,8 +176,8 @@ __global__ void __launch_bounds__(kBlock) k_plan_count(SampleArgs a, FinishArgs 
     if (tile * kPlanTile >= R) return;
     int32_t c = 0;
     if (r < R) {
-        int64_t start, end;
-        row_extent<OffT>(a, a.dst_nodes[r], &start, &end);
+        const RowExtent ext = a.row_ext[r];
+        const int64_t start = ext.start, end = ext.end;
         c = chunks_touched(start, end);
         a.plan_cnt[r] = c;
         a.plan_g0[r] = (int32_t) (start >> 6);
@@ -335,7 +323,7 @@ __device__ __forceinline__ int32_t group_inclusive_scan(int32_t v, int s)
     return v;
 }
 
-template <typename OffT, int G>
+template <int G>
 __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs prev, int relabel_blocks)
 {
     if ((int) blockIdx.x < relabel_blocks) { relabel_body(prev, blockIdx.x, relabel_blocks); return; }
@@ -355,8 +343,10 @@ __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs
         int32_t vi = -1;
         int64_t start = 0, end = 0;
         if (live) {
+            const RowExtent ext = a.row_ext[row];
             vi = a.dst_nodes[row];
-            row_extent<OffT>(a, vi, &start, &end);
+            start = ext.start;
+            end = ext.end;
         }
         const int32_t nw = chunks_touched(start, end);       // flag words of this row
         const int64_t g0 = start >> 6;
@@ -422,12 +412,9 @@ __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs
 
         if (live && s < cnt) {
             const int32_t u = a.indices[entry];
-            // Section 3.4: p_u = deg(u)/nnz, p^C_u = 1 - (1 - p_u)^|C| (expm1/log1p keep tiny p_u exact),
-            // coefficient p^C_u * k / min(k, N_C(v)), weight = 1 / coefficient
-            int64_t ub, ue;
-            row_extent<OffT>(a, u, &ub, &ue);
-            const double p = (double) (ue - ub) / (double) a.num_entries;
-            const double pc = (p >= 1.0) ? 1.0 : -expm1((double) a.cache_size * log1p(-p));
+            // Section 3.4: coefficient p^C_u * k / min(k, N_C(v)), weight = 1 / coefficient; p^C_u comes
+            // from the table filled when the cache was drawn (u is in the cache)
+            const double pc = a.node_pc[u];
             double wgt;
             if (a.wmode == GNS_W_UNBIASED) wgt = (double) m / ((double) cnt * pc);
             else                           wgt = 1.0 / (pc * (double) k / (double) cnt);
@@ -477,6 +464,8 @@ static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nod
     a.indptr = c->graph.indptr;
     a.indices = c->graph.indices;
     a.dst_nodes = dst_nodes;
+    a.row_ext = ws_ptr<RowExtent>(c, L.row_ext);
+    a.node_pc = c->uses_cache ? ws_ptr<double>(c, L.node_pc) : nullptr;
     a.cache_bitmap = ws_ptr<uint64_t>(c, L.cache_bitmap);
     a.cache_prefix = ws_ptr<int32_t>(c, L.cache_prefix);
     a.cache_size = c->config.cache_size;
@@ -515,7 +504,6 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
     }
 
     const int64_t rows_max = L.rows[layer_index];
-    const bool i64 = c->graph.indptr_is_i64 != 0;
     const int G = (a.fanout <= 8) ? 8 : (a.fanout <= 16) ? 16 : 64;
     const int64_t rows_per_block = kBlock / G;
     int64_t row_blocks = (rows_max + rows_per_block - 1) / rows_per_block;
@@ -524,19 +512,12 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
     if (row_blocks < 1) row_blocks = 1;
     const dim3 tb(kBlock);
 
-#define GNS_LAUNCH_BY_G(KERNEL, RL)                                                                          \
-    do {                                                                                                     \
-        const dim3 rb((unsigned) (row_blocks + (RL)));                                                       \
-        if (G == 8) {                                                                                        \
-            if (i64) hipLaunchKernelGGL((KERNEL<int64_t, 8>), rb, tb, 0, s, a, prev, (RL));                  \
-            else     hipLaunchKernelGGL((KERNEL<int32_t, 8>), rb, tb, 0, s, a, prev, (RL));                  \
-        } else if (G == 16) {                                                                                \
-            if (i64) hipLaunchKernelGGL((KERNEL<int64_t, 16>), rb, tb, 0, s, a, prev, (RL));                 \
-            else     hipLaunchKernelGGL((KERNEL<int32_t, 16>), rb, tb, 0, s, a, prev, (RL));                 \
-        } else {                                                                                             \
-            if (i64) hipLaunchKernelGGL((KERNEL<int64_t, 64>), rb, tb, 0, s, a, prev, (RL));                 \
-            else     hipLaunchKernelGGL((KERNEL<int32_t, 64>), rb, tb, 0, s, a, prev, (RL));                 \
-        }                                                                                                    \
+#define GNS_LAUNCH_BY_G(KERNEL, RL)                                                      \
+    do {                                                                                 \
+        const dim3 rb((unsigned) (row_blocks + (RL)));                                   \
+        if (G == 8)       hipLaunchKernelGGL((KERNEL<8>), rb, tb, 0, s, a, prev, (RL));  \
+        else if (G == 16) hipLaunchKernelGGL((KERNEL<16>), rb, tb, 0, s, a, prev, (RL)); \
+        else              hipLaunchKernelGGL((KERNEL<64>), rb, tb, 0, s, a, prev, (RL)); \
     } while (0)
 
     if (c->config.policy[layer_index] == GNS_UNIFORM) {
@@ -549,8 +530,7 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
         {
             StageTimer t(c, GNS_STAGE_PLAN, s);
             const unsigned plan_blocks = (unsigned) ((rows_max + kPlanTile - 1) / kPlanTile);
-            if (i64) hipLaunchKernelGGL((k_plan_count<int64_t>), dim3(plan_blocks + (unsigned) rl), tb, 0, s, a, prev, rl);
-            else     hipLaunchKernelGGL((k_plan_count<int32_t>), dim3(plan_blocks + (unsigned) rl), tb, 0, s, a, prev, rl);
+            hipLaunchKernelGGL(k_plan_count, dim3(plan_blocks + (unsigned) rl), tb, 0, s, a, prev, rl);
             hipLaunchKernelGGL(k_plan_expand, dim3(plan_blocks), tb, 0, s, a);
         }
         rl = 0;                          // done with the plan kernel
