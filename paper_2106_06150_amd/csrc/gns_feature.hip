@@ -115,6 +115,8 @@ struct AggArgs {
     float* out;
     int32_t num_dst;
     const int32_t* num_dst_dev;     // if not null the row count is read here
+    int32_t num_src;                // rows of x_src; an edge whose index lies outside is skipped
+    const int32_t* num_src_dev;
     int32_t feat_dim;
 };
 
@@ -127,6 +129,8 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggArgs a)
     const int64_t num_groups = (int64_t) gridDim.x * groups_per_block;
     const int64_t F = a.feat_dim;
     const int64_t count = a.num_dst_dev ? (int64_t) *a.num_dst_dev : (int64_t) a.num_dst;
+    const uint32_t num_src = (uint32_t) (a.num_src_dev ? *a.num_src_dev : a.num_src);
+    constexpr int kEdges = 8;       // edges whose rows are in flight together
     for (int64_t row = group; row < count; row += num_groups) {
         const int32_t b = a.indptr[row], e = a.indptr[row + 1];
         const float n_v = (float) (e - b);
@@ -136,13 +140,26 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggArgs a)
             const int64_t F4 = F >> 2;
             for (int i = lane; i < (int) F4; i += kLanes) {
                 float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-                for (int32_t q = b; q < e; ++q) {
-                    const float w = a.weights[q];
-                    const float4 x = x4[(int64_t) a.indices[q] * F4 + i];
-                    acc.x = fmaf(w, x.x, acc.x);
-                    acc.y = fmaf(w, x.y, acc.y);
-                    acc.z = fmaf(w, x.z, acc.z);
-                    acc.w = fmaf(w, x.w, acc.w);
+                for (int32_t q0 = b; q0 < e; q0 += kEdges) {
+                    float w[kEdges];
+                    float4 x[kEdges];
+#pragma unroll
+                    for (int t = 0; t < kEdges; ++t) {
+                        const int32_t q = q0 + t;
+                        const uint32_t j = (q < e) ? (uint32_t) a.indices[q] : 0xFFFFFFFFu;
+                        const bool ok = j < num_src;
+                        w[t] = ok ? a.weights[q] : 0.f;
+                        x[t] = x4[(int64_t) (ok ? j : 0u) * F4 + i];
+                    }
+#pragma unroll
+                    for (int t = 0; t < kEdges; ++t) {       // edge order, one fma per term
+                        if (q0 + t < e) {
+                            acc.x = fmaf(w[t], x[t].x, acc.x);
+                            acc.y = fmaf(w[t], x[t].y, acc.y);
+                            acc.z = fmaf(w[t], x[t].z, acc.z);
+                            acc.w = fmaf(w[t], x[t].w, acc.w);
+                        }
+                    }
                 }
                 if (e > b) { acc.x /= n_v; acc.y /= n_v; acc.z /= n_v; acc.w /= n_v; }
                 o4[i] = acc;
@@ -150,7 +167,10 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggArgs a)
         } else {
             for (int i = lane; i < (int) F; i += kLanes) {
                 float acc = 0.f;
-                for (int32_t q = b; q < e; ++q) acc = fmaf(a.weights[q], a.x_src[(int64_t) a.indices[q] * F + i], acc);
+                for (int32_t q = b; q < e; ++q) {
+                    const uint32_t j = (uint32_t) a.indices[q];
+                    if (j < num_src) acc = fmaf(a.weights[q], a.x_src[(int64_t) j * F + i], acc);
+                }
                 if (e > b) acc /= n_v;
                 a.out[row * F + i] = acc;
             }
@@ -177,9 +197,12 @@ hipError_t launch_aggregate(gns_ctx* c, const gns_block* blk, const float* x_src
     AggArgs a;
     int32_t rows = blk->num_dst;
     a.num_dst_dev = nullptr;
+    a.num_src_dev = nullptr;
+    a.num_src = blk->num_src;
     if (rows < 0) {                 // GNS_DEVICE_COUNTS(layer): rows counted on the device
         const int layer = -1 - rows;
         a.num_dst_dev = &c->d_state->num_dst[layer];
+        a.num_src_dev = &c->d_state->num_dst[layer + 1];
         rows = (int32_t) c->lay.rows[layer];
     }
     a.indptr = blk->indptr;

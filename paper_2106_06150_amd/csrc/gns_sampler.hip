@@ -323,6 +323,136 @@ __device__ __forceinline__ int32_t group_inclusive_scan(int32_t v, int s)
     return v;
 }
 
+constexpr int kHubWords = 4;        // flag words a lane holds per step when the whole wave walks a hub row
+constexpr int kHubSteps = 4;        // a row that needs more steps than this from its own group is a hub
+
+// One dst row per group of G consecutive lanes (s = lane within the group): count the row's
+// eligible neighbors from its flag words, draw, map the chosen ranks back to CSR positions and
+// emit.  A step covers G * W words, lane s holding words s*W .. s*W+W-1 of it,
+// so ranks run in lane order.  Every lane of the wave must call it (it exchanges data between
+// lanes); `live` says whether this lane's group has a row.
+template <int G, int W>
+__device__ __forceinline__ void select_row(const SampleArgs& a, int64_t row, bool live, int s, int64_t start,
+                                           int64_t end, int32_t vi)
+{
+    const int k = a.fanout;
+    const int32_t nw = live ? chunks_touched(start, end) : 0;     // flag words of this row
+    const int64_t g0 = start >> 6;
+    const uint64_t head_mask = ~0ull << (start & 63);
+    const int tail_bits = (int) (end & 63);
+    const uint64_t tail_mask = tail_bits ? ((1ull << tail_bits) - 1ull) : ~0ull;
+
+    auto load_words = [&](int32_t j0, uint64_t* w) -> int32_t {
+        int32_t c = 0;
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            const int32_t j = j0 + i;
+            uint64_t x = 0;
+            if (j < nw) {
+                x = a.flags[g0 + j];
+                if (j == 0) x &= head_mask;
+                if (j == nw - 1) x &= tail_mask;
+            }
+            w[i] = x;
+            c += __popcll(x);
+        }
+        return c;
+    };
+
+    // pass 1: N_C(v) = set bits of the row's flag words, trimmed to [start, end)
+    uint32_t m = 0;
+    uint64_t w_first[W];
+    int32_t incl_first = 0;
+#pragma unroll
+    for (int i = 0; i < W; ++i) w_first[i] = 0;
+    for (int32_t it = 0; __any(it * G * W < nw); ++it) {
+        uint64_t w[W];
+        const int32_t c = load_words((it * G + s) * W, w);
+        const int32_t incl = group_inclusive_scan<G>(c, s);
+        if (it == 0) {
+#pragma unroll
+            for (int i = 0; i < W; ++i) w_first[i] = w[i];
+            incl_first = incl;
+        }
+        m += (uint32_t) __shfl(incl, G - 1, G);
+    }
+
+    uint32_t val;
+    int pos;
+    floyd_in_group<G>(m > (uint32_t) k ? m : (uint32_t) k + 1u, k, a.st->key0, a.st->key1, a.layer_number,
+                      (uint32_t) vi, s, &val, &pos);
+    const int cnt = (m > (uint32_t) k) ? k : (int) m;
+    if (m <= (uint32_t) k) { val = (uint32_t) s; pos = s; }
+
+    // pass 2: lane s < cnt finds the lane, then the word, then the bit that holds its rank
+    int64_t entry = -1;
+    uint32_t run = 0;
+    for (int32_t it = 0; __any(it * G * W < nw); ++it) {
+        uint64_t w[W];
+        int32_t incl = incl_first;
+#pragma unroll
+        for (int i = 0; i < W; ++i) w[i] = w_first[i];
+        if (it > 0) incl = group_inclusive_scan<G>(load_words((it * G + s) * W, w), s);   // long rows reload
+        const uint32_t step_total = (uint32_t) __shfl(incl, G - 1, G);
+        const bool mine = s < cnt && entry < 0 && val >= run && val < run + step_total;
+        const uint32_t local = val - run;
+        // owner = number of lanes whose inclusive count is <= local
+        int owner = 0;
+        if (G == 64) {
+            // the whole wave is one group: one ballot per drawn slot instead of one shuffle per lane
+            for (int q = 0; q < k; ++q) {
+                const uint32_t local_q = (uint32_t) __shfl((int) local, q, G);
+                const int below = __popcll(__ballot((uint32_t) incl <= local_q));
+                if (s == q) owner = below;
+            }
+        } else {
+            for (int t = 0; t < G; ++t) owner += ((uint32_t) __shfl(incl, t, G) <= local) ? 1 : 0;
+        }
+        owner = owner < G ? owner : G - 1;
+        uint64_t wo[W];
+        int32_t own_total = 0;
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            wo[i] = __shfl(w[i], owner, G);
+            own_total += __popcll(wo[i]);
+        }
+        const int32_t incl_owner = __shfl(incl, owner, G);
+        if (mine) {
+            int32_t rest = (int32_t) local - (incl_owner - own_total);       // rank inside the owner's words
+            int which = 0;
+            uint64_t word = wo[0];
+#pragma unroll
+            for (int i = 0; i < W - 1; ++i) {
+                const int32_t c = __popcll(wo[i]);
+                if (which == i && rest >= c) { rest -= c; which = i + 1; word = wo[i + 1]; }
+            }
+            const int bit = select_bit64(word, rest);
+            entry = (g0 + ((int64_t) it * G + owner) * W + which) * 64 + bit;
+        }
+        run += step_total;
+    }
+
+    if (live && s < cnt) {
+        const int32_t u = a.indices[entry];
+        // Section 3.4: coefficient p^C_u * k / min(k, N_C(v)), weight = 1 / coefficient; p^C_u comes
+        // from the table filled when the cache was drawn (u is in the cache)
+        const double pc = a.node_pc[u];
+        double wgt;
+        if (a.wmode == GNS_W_UNBIASED) wgt = (double) m / ((double) cnt * pc);
+        else                           wgt = 1.0 / (pc * (double) k / (double) cnt);
+        a.s_nbr[row * k + pos] = u;
+        a.s_w[row * k + pos] = (float) wgt;
+        mark_if_new(a, (uint32_t) u);
+    }
+    if (live && s == 0) {
+        a.s_cnt[row] = cnt;
+        a.row_eligible[row] = (int32_t) m;
+    }
+}
+
+// G lanes per dst row, one flag word per lane and step.  A row that would take its group more
+// than kHubSteps steps (a hub) would keep the rest of the wave waiting, so such rows are set
+// aside and then taken one after the other by the whole wave (64 * kHubWords words per step).
 template <int G>
 __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs prev, int relabel_blocks)
 {
@@ -330,7 +460,6 @@ __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs
     const int64_t block = (int64_t) blockIdx.x - relabel_blocks;
     const int64_t nblocks = (int64_t) gridDim.x - relabel_blocks;
     const int32_t R = a.st->num_dst[a.layer_index];
-    const int k = a.fanout;
     constexpr int kRowsPerWave = kWave / G;
     const int64_t wave_global = block * (kBlock / kWave) +
                                 __builtin_amdgcn_readfirstlane((int) (threadIdx.x >> 6));
@@ -348,83 +477,20 @@ __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs
             start = ext.start;
             end = ext.end;
         }
-        const int32_t nw = chunks_touched(start, end);       // flag words of this row
-        const int64_t g0 = start >> 6;
-        const uint64_t head_mask = ~0ull << (start & 63);
-        const int tail_bits = (int) (end & 63);
-        const uint64_t tail_mask = tail_bits ? ((1ull << tail_bits) - 1ull) : ~0ull;
-
-        // pass 1: N_C(v) = set bits of the row's flag words, trimmed to [start, end)
-        uint32_t m = 0;
-        uint64_t w_first = 0;
-        int32_t incl_first = 0;
-        for (int32_t it = 0; __any(it * G + s < nw); ++it) {
-            const int32_t j = it * G + s;
-            uint64_t w = 0;
-            if (j < nw) {
-                w = a.flags[g0 + j];
-                if (j == 0) w &= head_mask;
-                if (j == nw - 1) w &= tail_mask;
+        const bool hub = (G < 64) && live && chunks_touched(start, end) > G * kHubSteps;
+        select_row<G, 1>(a, row, live && !hub, s, start, end, vi);
+        if (G < 64) {
+            uint64_t hubs = __ballot(hub && s == 0);                 // wave-uniform
+            while (hubs) {
+                const int src = __builtin_ctzll(hubs);               // a lane of the hub's group
+                hubs &= hubs - 1;
+                const int lane64 = opaque_lane_id();
+                const int64_t h_row = row0 + src / G;
+                const int64_t h_start = __shfl(start, src, kWave);
+                const int64_t h_end = __shfl(end, src, kWave);
+                const int32_t h_vi = __shfl(vi, src, kWave);
+                select_row<64, kHubWords>(a, h_row, true, lane64, h_start, h_end, h_vi);
             }
-            const int32_t incl = group_inclusive_scan<G>(__popcll(w), s);
-            if (it == 0) { w_first = w; incl_first = incl; }
-            m += (uint32_t) __shfl(incl, G - 1, G);
-        }
-
-        uint32_t val;
-        int pos;
-        floyd_in_group<G>(m > (uint32_t) k ? m : (uint32_t) k + 1u, k, a.st->key0, a.st->key1, a.layer_number,
-                          (uint32_t) vi, s, &val, &pos);
-        const int cnt = (m > (uint32_t) k) ? k : (int) m;
-        if (m <= (uint32_t) k) { val = (uint32_t) s; pos = s; }
-
-        // pass 2: lane s < cnt finds the flag word that holds its rank and the bit inside it
-        int64_t entry = -1;
-        uint32_t run = 0;
-        for (int32_t it = 0; __any(it * G + s < nw); ++it) {
-            const int32_t j = it * G + s;
-            uint64_t w = w_first;
-            int32_t incl = incl_first;
-            if (it > 0) {                                   // only rows longer than G words reload
-                w = 0;
-                if (j < nw) {
-                    w = a.flags[g0 + j];
-                    if (j == nw - 1) w &= tail_mask;
-                }
-                incl = group_inclusive_scan<G>(__popcll(w), s);
-            }
-            const uint32_t step_total = (uint32_t) __shfl(incl, G - 1, G);
-            const bool mine = s < cnt && entry < 0 && val >= run && val < run + step_total;
-            const uint32_t local = val - run;
-            // owner = number of lanes whose inclusive count is <= local
-            int owner = 0;
-            for (int t = 0; t < G; ++t) owner += ((uint32_t) __shfl(incl, t, G) <= local) ? 1 : 0;
-            owner = owner < G ? owner : G - 1;
-            const uint64_t w_owner = __shfl(w, owner, G);
-            const int32_t incl_owner = __shfl(incl, owner, G);
-            if (mine) {
-                const int32_t before = incl_owner - __popcll(w_owner);
-                const int bit = select_bit64(w_owner, (int) local - before);
-                entry = (g0 + (j - s) + owner) * 64 + bit;
-            }
-            run += step_total;
-        }
-
-        if (live && s < cnt) {
-            const int32_t u = a.indices[entry];
-            // Section 3.4: coefficient p^C_u * k / min(k, N_C(v)), weight = 1 / coefficient; p^C_u comes
-            // from the table filled when the cache was drawn (u is in the cache)
-            const double pc = a.node_pc[u];
-            double wgt;
-            if (a.wmode == GNS_W_UNBIASED) wgt = (double) m / ((double) cnt * pc);
-            else                           wgt = 1.0 / (pc * (double) k / (double) cnt);
-            a.s_nbr[row * k + pos] = u;
-            a.s_w[row * k + pos] = (float) wgt;
-            mark_if_new(a, (uint32_t) u);
-        }
-        if (live && s == 0) {
-            a.s_cnt[row] = cnt;
-            a.row_eligible[row] = (int32_t) m;
         }
     }
 }

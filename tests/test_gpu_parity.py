@@ -34,7 +34,7 @@ def _feat(n, F, seed=0):
 @pytest.mark.parametrize("flag_mode", [0, 1])
 @pytest.mark.parametrize("offsets", [torch.int32, torch.int64])
 @pytest.mark.parametrize("fanouts,policies", [((10, 5), (U, C)), ((15, 10, 5), (U, U, C)), ((3, 2, 1), (C, C, C)),
-                                              ((4, 4), (U, U)), ((20, 17), (U, C))])
+                                              ((4, 4), (U, U)), ((20, 17), (U, C)), ((6, 12), (U, C))])
 def test_small_graph_parity(offsets, fanouts, policies, flag_mode):
     ip, ix = _small()
     n = ip.numel() - 1
