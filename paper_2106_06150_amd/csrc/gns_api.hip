@@ -119,7 +119,7 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
         L.draw_node = take((size_t) L.draw_chunk * 4);
         L.draw_slot = take((size_t) L.draw_chunk * 4);
         L.edge_flags = take((size_t) (g->num_entries / 64 + 1) * 8);
-        L.node_pc = take((size_t) n * 8);
+        L.node_pc = take((size_t) n * 4);
     }
     L.total = off;
     *out = L;

@@ -241,18 +241,19 @@ __global__ void __launch_bounds__(kBlock) k_cache_index_phase3(IndexArgs a)
 }
 
 // Section 3.4 for every node of the cache: p_u = deg(u)/nnz, p^C_u = 1 - (1 - p_u)^|C|
-// (expm1/log1p keep a tiny p_u exact).  The table is indexed by node id; entries of nodes
+// (expm1/log1p keep a tiny p_u exact), stored as 1/p^C_u in fp32.  The table is indexed by node id; entries of nodes
 // outside the current cache are stale and never read.
 template <typename OffT>
 __global__ void __launch_bounds__(kBlock) k_cache_pc(const int32_t* cache_nodes, int64_t C, const void* indptr,
-                                                     int64_t nnz, double* node_pc)
+                                                     int64_t nnz, float* node_inv_pc)
 {
     const int64_t i = (int64_t) blockIdx.x * kBlock + threadIdx.x;
     if (i >= C) return;
     const int32_t u = cache_nodes[i];
     const int64_t deg = load_off<OffT>(indptr, (int64_t) u + 1) - load_off<OffT>(indptr, u);
     const double p = (double) deg / (double) nnz;
-    node_pc[u] = (p >= 1.0) ? 1.0 : -expm1((double) C * log1p(-p));
+    const double pc = (p >= 1.0) ? 1.0 : -expm1((double) C * log1p(-p));
+    node_inv_pc[u] = (float) (1.0 / pc);
 }
 
 // ---------------------------------------------------------------------------
@@ -346,7 +347,7 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
 
     {
         const unsigned pc_blocks = (unsigned) ((C + kBlock - 1) / kBlock);
-        double* node_pc = ws_ptr<double>(c, L.node_pc);
+        float* node_pc = ws_ptr<float>(c, L.node_pc);
         if (i64) hipLaunchKernelGGL((k_cache_pc<int64_t>), dim3(pc_blocks), dim3(kBlock), 0, s, x.cache_nodes, C, c->graph.indptr, c->graph.num_entries, node_pc);
         else     hipLaunchKernelGGL((k_cache_pc<int32_t>), dim3(pc_blocks), dim3(kBlock), 0, s, x.cache_nodes, C, c->graph.indptr, c->graph.num_entries, node_pc);
         GNS_HIP_TRY(hipGetLastError(), "cache weight table launch");

@@ -25,7 +25,7 @@ struct DeviceState {
 struct Layout {
     // persistent cache structures
     size_t cache_bitmap, cache_prefix, cache_nodes, cache_feat;
-    size_t node_pc;           // [n] doubles: p^C_u of Section 3.4, filled for the nodes of the current cache
+    size_t node_pc;           // [n] floats: 1 / p^C_u (Section 3.4), filled for the nodes of the current cache
     // cache-draw scratch
     size_t draw_keys, draw_vals, draw_node, draw_slot;
     // frontier structures

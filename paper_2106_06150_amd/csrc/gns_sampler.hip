@@ -31,7 +31,7 @@ struct SampleArgs {
     const int32_t* indices;
     const int32_t* dst_nodes;
     const RowExtent* row_ext;  // CSR extent of every dst row's node (written when the node joined the batch)
-    const double* node_pc;     // p^C_u for the nodes of the cache
+    const float* node_inv_pc;  // 1 / p^C_u for the nodes of the cache
     const uint64_t* cache_bitmap;
     const int32_t* cache_prefix;
     int64_t cache_size;
@@ -435,13 +435,13 @@ __device__ __forceinline__ void select_row(const SampleArgs& a, int64_t row, boo
     if (live && s < cnt) {
         const int32_t u = a.indices[entry];
         // Section 3.4: coefficient p^C_u * k / min(k, N_C(v)), weight = 1 / coefficient; p^C_u comes
-        // from the table filled when the cache was drawn (u is in the cache)
-        const double pc = a.node_pc[u];
-        double wgt;
-        if (a.wmode == GNS_W_UNBIASED) wgt = (double) m / ((double) cnt * pc);
-        else                           wgt = 1.0 / (pc * (double) k / (double) cnt);
+        // from the table filled when the cache was drawn (u is in the cache); fp32 from here on
+        const float inv_pc = a.node_inv_pc[u];
+        float wgt;
+        if (a.wmode == GNS_W_UNBIASED) wgt = inv_pc * ((float) m / (float) cnt);
+        else                           wgt = inv_pc * ((float) cnt / (float) k);
         a.s_nbr[row * k + pos] = u;
-        a.s_w[row * k + pos] = (float) wgt;
+        a.s_w[row * k + pos] = wgt;
         mark_if_new(a, (uint32_t) u);
     }
     if (live && s == 0) {
@@ -531,7 +531,7 @@ static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nod
     a.indices = c->graph.indices;
     a.dst_nodes = dst_nodes;
     a.row_ext = ws_ptr<RowExtent>(c, L.row_ext);
-    a.node_pc = c->uses_cache ? ws_ptr<double>(c, L.node_pc) : nullptr;
+    a.node_inv_pc = c->uses_cache ? ws_ptr<float>(c, L.node_pc) : nullptr;
     a.cache_bitmap = ws_ptr<uint64_t>(c, L.cache_bitmap);
     a.cache_prefix = ws_ptr<int32_t>(c, L.cache_prefix);
     a.cache_size = c->config.cache_size;
@@ -573,7 +573,9 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
     const int G = (a.fanout <= 8) ? 8 : (a.fanout <= 16) ? 16 : 64;
     const int64_t rows_per_block = kBlock / G;
     int64_t row_blocks = (rows_max + rows_per_block - 1) / rows_per_block;
-    const int64_t cap = (int64_t) c->num_cus * 8;
+    // One step of rows per wave where that fits: rows differ a lot in cost, and with more blocks
+    // than the chip holds the dispatcher hands out new rows as waves finish.
+    const int64_t cap = (int64_t) c->num_cus * 64;
     if (row_blocks > cap) row_blocks = cap;
     if (row_blocks < 1) row_blocks = 1;
     const dim3 tb(kBlock);
