@@ -70,6 +70,7 @@ struct BeginArgs {
     RowExtent* row_ext;
     const void* g_indptr;
     int g_i64;
+    int32_t* hub_rows;
 };
 
 __global__ void __launch_bounds__(kBlock) k_batch_begin(BeginArgs a, int32_t num_seeds, uint32_t key0, uint32_t key1,
@@ -91,6 +92,7 @@ __global__ void __launch_bounds__(kBlock) k_batch_begin(BeginArgs a, int32_t num
             ext.end = load_off_rt(a.g_indptr, a.g_i64, (int64_t) u + 1);
         }
         a.row_ext[q] = ext;
+        append_hub_rows(a.st, a.hub_rows, is_hub_extent(ext.start, ext.end), (int32_t) q);
         const bool ok = in_range && hash_insert(a.slots, a.hmask, a.hshift, (uint32_t) u, (uint32_t) q);
         if (!ok) a.st->bad_seed = batch_id;
     }
@@ -114,6 +116,7 @@ void fill_begin_args(gns_ctx* c, const int32_t* seeds, BeginArgsHost* out)
     a->row_ext = ws_ptr<RowExtent>(c, L.row_ext);
     a->g_indptr = c->graph.indptr;
     a->g_i64 = c->graph.indptr_is_i64;
+    a->hub_rows = ws_ptr<int32_t>(c, L.hub_rows);
 }
 
 hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, uint32_t batch_id,
@@ -229,6 +232,7 @@ __global__ void __launch_bounds__(kBlock) k_finish_phase3(FinishArgs a)
             ext.end = load_off_rt(a.g_indptr, a.g_i64, (int64_t) node + 1);
             a.src_nodes[pos] = (int32_t) node;
             a.row_ext[pos] = ext;
+            append_hub_rows(a.st, a.hub_rows, is_hub_extent(ext.start, ext.end), pos);
             hash_insert(a.slots, a.hmask, a.hshift, node, (uint32_t) pos);
         }
     }
@@ -263,6 +267,7 @@ void fill_finish_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, con
     a.row_ext = ws_ptr<RowExtent>(c, L.row_ext);
     a.g_indptr = c->graph.indptr;
     a.g_i64 = c->graph.indptr_is_i64;
+    a.hub_rows = ws_ptr<int32_t>(c, L.hub_rows);
 }
 
 int relabel_grid(const gns_ctx* c, int layer_index)
@@ -291,6 +296,7 @@ __global__ void __launch_bounds__(kBlock) k_relabel_last(FinishArgs a, unsigned 
 {
     relabel_body(a, blockIdx.x, gridDim.x);
     size_t i = (size_t) blockIdx.x * kBlock + threadIdx.x;
+    if (i == 0) a.st->hub_count = 0;                 // the next batch starts a new hub list
     const size_t stride = (size_t) gridDim.x * kBlock;
     for (; i < cap; i += stride) other_slots[i] = kEmptySlot;
 }

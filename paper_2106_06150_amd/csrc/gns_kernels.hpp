@@ -29,6 +29,7 @@ struct FinishArgs {
     RowExtent* row_ext;            // [nodes of the batch] phase 3 appends the new nodes' CSR extents
     const void* g_indptr;          // the graph's offsets
     int g_i64;
+    int32_t* hub_rows;             // phase 3 appends the new nodes that are hubs
 };
 
 // Relabel: every sampled edge of a finished layer looks its neighbor's local id up in the batch's
@@ -50,6 +51,29 @@ __device__ __forceinline__ void relabel_body(const FinishArgs& a, int64_t block,
             a.weights[o] = a.s_w[t];
         }
     }
+}
+
+// A node whose CSR segment touches more than kHubChunks aligned 64-entry chunks is a hub: the
+// CACHE_ONLY sampler gives such rows a whole wave each.  Nodes are classified when they join the
+// batch's node list; the list of hub rows is append-only like the node list itself.
+constexpr int kHubChunks = 32;
+
+__device__ __forceinline__ bool is_hub_extent(int64_t start, int64_t end)
+{
+    return end > start && ((end - 1) >> 6) - (start >> 6) + 1 > kHubChunks;
+}
+
+// Appends `row` for the calling lanes that have is_hub set: one atomic per wave.
+__device__ __forceinline__ void append_hub_rows(DeviceState* st, int32_t* hub_rows, bool is_hub, int32_t row)
+{
+    const uint64_t m = __ballot(is_hub);
+    if (m == 0) return;
+    const int lane = lane_id();
+    const int leader = __builtin_ctzll(m);
+    int32_t base = 0;
+    if (lane == leader) base = atomicAdd(&st->hub_count, (int32_t) __popcll(m));
+    base = __shfl(base, leader, kWave);
+    if (is_hub) hub_rows[base + __popcll(m & ((1ull << lane) - 1ull))] = row;
 }
 
 void fill_finish_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, const gns_block* blk, FinishArgs* out);

@@ -32,6 +32,7 @@ struct SampleArgs {
     const int32_t* dst_nodes;
     const RowExtent* row_ext;  // CSR extent of every dst row's node (written when the node joined the batch)
     const float* node_inv_pc;  // 1 / p^C_u for the nodes of the cache
+    const int32_t* hub_rows;   // rows of the batch whose CSR segment spans more than kHubChunks chunks
     const uint64_t* cache_bitmap;
     const int32_t* cache_prefix;
     int64_t cache_size;
@@ -324,7 +325,6 @@ __device__ __forceinline__ int32_t group_inclusive_scan(int32_t v, int s)
 }
 
 constexpr int kHubWords = 4;        // flag words a lane holds per step when the whole wave walks a hub row
-constexpr int kHubSteps = 4;        // a row that needs more steps than this from its own group is a hub
 
 // One dst row per group of G consecutive lanes (s = lane within the group): count the row's
 // eligible neighbors from its flag words, draw, map the chosen ranks back to CSR positions and
@@ -450,25 +450,38 @@ __device__ __forceinline__ void select_row(const SampleArgs& a, int64_t row, boo
     }
 }
 
-// G lanes per dst row, one flag word per lane and step.  A row that would take its group more
-// than kHubSteps steps (a hub) would keep the rest of the wave waiting, so such rows are set
-// aside and then taken one after the other by the whole wave (64 * kHubWords words per step).
+// G lanes per dst row, one flag word per lane and step.  Hub rows (listed when their nodes joined
+// the batch) would keep the rest of their wave waiting, so for G < 64 the row blocks skip them
+// and hub_blocks further blocks give each of them a whole wave (64 * kHubWords words per step).
+// Block order: relabel blocks of the previous layer, hub blocks, row blocks.
 template <int G>
-__global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs prev, int relabel_blocks)
+__global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs prev, int relabel_blocks, int hub_blocks)
 {
     if ((int) blockIdx.x < relabel_blocks) { relabel_body(prev, blockIdx.x, relabel_blocks); return; }
-    const int64_t block = (int64_t) blockIdx.x - relabel_blocks;
-    const int64_t nblocks = (int64_t) gridDim.x - relabel_blocks;
+    const int wave_in_block = __builtin_amdgcn_readfirstlane((int) (threadIdx.x >> 6));
+    if ((int) blockIdx.x < relabel_blocks + hub_blocks) {
+        const int32_t H = a.st->hub_count;
+        const int32_t nhw = hub_blocks * (kBlock / kWave);
+        for (int32_t h = ((int32_t) blockIdx.x - relabel_blocks) * (kBlock / kWave) + wave_in_block; h < H; h += nhw) {
+            const int lane = opaque_lane_id();
+            const int32_t row = a.hub_rows[h];
+            const RowExtent ext = a.row_ext[row];
+            const int32_t vi = a.dst_nodes[row];
+            select_row<64, kHubWords>(a, row, true, lane, ext.start, ext.end, vi);
+        }
+        return;
+    }
+    const int64_t block = (int64_t) blockIdx.x - relabel_blocks - hub_blocks;
+    const int64_t nblocks = (int64_t) gridDim.x - relabel_blocks - hub_blocks;
     const int32_t R = a.st->num_dst[a.layer_index];
     constexpr int kRowsPerWave = kWave / G;
-    const int64_t wave_global = block * (kBlock / kWave) +
-                                __builtin_amdgcn_readfirstlane((int) (threadIdx.x >> 6));
+    const int64_t wave_global = block * (kBlock / kWave) + wave_in_block;
     const int64_t num_waves = nblocks * (kBlock / kWave);
     for (int64_t row0 = wave_global * kRowsPerWave; row0 < R; row0 += num_waves * kRowsPerWave) {
         const int lane = opaque_lane_id();
         const int s = lane & (G - 1);
         const int64_t row = row0 + (lane / G);
-        const bool live = row < R;
+        bool live = row < R;
         int32_t vi = -1;
         int64_t start = 0, end = 0;
         if (live) {
@@ -477,21 +490,8 @@ __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs
             start = ext.start;
             end = ext.end;
         }
-        const bool hub = (G < 64) && live && chunks_touched(start, end) > G * kHubSteps;
-        select_row<G, 1>(a, row, live && !hub, s, start, end, vi);
-        if (G < 64) {
-            uint64_t hubs = __ballot(hub && s == 0);                 // wave-uniform
-            while (hubs) {
-                const int src = __builtin_ctzll(hubs);               // a lane of the hub's group
-                hubs &= hubs - 1;
-                const int lane64 = opaque_lane_id();
-                const int64_t h_row = row0 + src / G;
-                const int64_t h_start = __shfl(start, src, kWave);
-                const int64_t h_end = __shfl(end, src, kWave);
-                const int32_t h_vi = __shfl(vi, src, kWave);
-                select_row<64, kHubWords>(a, h_row, true, lane64, h_start, h_end, h_vi);
-            }
-        }
+        if (hub_blocks > 0 && is_hub_extent(start, end)) live = false;      // taken by a hub wave
+        select_row<G, 1>(a, row, live, s, start, end, vi);
     }
 }
 
@@ -531,6 +531,7 @@ static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nod
     a.indices = c->graph.indices;
     a.dst_nodes = dst_nodes;
     a.row_ext = ws_ptr<RowExtent>(c, L.row_ext);
+    a.hub_rows = ws_ptr<int32_t>(c, L.hub_rows);
     a.node_inv_pc = c->uses_cache ? ws_ptr<float>(c, L.node_pc) : nullptr;
     a.cache_bitmap = ws_ptr<uint64_t>(c, L.cache_bitmap);
     a.cache_prefix = ws_ptr<int32_t>(c, L.cache_prefix);
@@ -580,15 +581,15 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
     if (row_blocks < 1) row_blocks = 1;
     const dim3 tb(kBlock);
 
-#define GNS_LAUNCH_BY_G(KERNEL, RL)                                                      \
-    do {                                                                                 \
-        const dim3 rb((unsigned) (row_blocks + (RL)));                                   \
-        if (G == 8)       hipLaunchKernelGGL((KERNEL<8>), rb, tb, 0, s, a, prev, (RL));  \
-        else if (G == 16) hipLaunchKernelGGL((KERNEL<16>), rb, tb, 0, s, a, prev, (RL)); \
-        else              hipLaunchKernelGGL((KERNEL<64>), rb, tb, 0, s, a, prev, (RL)); \
+#define GNS_LAUNCH_BY_G(KERNEL, RL, ...)                                                              \
+    do {                                                                                              \
+        if (G == 8)       hipLaunchKernelGGL((KERNEL<8>), rb, tb, 0, s, a, prev, (RL), ##__VA_ARGS__);  \
+        else if (G == 16) hipLaunchKernelGGL((KERNEL<16>), rb, tb, 0, s, a, prev, (RL), ##__VA_ARGS__); \
+        else              hipLaunchKernelGGL((KERNEL<64>), rb, tb, 0, s, a, prev, (RL), ##__VA_ARGS__); \
     } while (0)
 
     if (c->config.policy[layer_index] == GNS_UNIFORM) {
+        const dim3 rb((unsigned) (row_blocks + rl));
         GNS_LAUNCH_BY_G(k_sample_uniform, rl);
         return hipGetLastError();
     }
@@ -606,7 +607,11 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
         launch_flag_kernel(c, a, 1, 0, s);
     }
     StageTimer t(c, GNS_STAGE_SELECT, s);
-    GNS_LAUNCH_BY_G(k_select_rows, rl);
+    // hub rows get dedicated waves (the count lives on the device; the waves stride over the list)
+    const int hub_blocks = (G < 64) ? (int) (rows_max / (kBlock / kWave) < (int64_t) c->num_cus * 2
+                                                 ? rows_max / (kBlock / kWave) + 1 : (int64_t) c->num_cus * 2) : 0;
+    const dim3 rb((unsigned) (row_blocks + rl + hub_blocks));
+    GNS_LAUNCH_BY_G(k_select_rows, rl, hub_blocks);
 #undef GNS_LAUNCH_BY_G
     return hipGetLastError();
 }
