@@ -86,6 +86,7 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     // per-batch scratch (every forked context has its own copy of these sections)
     L.state = take(sizeof(DeviceState) + 64);
     L.mark_bitmap = take((size_t) L.words * 8);
+    L.seed_copy = take((size_t) cfg->max_seeds * 4);
     L.row_ext = take((size_t) L.rows[cfg->num_layers] * 16);
     L.hub_rows = take((size_t) L.rows[cfg->num_layers] * 4);
     L.hash_slots[0] = take((size_t) L.hash_cap * 8);
@@ -146,7 +147,9 @@ static gns_status enqueue_batch(gns_ctx* c, uint64_t seed, const int32_t* seeds_
     const int nl = c->config.num_layers;
     hipError_t e = launch_batch_begin(c, seed, seeds_dev, num_seeds, c->batch_id + 1, s);
     if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "batch begin", e);
-    const int32_t* dst = seeds_dev;
+    // the batch's kernels read the seeds from the context's own copy (made by the first kernel), so
+    // the captured launch sequence does not depend on where the caller keeps them
+    const int32_t* dst = ws_ptr<int32_t>(c, c->lay.seed_copy);
     const int32_t* prev_dst = nullptr;
     for (int i = 0; i < nl; ++i) {
         {
@@ -178,16 +181,16 @@ static void graph_release(gns_ctx* c, int par)
 }
 
 // The batch's launch sequence does not depend on the data (grids are sized for the worst
-// case and counts stay on the device), so it is captured once per set of caller buffers and
-// hash-map parity, and replayed with hipGraphLaunch; only the first kernel's scalar arguments
-// (seed, seed count, batch id) change between replays.
+// case and counts stay on the device), so it is captured once per set of caller block buffers and
+// hash-map parity, and replayed with hipGraphLaunch; only the first kernel's arguments (seeds
+// pointer, seed, seed count, batch id) change between replays.
 static gns_status launch_batch_graph(gns_ctx* c, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
                                      gns_block* blocks, hipStream_t s)
 {
     const int nl = c->config.num_layers;
     const int par = c->hash_parity;
     BatchGraph& g = c->bg[par];
-    bool same = g.valid && g.seeds == seeds_dev;
+    bool same = g.valid;
     for (int i = 0; same && i < nl; ++i) {
         const gns_block& a = g.blocks[i];
         const gns_block& b = blocks[i];
@@ -220,7 +223,6 @@ static gns_status launch_batch_graph(gns_ctx* c, uint64_t seed, const int32_t* s
             if (kp.func == batch_first_kernel()) g.first = nodes[i];
         }
         if (!g.first) { graph_release(c, par); return ctx_fail(c, GNS_EHIP, "first kernel node not found in the captured graph"); }
-        g.seeds = seeds_dev;
         for (int i = 0; i < nl; ++i) g.blocks[i] = blocks[i];
         g.valid = true;
     }

@@ -57,7 +57,8 @@ hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s)
 
 // ---------------------------------------------------------------------------
 // First kernel of a mini-batch: publishes the batch's scalars (number of seeds, Philox key) in
-// the device state and inserts the seeds, with their local ids, into this batch's hash map.  The
+// the device state, copies the seeds into the context and inserts them, with their local ids, into
+// this batch's hash map.  The
 // map is already empty: the context keeps two, and every batch empties the other one for its
 // successor (see k_relabel_last).  A bad seed is reported by stamping the batch id, so no flag
 // needs resetting while other blocks may be setting it.
@@ -71,6 +72,7 @@ struct BeginArgs {
     const void* g_indptr;
     int g_i64;
     int32_t* hub_rows;
+    int32_t* seed_copy;
 };
 
 __global__ void __launch_bounds__(kBlock) k_batch_begin(BeginArgs a, int32_t num_seeds, uint32_t key0, uint32_t key1,
@@ -91,6 +93,7 @@ __global__ void __launch_bounds__(kBlock) k_batch_begin(BeginArgs a, int32_t num
             ext.start = load_off_rt(a.g_indptr, a.g_i64, u);
             ext.end = load_off_rt(a.g_indptr, a.g_i64, (int64_t) u + 1);
         }
+        a.seed_copy[q] = u;
         a.row_ext[q] = ext;
         append_hub_rows(a.st, a.hub_rows, is_hub_extent(ext.start, ext.end), (int32_t) q);
         const bool ok = in_range && hash_insert(a.slots, a.hmask, a.hshift, (uint32_t) u, (uint32_t) q);
@@ -117,6 +120,7 @@ void fill_begin_args(gns_ctx* c, const int32_t* seeds, BeginArgsHost* out)
     a->g_indptr = c->graph.indptr;
     a->g_i64 = c->graph.indptr_is_i64;
     a->hub_rows = ws_ptr<int32_t>(c, L.hub_rows);
+    a->seed_copy = ws_ptr<int32_t>(c, L.seed_copy);
 }
 
 hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, uint32_t batch_id,

@@ -30,6 +30,7 @@ struct Layout {
     size_t draw_keys, draw_vals, draw_node, draw_slot;
     // frontier structures
     size_t mark_bitmap;
+    size_t seed_copy;         // [max_seeds] the batch's seeds, copied by its first kernel
     size_t hub_rows;          // [max nodes of a batch] rows whose CSR segment spans more than kHubChunks chunks
     size_t row_ext;           // [max nodes of a batch] CSR extent of every node of the batch's list (append-only)
     size_t hash_slots[2];     // consecutive batches alternate: each one leaves the other map empty for the next
@@ -71,8 +72,7 @@ struct BatchGraph {
     hipGraphExec_t exec;
     hipGraphNode_t first;            // the k_batch_begin node
     bool valid;
-    const int32_t* seeds;            // capture key: seeds pointer and block buffers
-    gns_block blocks[GNS_MAX_LAYERS];
+    gns_block blocks[GNS_MAX_LAYERS];   // capture key: the caller's block buffers
 };
 struct ProfileRecord {
     int32_t stage;
