@@ -54,8 +54,9 @@ def main():
     ap.add_argument("--cpu-batches", type=int, default=32, help="mini-batches the CPU oracle is timed on (0: skip)")
     ap.add_argument("--slots", type=int, default=4,
                     help="mini-batches kept in flight in pass A (one context + stream each; they share the cache)")
-    ap.add_argument("--flag-mode", type=int, default=0,
-                    help="0: cache-membership flags per mini-batch (CSR-segment scan); 1: once per cache draw")
+    ap.add_argument("--flag-mode", type=int, default=1,
+                    help="cache-membership flags of the CSR entries: 1 (default) once per cache draw, inside the timed "
+                         "region like the draw itself; 0 per mini-batch, for the dst rows' CSR segments only")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference point for rocprofv3 byte counters)")
     ap.add_argument("--skip-pass-a", action="store_true", help="profiling aid: only the single-stream pass")
@@ -196,9 +197,9 @@ def main():
     alg = {
         # CSR segments streamed once + the work list read + one flag word written per chunk + the bitmap once
         "flag": avg["scanned_entries"] * 4 + avg["chunks"] * (4 + 8) + (n + 7) // 8,
-        # per row: dst id, two offsets, count + eligible out; the row's flag words; per edge: index read,
-        # two offsets of the sampled node, id + weight written
-        "select": avg["rows"] * (4 + 2 * off_bytes + 8) + avg["chunks"] * 8 + avg["edges"] * (4 + 2 * off_bytes + 8),
+        # per row: dst id, its CSR extent, count + eligible out; the row's flag words; per edge: index read,
+        # 1/p^C of the sampled node, id + weight written
+        "select": avg["rows"] * (4 + 16 + 8) + avg["chunks"] * 8 + avg["edges"] * (4 + 4 + 8),
         "gather": avg["input_nodes"] * (F * 4 * 2 + 4),
         "aggregate": avg["input_nodes"] * F * 4 + avg["rows"] * (F * 4 + 4) + avg["edges"] * 8,
     }

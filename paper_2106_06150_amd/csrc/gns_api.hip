@@ -57,7 +57,9 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     const int64_t C = uses_cache ? cfg->cache_size : 0;
     L.words = (n + 63) / 64;
     L.word_tiles = (L.words + kTile - 1) / kTile;
-    L.mark_tiles = (L.words + kMarkTile - 1) / kMarkTile;
+    L.mark_tile_words = kMarkTileMin;
+    while (L.mark_tile_words < kMarkTileMax && L.words / L.mark_tile_words > 2048) L.mark_tile_words *= 2;
+    L.mark_tiles = (L.words + L.mark_tile_words - 1) / L.mark_tile_words;
 
     // worst-case frontier growth: rows[i+1] = min(rows[i] * (1 + k_i), n)
     L.rows[0] = cfg->max_seeds;

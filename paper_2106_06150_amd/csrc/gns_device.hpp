@@ -9,7 +9,8 @@ constexpr int kWave = 64;
 constexpr int kBlock = 256;                 // threads per block for the scan-style kernels
 constexpr int kItems = 8;                   // items per thread in a scan tile
 constexpr int kTile = kBlock * kItems;      // 2048 items per scan tile
-constexpr int kMarkTile = kBlock;           // frontier mark bitmap: one 64-bit word per thread
+constexpr int kMarkTileMin = 64;             // frontier mark bitmap: words per tile, a power of two chosen per graph
+constexpr int kMarkTileMax = 4 * kBlock;     //   so that the tiles number a thousand or two (at most 4 words per thread)
 
 constexpr uint32_t kTagCache = 0x43414348u;     // 'CACH'
 constexpr uint32_t kTagNeighbor = 0x4E424853u;  // 'NBHS'

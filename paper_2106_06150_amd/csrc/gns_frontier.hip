@@ -154,8 +154,10 @@ __global__ void __launch_bounds__(kBlock) k_finish_phase1(FinishArgs a)
         if (threadIdx.x == 0) a.sums_rows[blockIdx.x] = sum;
     } else {
         const int32_t tile = (int32_t) blockIdx.x - a.row_tiles_max;
-        const int64_t w = (int64_t) tile * kMarkTile + threadIdx.x;
-        int32_t sum = (w < a.words) ? __popcll(a.mark[w]) : 0;
+        const int64_t base = (int64_t) tile * a.mark_tile_words;
+        int32_t sum = 0;
+        for (int i = (int) threadIdx.x; i < a.mark_tile_words; i += kBlock)
+            if (base + i < a.words) sum += __popcll(a.mark[base + i]);
         sum = block_sum(sum, smem);
         if (threadIdx.x == 0) a.sums_marks[tile] = sum;
     }
@@ -174,8 +176,8 @@ __device__ __forceinline__ int32_t block_sum_array(const int32_t* vals, int32_t 
 __global__ void __launch_bounds__(kBlock) k_finish_phase3(FinishArgs a)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
-    __shared__ int32_t s_off[kMarkTile + 1];
-    __shared__ uint64_t s_word[kMarkTile];
+    __shared__ int32_t s_off[kMarkTileMax + 1];
+    __shared__ uint64_t s_word[kMarkTileMax];
     const int32_t R = a.st->num_dst[a.layer_index];
     const int32_t row_tiles = (R + kTile - 1) / kTile;
     if ((int32_t) blockIdx.x < a.row_tiles_max) {
@@ -207,23 +209,41 @@ __global__ void __launch_bounds__(kBlock) k_finish_phase3(FinishArgs a)
         }
     } else {
         const int32_t tile = (int32_t) blockIdx.x - a.row_tiles_max;
-        const int64_t base = (int64_t) tile * kMarkTile;
+        const int T = a.mark_tile_words;
+        const int64_t base = (int64_t) tile * T;
         const int32_t before = block_sum_array(a.sums_marks, tile, smem);
         const int32_t here = a.sums_marks[tile];
         if (tile == a.mark_tiles - 1 && threadIdx.x == 0) a.st->num_dst[a.layer_index + 1] = R + before + here;
         if (here == 0) return;
-        // one bitmap word per thread; exclusive offsets of the tile's words into LDS
-        const int64_t w = base + threadIdx.x;
-        const uint64_t word = (w < a.words) ? a.mark[w] : 0ull;
+        // thread t owns words t*per .. t*per+per-1 of the tile (per = 1 for tiles of up to kBlock words);
+        // exclusive offsets of the tile's words into LDS
+        constexpr int kPerMax = kMarkTileMax / kBlock;
+        const int per = T > kBlock ? T / kBlock : 1;
+        const int first = (int) threadIdx.x * per;
+        uint64_t word[kPerMax];
+        int32_t cnt = 0;
+#pragma unroll
+        for (int i = 0; i < kPerMax; ++i) {
+            const int64_t w = base + first + i;
+            word[i] = (i < per && first + i < T && w < a.words) ? a.mark[w] : 0ull;
+            cnt += __popcll(word[i]);
+        }
         int32_t total;
-        s_off[threadIdx.x] = block_exclusive_scan(__popcll(word), smem, &total);
-        s_word[threadIdx.x] = word;
-        if (threadIdx.x == 0) s_off[kMarkTile] = total;
-        if (word) a.mark[w] = 0ull;                                  // ready for the next layer
+        int32_t off = block_exclusive_scan(cnt, smem, &total);
+#pragma unroll
+        for (int i = 0; i < kPerMax; ++i) {
+            if (i < per && first + i < T) {
+                s_off[first + i] = off;
+                s_word[first + i] = word[i];
+                off += __popcll(word[i]);
+                if (word[i]) a.mark[base + first + i] = 0ull;        // ready for the next layer
+            }
+        }
+        if (threadIdx.x == 0) s_off[T] = total;
         __syncthreads();
         // one thread per new node: locate its word (last word whose offset is <= j), then its bit
         for (int32_t j = (int32_t) threadIdx.x; j < total; j += kBlock) {
-            int32_t lo = 0, hi = kMarkTile;                          // answer in [lo, hi)
+            int32_t lo = 0, hi = T;                                  // answer in [lo, hi)
             while (hi - lo > 1) {
                 const int32_t mid = (lo + hi) >> 1;
                 if (s_off[mid] <= j) lo = mid; else hi = mid;
@@ -263,6 +283,7 @@ void fill_finish_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, con
     a.sums_marks = ws_ptr<int32_t>(c, L.sums_marks);
     a.row_tiles_max = (int32_t) ((L.rows[layer_index] + kTile - 1) / kTile);
     a.mark_tiles = (int32_t) L.mark_tiles;
+    a.mark_tile_words = L.mark_tile_words;
     a.indptr = blk->indptr;
     a.indices = blk->indices;
     a.weights = blk->weights;

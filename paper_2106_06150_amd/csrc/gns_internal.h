@@ -47,7 +47,8 @@ struct Layout {
     // sizes
     int64_t words;            // ceil(n / 64)
     int64_t word_tiles;       // ceil(words / kTile)
-    int64_t mark_tiles;       // ceil(words / kMarkTile)
+    int32_t mark_tile_words;  // bitmap words per frontier tile (kMarkTileMin .. kMarkTileMax, a power of two)
+    int64_t mark_tiles;       // ceil(words / mark_tile_words)
     int64_t row_tiles;        // ceil(max rows / kTile)
     int64_t draw_chunk;       // stream draws processed per round of the cache draw
     int64_t draw_tiles;

@@ -20,7 +20,8 @@ struct FinishArgs {
     int32_t* sums_rows;            // [row_tiles + 1]
     int32_t* sums_marks;           // [mark_tiles + 1]
     int32_t row_tiles_max;         // grid split point: blocks [0, row_tiles_max) work on rows
-    int32_t mark_tiles;            // tiles of kMarkTile bitmap words
+    int32_t mark_tiles;            // tiles of mark_tile_words bitmap words
+    int32_t mark_tile_words;
     int32_t* indptr;               // block outputs
     int32_t* indices;
     float* weights;
