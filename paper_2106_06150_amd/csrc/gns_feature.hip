@@ -131,6 +131,78 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggArgs a)
     const int64_t count = a.num_dst_dev ? (int64_t) *a.num_dst_dev : (int64_t) a.num_dst;
     const uint32_t num_src = (uint32_t) (a.num_src_dev ? *a.num_src_dev : a.num_src);
     constexpr int kEdges = 8;       // edges whose rows are in flight together
+    if (kVec && F <= 4 * kLanes) {
+        // One float4 per lane covers a row.  The three dependent reads of a row (its offsets, its
+        // edges, its sources' rows) are staggered over three consecutive rows of the group, so every
+        // trip of the loop issues all three kinds of load before it waits for any of them:
+        //   row i: source rows -> fma;  row i+1: indices and weights;  row i+2: offsets.
+        const float4* x4 = reinterpret_cast<const float4*>(a.x_src);
+        const int64_t F4 = F >> 2;
+        const bool has = lane < (int) F4;
+        int32_t b0 = 0, e0 = 0, b1 = 0, e1 = 0, b2 = 0, e2 = 0;          // offsets of rows i, i+1, i+2
+        uint32_t j1[kEdges];                                              // first kEdges edges of row i+1
+        float w1[kEdges];
+        const int64_t r0 = group, r1 = group + num_groups, r2 = group + 2 * num_groups;
+        if (r0 < count) { b0 = a.indptr[r0]; e0 = a.indptr[r0 + 1]; }
+        if (r1 < count) { b1 = a.indptr[r1]; e1 = a.indptr[r1 + 1]; }
+        if (r2 < count) { b2 = a.indptr[r2]; e2 = a.indptr[r2 + 1]; }
+#pragma unroll
+        for (int t = 0; t < kEdges; ++t) {                                // edges of row i (kept in j1 / w1)
+            const int32_t q = b0 + t;
+            j1[t] = (q < e0) ? (uint32_t) a.indices[q] : 0xFFFFFFFFu;
+            w1[t] = (q < e0) ? a.weights[q] : 0.f;
+        }
+        for (int64_t row = group; row < count; row += num_groups) {
+            // (1) source rows of this row's first kEdges edges
+            float4 x[kEdges];
+            float w[kEdges];
+#pragma unroll
+            for (int t = 0; t < kEdges; ++t) {
+                const bool ok = j1[t] < num_src;
+                w[t] = ok ? w1[t] : 0.f;
+                x[t] = (ok && has) ? x4[(int64_t) j1[t] * F4 + lane] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            // (2) edges of the next row, (3) offsets of the row after the next
+#pragma unroll
+            for (int t = 0; t < kEdges; ++t) {
+                const int32_t q = b1 + t;
+                j1[t] = (q < e1) ? (uint32_t) a.indices[q] : 0xFFFFFFFFu;
+                w1[t] = (q < e1) ? a.weights[q] : 0.f;
+            }
+            const int64_t r3 = row + 3 * num_groups;
+            int32_t b3 = 0, e3 = 0;
+            if (r3 < count) { b3 = a.indptr[r3]; e3 = a.indptr[r3 + 1]; }
+
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int t = 0; t < kEdges; ++t) {                            // edge order, one fma per term
+                if (b0 + t < e0) {
+                    acc.x = fmaf(w[t], x[t].x, acc.x);
+                    acc.y = fmaf(w[t], x[t].y, acc.y);
+                    acc.z = fmaf(w[t], x[t].z, acc.z);
+                    acc.w = fmaf(w[t], x[t].w, acc.w);
+                }
+            }
+            for (int32_t q = b0 + kEdges; q < e0; ++q) {                  // rows with more edges: the rest in order
+                const uint32_t j = (uint32_t) a.indices[q];
+                if (j < num_src && has) {
+                    const float wq = a.weights[q];
+                    const float4 xq = x4[(int64_t) j * F4 + lane];
+                    acc.x = fmaf(wq, xq.x, acc.x);
+                    acc.y = fmaf(wq, xq.y, acc.y);
+                    acc.z = fmaf(wq, xq.z, acc.z);
+                    acc.w = fmaf(wq, xq.w, acc.w);
+                }
+            }
+            if (e0 > b0) {
+                const float n_v = (float) (e0 - b0);
+                acc.x /= n_v; acc.y /= n_v; acc.z /= n_v; acc.w /= n_v;
+            }
+            if (has) reinterpret_cast<float4*>(a.out + row * F)[lane] = acc;
+            b0 = b1; e0 = e1; b1 = b2; e1 = e2; b2 = b3; e2 = e3;
+        }
+        return;
+    }
     for (int64_t row = group; row < count; row += num_groups) {
         const int32_t b = a.indptr[row], e = a.indptr[row + 1];
         const float n_v = (float) (e - b);
