@@ -171,7 +171,7 @@ def main():
     # ---- untimed replay with host-visible counts: algorithmic bytes per launch, shape statistics
     start_all = g.indptr[:-1].to(torch.int64)
     end_all = g.indptr[1:].to(torch.int64)
-    acc = dict(rows=0, scanned_entries=0, chunks=0, edges=0, input_nodes=0, cached_input=0, eligible=0)
+    acc = dict(rows=0, scanned_entries=0, chunks=0, edges=0, input_nodes=0, cached_input=0, eligible=0, read_rows=0)
     blocks = bufs[0]
     for b in range(W, total):
         if b % refresh == 0:
@@ -191,6 +191,7 @@ def main():
         acc["input_nodes"] += blk.num_src
         acc["cached_input"] += blk.num_src - rows
         acc["eligible"] += int(v["row_eligible"].sum())
+        acc["read_rows"] += int(torch.unique(v["indices"][:blk.num_edges]).numel())    # distinct source rows of the layer
     torch.cuda.synchronize()
     avg = {k: v / K for k, v in acc.items()}
     # algorithmic bytes per launch of each single-kernel stage (averages over the K steps)
@@ -201,7 +202,8 @@ def main():
         # 1/p^C of the sampled node, id + weight written
         "select": avg["rows"] * (4 + 16 + 8) + avg["chunks"] * 8 + avg["edges"] * (4 + 4 + 8),
         "gather": avg["input_nodes"] * (F * 4 * 2 + 4),
-        "aggregate": avg["input_nodes"] * F * 4 + avg["rows"] * (F * 4 + 4) + avg["edges"] * 8,
+        # every distinct source row read once, every dst row written once, offsets, and index + weight per edge
+        "aggregate": avg["read_rows"] * F * 4 + avg["rows"] * (F * 4 + 4) + avg["edges"] * 8,
     }
     kernel_of = {"flag": "k_flag_chunks", "select": "k_select_rows", "gather": "k_gather", "aggregate": "k_aggregate"}
     candidates = [s_ for s_ in alg if s_ in stage_us]
