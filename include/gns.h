@@ -190,12 +190,13 @@ gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_d
                              gns_block* blocks, void* hip_stream);
 
 /* The same work without the final synchronisation, for callers that keep several
- * mini-batches in flight.  gns_sample_blocks_async validates, enqueues everything
- * (including the copy of the counts to pinned host memory) and returns; until
+ * mini-batches in flight.  gns_sample_blocks_async validates, enqueues the batch's
+ * kernels and returns (seeds_dev is read by the first of them: keep it unchanged until
+ * the stream has passed that point); until
  * gns_sample_blocks_wait the blocks' host counts hold the placeholder
  * GNS_DEVICE_COUNTS(layer_index), which gns_aggregate understands (see there).
- * gns_sample_blocks_wait synchronises the stream, fills in the counts and reports
- * GNS_EINVAL for bad seeds.  gns_sample_blocks is exactly async followed by wait.
+ * gns_sample_blocks_wait copies the counts to the host, synchronises the stream, fills
+ * them in and reports GNS_EINVAL for bad seeds.  gns_sample_blocks is exactly async followed by wait.
  * Between the two calls no other call may use the context's block state except
  * gns_gather_features / gns_aggregate on the same stream. */
 #define GNS_DEVICE_COUNTS(layer_index) (-1 - (layer_index))
@@ -218,15 +219,16 @@ gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t n
  * weights[e] * x_src_dev[indices[e], :], n_v = row length, zeros for an empty
  * row.  x_src_dev is fp32[block->num_src x feat_dim], out_dev is
  * fp32[block->num_dst x feat_dim], both row-major.  fp32 arithmetic, edges
- * accumulated in row order.  Uses the block's host counts; if block->num_dst is
+ * accumulated in row order.  An edge whose index lies outside [0, num_src) is skipped.  Uses the block's host counts; if block->num_dst is
  * GNS_DEVICE_COUNTS(i) the row count of layer index i is read on the device instead
  * (out_dev must then hold cap_dst rows).  Enqueue only. */
 gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_src_dev, int32_t feat_dim,
                          float* out_dev, void* hip_stream);
 
 /* Stage timing for benchmarks (no part of the method).  Stages: GNS_STAGE_SAMPLE + i
- * = the sampler kernel of layer index i; GNS_STAGE_FINISH + i = the union / relabel
- * kernels of layer index i; GNS_STAGE_GATHER; GNS_STAGE_AGGREGATE; GNS_STAGE_PLAN / FLAG /
+ * = the sampler launches of layer index i (the first of them also carries the relabel
+ * of layer index i - 1); GNS_STAGE_FINISH + i = the union kernels of layer index i (and
+ * the last layer's relabel); GNS_STAGE_GATHER; GNS_STAGE_AGGREGATE; GNS_STAGE_PLAN / FLAG /
  * SELECT = the parts of a CACHE_ONLY layer's sampler (also counted in its GNS_STAGE_SAMPLE).
  * gns_profile_begin(ctx, stage_mask, capacity) makes the following calls bracket
  * every launch of a stage whose bit is set in stage_mask with a pair of HIP events on
