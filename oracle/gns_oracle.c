@@ -10,7 +10,8 @@
  *   - cache draw ............ Section 3.2, Eq. (1) (degree-proportional probability),
  *                             Theorem 1 (drawn without replacement, |C| nodes)
  *   - layer sampling ........ Algorithm 1 top-down loop, Section 3.3 (neighbors
- *                             restricted to the cache), Section 4.1 (input layer
+ *                             from the cache first, a shortfall filled uniformly from
+ *                             the rest of the neighborhood), Section 4.1 (input layer
  *                             sampled only from the cache), Section 2.1 (uniform
  *                             node-wise sampling with fan-out k)
  *   - importance weights .... Section 3.4 (p^C_u = 1-(1-p_u)^|C|, coefficient
@@ -23,7 +24,10 @@
  * inside a frontier, how a without-replacement draw is realised) are stated at
  * each function.  Pins: see tests/test_oracle_*.py.  Parity unpinned: the choice
  * of Floyd's subset algorithm, the Philox counter layout and the ascending order
- * of the frontier tail are conventions; only invariants constrain them.
+ * of the frontier tail are conventions; only invariants constrain them.  The same
+ * holds for two choices of the cache-first policy the paper does not fix: that the
+ * fill is drawn from N(v) \ C (so no neighbor is taken twice) and the fill
+ * neighbors' weights (1, or |N(v) \ C| / r in the unbiased mode).
  *
  * All floating point is fp64 with one final rounding to fp32.
  */
@@ -34,6 +38,7 @@
 
 #define GNS_ORACLE_UNIFORM 0
 #define GNS_ORACLE_CACHE_ONLY 1
+#define GNS_ORACLE_CACHE_FIRST 2
 #define GNS_ORACLE_W_PRINTED 0
 #define GNS_ORACLE_W_UNBIASED 1
 
@@ -201,14 +206,40 @@ float gns_oracle_edge_weight(int64_t deg_u, int64_t nnz, int64_t cache_size, int
     return (float)w;
 }
 
+/* Picks min(k, m) of the m entries of a list: all of them if m <= k, otherwise
+ * Floyd's subset with the Philox words of slots slot0 .. slot0+k-1 of (layer, v).
+ * Ranks come back ascending (= CSR order).  Returns how many were taken.       */
+static int32_t pick_ranks(int64_t m, int32_t k, uint64_t seed, int32_t layer, int64_t v, int32_t slot0, int64_t* ranks)
+{
+    if (m <= k) {
+        for (int32_t s = 0; s < (int32_t)m; ++s) ranks[s] = s;
+        return (int32_t)m;
+    }
+    uint32_t words[64];
+    for (int32_t s = 0; s < k; ++s)
+        words[s] = neighbor_word(seed, (uint32_t)layer, (uint32_t)v, (uint32_t)(slot0 + s));
+    gns_oracle_floyd(m, k, words, ranks);
+    return k;
+}
+
 /* One layer of Algorithm 1's top-down loop: for every dst row v independently,
  * N_l(v) <- sample(N(v), C).
- *   UNIFORM:    eligible list E(v) = N(v) in CSR order            (Section 2.1)
- *   CACHE_ONLY: E(v) = entries of N(v) whose node is in C         (Sections 3.3, 4.1)
+ *   UNIFORM:     eligible list E(v) = N(v) in CSR order                      (Section 2.1)
+ *   CACHE_ONLY:  E(v) = entries of N(v) whose node is in C                   (Sections 3.3, 4.1)
+ *   CACHE_FIRST: first from E_C(v) = N(v) & C as CACHE_ONLY does; if that gave
+ *                fewer than k (N_C(v) < k), the remaining k - N_C(v) are drawn
+ *                uniformly without replacement from E_N(v) = N(v) \ C           (Section 3.3)
  * m = |E(v)|.  If m <= k all of E(v) is taken; otherwise Floyd picks k ranks
- * with the Philox words of slots 0..k-1.  Chosen neighbors are emitted in
- * ascending rank (= CSR position).  Row v writes out_nbr[r*k .. r*k+cnt),
- * out_w likewise (1.0f for UNIFORM), out_cnt[r] = min(k, m), out_elig[r] = m.
+ * with the Philox words of slots 0..k-1.  CACHE_FIRST's fill draw takes
+ * r = min(k - N_C, |E_N|) ranks of E_N with the words of slots N_C .. N_C+r-1, so a
+ * row's slots are never used twice.  Chosen neighbors are emitted in ascending rank
+ * (= CSR position), cached ones before fill ones.  Row v writes
+ * out_nbr[r*k .. r*k+cnt), out_w likewise, out_cnt[r] = number taken,
+ * out_elig[r] = |E(v)| (N_C(v) for both cache policies).
+ * Weights: UNIFORM 1; cached neighbors Section 3.4 (gns_oracle_edge_weight with
+ * N_C(v)); fill neighbors 1 in the printed mode (they are a node-wise sample,
+ * Section 2.1), |E_N|/r in the unbiased mode (inverse inclusion probability of a
+ * uniform r-subset, given the cache).
  * Returns 0, or -1 on bad arguments.                                          */
 int gns_oracle_sample_layer(int64_t n, const int64_t* indptr, const int32_t* indices,
                             const uint64_t* cache_bitmap, int64_t cache_size,
@@ -217,47 +248,47 @@ int gns_oracle_sample_layer(int64_t n, const int64_t* indptr, const int32_t* ind
                             int32_t* out_nbr, float* out_w, int32_t* out_cnt, int32_t* out_elig)
 {
     if (k <= 0 || k > 64) return -1;
-    if (policy == GNS_ORACLE_CACHE_ONLY && !cache_bitmap) return -1;
+    if (policy != GNS_ORACLE_UNIFORM && !cache_bitmap) return -1;
     int64_t nnz = indptr[n];
     for (int64_t r = 0; r < num_dst; ++r) {
         int64_t v = dst_nodes[r];
         if (v < 0 || v >= n) return -1;
         int64_t start = indptr[v], deg = indptr[v + 1] - start;
         int32_t* elig = (int32_t*)malloc((size_t)(deg > 0 ? deg : 1) * sizeof(int32_t));
-        if (!elig) return -1;
-        int64_t m = 0;
+        int32_t* rest = (int32_t*)malloc((size_t)(deg > 0 ? deg : 1) * sizeof(int32_t));
+        if (!elig || !rest) { free(elig); free(rest); return -1; }
+        int64_t m = 0, m_rest = 0;
         for (int64_t e = 0; e < deg; ++e) {
             int32_t u = indices[start + e];
             int ok = 1;
-            if (policy == GNS_ORACLE_CACHE_ONLY)
+            if (policy != GNS_ORACLE_UNIFORM)
                 ok = (int)((cache_bitmap[u >> 6] >> (u & 63)) & 1u);
-            if (ok) elig[m++] = u;
+            if (ok) elig[m++] = u; else rest[m_rest++] = u;
         }
         int64_t ranks[64];
-        int32_t cnt;
-        if (m <= k) {
-            cnt = (int32_t)m;
-            for (int32_t s = 0; s < cnt; ++s) ranks[s] = s;
-        } else {
-            uint32_t words[64];
-            for (int32_t s = 0; s < k; ++s)
-                words[s] = neighbor_word(seed, (uint32_t)layer, (uint32_t)v, (uint32_t)s);
-            gns_oracle_floyd(m, k, words, ranks);
-            cnt = k;
-        }
+        int32_t cnt = pick_ranks(m, k, seed, layer, v, 0, ranks);
         for (int32_t s = 0; s < cnt; ++s) {
             int32_t u = elig[ranks[s]];
             out_nbr[r * k + s] = u;
-            if (policy == GNS_ORACLE_CACHE_ONLY) {
+            if (policy == GNS_ORACLE_UNIFORM) {
+                out_w[r * k + s] = 1.0f;
+            } else {
                 int64_t deg_u = indptr[(int64_t)u + 1] - indptr[u];
                 out_w[r * k + s] = gns_oracle_edge_weight(deg_u, nnz, cache_size, k, m, wmode);
-            } else {
-                out_w[r * k + s] = 1.0f;
             }
+        }
+        if (policy == GNS_ORACLE_CACHE_FIRST && cnt < k && m_rest > 0) {
+            int32_t fill = pick_ranks(m_rest, k - cnt, seed, layer, v, cnt, ranks);
+            for (int32_t s = 0; s < fill; ++s) {
+                out_nbr[r * k + cnt + s] = rest[ranks[s]];
+                out_w[r * k + cnt + s] = (wmode == GNS_ORACLE_W_UNBIASED) ? (float)((double)m_rest / (double)fill) : 1.0f;
+            }
+            cnt += fill;
         }
         out_cnt[r] = cnt;
         out_elig[r] = (int32_t)m;
         free(elig);
+        free(rest);
     }
     return 0;
 }

@@ -13,6 +13,7 @@ import numpy as np
 
 UNIFORM = 0
 CACHE_ONLY = 1
+CACHE_FIRST = 2
 W_PRINTED = 0
 W_UNBIASED = 1
 

@@ -171,3 +171,118 @@ def test_unbiased_weights_expectation_closed_form():
         vals[seed] = sum(float(w[0, s]) * x[nbr[0, s]] for s in range(cnt[0]))
     z = (vals.mean() - expect) / (vals.std(ddof=1) / np.sqrt(T))
     assert abs(z) < 4.5, (vals.mean(), expect)
+
+
+# ---------------------------------------------------------------------------
+# CACHE_FIRST (Section 3.3: from the cache first, the shortfall uniformly from the
+# rest of the neighborhood)
+
+def _split_row(indptr, indices, bitmap, v):
+    row = [int(u) for u in indices[indptr[v]:indptr[v + 1]]]
+    cached = [u for u in row if (int(bitmap[u >> 6]) >> (u & 63)) & 1]
+    rest = [u for u in row if not (int(bitmap[u >> 6]) >> (u & 63)) & 1]
+    return row, cached, rest
+
+
+@pytest.mark.parametrize("k", [1, 4, 9])
+def test_cache_first_invariants_and_reduction_to_the_other_policies(small_graph, k):
+    indptr, indices = small_graph
+    n = len(indptr) - 1
+    c = 60
+    _, bitmap, _ = oracle.sample_cache(indptr, 3, 0, c)
+    dst = np.random.default_rng(6).permutation(n)[:300].astype(np.int32)
+    args = (indptr, indices, bitmap, c, 4321, 2)
+    nbr, w, cnt, elig = oracle.sample_layer(*args, oracle.CACHE_FIRST, oracle.W_PRINTED, k, dst)
+    nbr_c, w_c, cnt_c, _ = oracle.sample_layer(*args, oracle.CACHE_ONLY, oracle.W_PRINTED, k, dst)
+    nbr_u, w_u, cnt_u, _ = oracle.sample_layer(*args, oracle.UNIFORM, oracle.W_PRINTED, k, dst)
+    seen = dict(full_cache=0, no_cache=0, mixed_subset=0, mixed_all=0)
+    for r, v in enumerate(dst):
+        row, cached, rest = _split_row(indptr, indices, bitmap, v)
+        assert elig[r] == len(cached)
+        assert cnt[r] == min(k, len(row))
+        got = nbr[r, :cnt[r]].tolist()
+        assert all(x == -1 for x in nbr[r, cnt[r]:]) and len(set(got)) == len(got)
+        head = min(k, len(cached))
+        # the cached part is exactly what CACHE_ONLY takes, with its weights
+        assert got[:head] == nbr_c[r, :cnt_c[r]].tolist() and cnt_c[r] == head
+        assert np.array_equal(w[r, :head], w_c[r, :head])
+        fill = got[head:]
+        assert len(fill) == min(k - head, len(rest))
+        pos = [rest.index(u) for u in fill]              # members of N(v) \ C ...
+        assert pos == sorted(pos)                        # ... in ascending CSR position
+        assert np.all(w[r, head:cnt[r]] == 1.0)
+        if len(cached) >= k:
+            seen["full_cache"] += 1
+            assert not fill
+        elif not cached:
+            seen["no_cache"] += 1                        # nothing cached: the row's draw is the UNIFORM one
+            assert got == nbr_u[r, :cnt_u[r]].tolist() and np.array_equal(w[r], w_u[r])
+        elif len(rest) > k - head:
+            seen["mixed_subset"] += 1
+        else:
+            seen["mixed_all"] += 1
+            assert fill == rest
+    assert seen["no_cache"] > 0 and seen["full_cache"] > 0, seen
+    if k > 1:                                            # 0 < N_C < k needs k >= 2
+        assert seen["mixed_subset"] > 0, seen
+
+
+def _star_row():
+    # node 0 has neighbors 1..9; 1 and 2 are cached
+    n = 10
+    indptr = np.array([0, 9] + list(range(10, 19)), dtype=np.int64)
+    indices = np.array(list(range(1, 10)) + [0] * 9, dtype=np.int32)
+    bitmap = np.array([0b110], dtype=np.uint64)
+    return n, indptr, indices, bitmap
+
+
+def test_cache_first_fill_is_uniform_over_the_uncached_neighbors():
+    n, indptr, indices, bitmap = _star_row()
+    k = 5                                                 # 2 from the cache, 3 of the 7 others
+    subsets = {s: 0 for s in combinations(range(3, 10), 3)}
+    T = 35_000
+    dst = np.array([0], dtype=np.int32)
+    for seed in range(T):
+        nbr, _, cnt, elig = oracle.sample_layer(indptr, indices, bitmap, 2, seed, 1, oracle.CACHE_FIRST, 0, k, dst)
+        assert cnt[0] == 5 and elig[0] == 2 and nbr[0, :2].tolist() == [1, 2]
+        subsets[tuple(nbr[0, 2:].tolist())] += 1
+    chi = stats.chisquare(list(subsets.values()))
+    assert chi.pvalue > 1e-4, chi
+
+
+def test_cache_first_fill_uses_its_own_philox_slots():
+    """The fill draw of a row with N_C cached neighbors uses slots N_C, N_C+1, ...: with one cached
+    neighbor and k = 2 the single fill word is slot 1 of the row, i.e. the word that a UNIFORM row
+    draws second."""
+    n, indptr, indices, _ = _star_row()
+    bitmap = np.array([0b10], dtype=np.uint64)            # only node 1 cached; 8 others
+    dst = np.array([0], dtype=np.int32)
+    for seed in range(50):
+        nbr, _, cnt, _ = oracle.sample_layer(indptr, indices, bitmap, 1, seed, 3, oracle.CACHE_FIRST, 0, 2, dst)
+        ctr = (0, 0, 3, 0x4E424853)                       # (node, slot >> 2, layer, tag)
+        word = int(oracle.philox4x32_10(ctr, (seed & 0xFFFFFFFF, seed >> 32))[1])
+        expect = 2 + ((word * 8) >> 32)                   # rank t of the 8 uncached neighbors 2..9
+        assert cnt[0] == 2 and nbr[0].tolist() == [1, expect]
+
+
+def test_cache_first_unbiased_weights_given_the_cache():
+    """Given the cache, sum over fill edges of w*x estimates the sum of x over N(v) \\ C, and
+    the fill weight is |N(v) \\ C| / r exactly; the cached part is taken whole (N_C < k)."""
+    n, indptr, indices, bitmap = _star_row()
+    x = np.array([0.0, 2.0, -1.0, 0.5, 3.0, -2.5, 1.25, 4.0, -0.75, 6.0])
+    k = 4                                                 # 2 cached + 2 of 7
+    dst = np.array([0], dtype=np.int32)
+    T = 30_000
+    vals = np.zeros(T)
+    for seed in range(T):
+        nbr, w, cnt, _ = oracle.sample_layer(indptr, indices, bitmap, 2, seed, 1, oracle.CACHE_FIRST,
+                                             oracle.W_UNBIASED, k, dst)
+        assert np.all(w[0, 2:4] == np.float32(7.0 / 2.0))
+        vals[seed] = float(np.dot(w[0, 2:4].astype(np.float64), x[nbr[0, 2:4]]))
+    expect = x[3:].sum()
+    z = (vals.mean() - expect) / (vals.std(ddof=1) / np.sqrt(T))
+    assert abs(z) < 4.5, (vals.mean(), expect)
+    # cached part: N_C / (min(k, N_C) * p^C) = 1 / p^C
+    p1 = 1.0 / 18.0
+    pc = 1 - (1 - p1) ** 2
+    assert abs(float(w[0, 0]) - 1.0 / pc) < 1e-6 / pc
