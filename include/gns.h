@@ -64,7 +64,10 @@ typedef enum {
 enum {
     GNS_UNIFORM = 0,    /* Section 2.1: min(k, deg(v)) neighbors uniformly without replacement, weight 1 */
     GNS_CACHE_ONLY = 1, /* Sections 3.3 / 4.1: min(k, N_C(v)) of the cached neighbors, weight from Section 3.4 */
-    GNS_CACHE_FIRST = 2 /* Section 3.3 with fill from outside the cache: not provided (GNS_ENOTIMPL) */
+    GNS_CACHE_FIRST = 2 /* Section 3.3: as GNS_CACHE_ONLY; a row with fewer than k cached neighbors then draws
+                           the shortfall uniformly without replacement from its neighbors outside the cache
+                           (slots N_C, N_C + 1, ... of the row's Philox stream); cached neighbors are
+                           emitted first; fill weight 1, or |N(v) \ C| / r with GNS_W_UNBIASED */
 };
 
 /* Section 3.4 rescaling.  p^C_u = 1 - (1 - deg(u)/nnz)^|C|.
@@ -99,7 +102,7 @@ typedef struct {
     int32_t num_layers;               /* L, 1..GNS_MAX_LAYERS                                       */
     int32_t fanout[GNS_MAX_LAYERS];   /* k per layer; index 0 is layer L (next to the seeds), index
                                          L-1 is layer 1 (the input layer); 1..GNS_MAX_FANOUT        */
-    int32_t policy[GNS_MAX_LAYERS];   /* GNS_UNIFORM / GNS_CACHE_ONLY per layer, same indexing      */
+    int32_t policy[GNS_MAX_LAYERS];   /* gns_policy per layer, same indexing                          */
     int64_t cache_size;               /* |C|; 0 if no layer uses the cache                          */
     int32_t wmode;                    /* GNS_W_PRINTED / GNS_W_UNBIASED                             */
     int32_t max_seeds;                /* largest mini-batch |B| the context must accept             */

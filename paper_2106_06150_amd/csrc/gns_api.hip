@@ -282,11 +282,6 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
     *out_ctx = nullptr;
     Layout L;
     if (!compute_layout(graph, config, &L, g_create_err, sizeof(g_create_err))) return GNS_EINVAL;
-    for (int i = 0; i < config->num_layers; ++i)
-        if (config->policy[i] == GNS_CACHE_FIRST) {
-            snprintf(g_create_err, sizeof(g_create_err), "policy GNS_CACHE_FIRST is not provided");
-            return GNS_ENOTIMPL;
-        }
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) {
         snprintf(g_create_err, sizeof(g_create_err), "workspace must be a 256-byte aligned device pointer");
         return GNS_EINVAL;

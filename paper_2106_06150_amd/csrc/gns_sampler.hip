@@ -26,6 +26,7 @@ struct SampleArgs {
     uint32_t layer_number;     // the paper's l = L - layer_index
     int fanout;
     int wmode;
+    int policy;                // GNS_CACHE_ONLY or GNS_CACHE_FIRST for the select kernel
     int64_t num_nodes;
     const void* indptr;
     const int32_t* indices;
@@ -54,33 +55,37 @@ struct SampleArgs {
 };
 
 // Floyd's subset draw inside a group of G consecutive lanes (G a power of two
-// <= 64, k <= G).  Lane s < k ends up with one chosen rank in *val and that
-// rank's position in ascending order in *pos.  Requires m > k.  Every lane of
-// the group must call it.
+// <= 64).  Lane s < k ends up with one chosen rank of {0..m-1} in *val and that
+// rank's position in ascending order in *pos.  Requires m > k.  k may differ from
+// group to group; k_loop >= every group's k must be the same for the whole wave
+// (it bounds the loops that exchange data between lanes).  The word of lane s is
+// slot slot0 + s of (layer, node).  Every lane of the wave must call it.
 template <int G>
-__device__ __forceinline__ void floyd_in_group(uint32_t m, int k, uint32_t key0, uint32_t key1, uint32_t layer,
-                                               uint32_t node, int s, uint32_t* val, int* pos)
+__device__ __forceinline__ void floyd_in_group(uint32_t m, int k, int k_loop, uint32_t key0, uint32_t key1,
+                                               uint32_t layer, uint32_t node, int s, uint32_t* val, int* pos,
+                                               int slot0 = 0)
 {
     s = opaque(s);
-    // slot s draws t_s uniform in [0, m-k+s]
-    const Philox4 r = philox4x32_10(node, (uint32_t) s >> 2, layer, kTagNeighbor, key0, key1);
-    const int sel = s & 3;
+    // lane s draws t_s uniform in [0, m-k+s]
+    const uint32_t slot = (uint32_t) (slot0 + s);
+    const Philox4 r = philox4x32_10(node, slot >> 2, layer, kTagNeighbor, key0, key1);
+    const int sel = (int) (slot & 3u);
     const uint32_t word = sel == 0 ? r.w[0] : sel == 1 ? r.w[1] : sel == 2 ? r.w[2] : r.w[3];
     const uint32_t j_own = m - (uint32_t) k + (uint32_t) s;
     const uint32_t t_own = __umulhi(word, j_own + 1u);
     uint32_t chosen = 0xFFFFFFFFu;              // not yet decided
     const int group_base = opaque_lane_id() & ~(G - 1);
-    const uint64_t group_mask = (G == 64) ? ~0ull : (((1ull << G) - 1ull) << group_base);
-    for (int q = 0; q < k; ++q) {
+    const uint64_t group_mask = (G == 64) ? ~0ull : (((1ull << (G & 63)) - 1ull) << group_base);
+    for (int q = 0; q < k_loop; ++q) {
         const uint32_t t_q = __shfl(t_own, q, G);
         // is t_q already among the ranks decided by slots < q ?
         const uint64_t hit = __ballot(s < q && chosen == t_q) & group_mask;
         if (s == q) chosen = hit ? j_own : t_own;
     }
     int rank = 0;
-    for (int q = 0; q < k; ++q) {
+    for (int q = 0; q < k_loop; ++q) {
         const uint32_t c_q = __shfl(chosen, q, G);
-        rank += (c_q < chosen) ? 1 : 0;
+        rank += (q < k && c_q < chosen) ? 1 : 0;
     }
     *val = chosen;
     *pos = rank;
@@ -127,7 +132,7 @@ __global__ void __launch_bounds__(kBlock) k_sample_uniform(SampleArgs a, FinishA
         uint32_t val;
         int pos;
         // run the draw with a safe size in every lane, then keep it only where it applies
-        floyd_in_group<G>(m > (uint32_t) k ? m : (uint32_t) k + 1u, k, a.st->key0, a.st->key1, a.layer_number, v, s, &val, &pos);
+        floyd_in_group<G>(m > (uint32_t) k ? m : (uint32_t) k + 1u, k, k, a.st->key0, a.st->key1, a.layer_number, v, s, &val, &pos);
         const int cnt = (m > (uint32_t) k) ? k : (int) m;
         if (m <= (uint32_t) k) { val = (uint32_t) s; pos = s; }
         if (live && s < cnt) {
@@ -379,59 +384,78 @@ __device__ __forceinline__ void select_row(const SampleArgs& a, int64_t row, boo
 
     uint32_t val;
     int pos;
-    floyd_in_group<G>(m > (uint32_t) k ? m : (uint32_t) k + 1u, k, a.st->key0, a.st->key1, a.layer_number,
+    floyd_in_group<G>(m > (uint32_t) k ? m : (uint32_t) k + 1u, k, k, a.st->key0, a.st->key1, a.layer_number,
                       (uint32_t) vi, s, &val, &pos);
     const int cnt = (m > (uint32_t) k) ? k : (int) m;
     if (m <= (uint32_t) k) { val = (uint32_t) s; pos = s; }
 
-    // pass 2: lane s < cnt finds the lane, then the word, then the bit that holds its rank
-    int64_t entry = -1;
-    uint32_t run = 0;
-    for (int32_t it = 0; __any(it * G * W < nw); ++it) {
-        uint64_t w[W];
-        int32_t incl = incl_first;
+    // pass 2: lane s < count finds the lane, then the word, then the bit that holds its rank `want` among
+    // the set bits of the row's words (of their complements inside the row when `inverted`)
+    auto locate = [&](uint32_t want, int count, bool inverted) -> int64_t {
+        int64_t entry = -1;
+        uint32_t run = 0;
+        for (int32_t it = 0; __any(it * G * W < nw); ++it) {
+            uint64_t w[W];
+            int32_t incl = incl_first;
 #pragma unroll
-        for (int i = 0; i < W; ++i) w[i] = w_first[i];
-        if (it > 0) incl = group_inclusive_scan<G>(load_words((it * G + s) * W, w), s);   // long rows reload
-        const uint32_t step_total = (uint32_t) __shfl(incl, G - 1, G);
-        const bool mine = s < cnt && entry < 0 && val >= run && val < run + step_total;
-        const uint32_t local = val - run;
-        // owner = number of lanes whose inclusive count is <= local
-        int owner = 0;
-        if (G == 64) {
-            // the whole wave is one group: one ballot per drawn slot instead of one shuffle per lane
-            for (int q = 0; q < k; ++q) {
-                const uint32_t local_q = (uint32_t) __shfl((int) local, q, G);
-                const int below = __popcll(__ballot((uint32_t) incl <= local_q));
-                if (s == q) owner = below;
+            for (int i = 0; i < W; ++i) w[i] = w_first[i];
+            if (it > 0) incl = group_inclusive_scan<G>(load_words((it * G + s) * W, w), s);   // long rows reload
+            if (inverted) {
+                // entries of the row that are not flagged: complement inside [start, end)
+                int32_t c = 0;
+#pragma unroll
+                for (int i = 0; i < W; ++i) {
+                    const int32_t j = (it * G + s) * W + i;
+                    uint64_t valid = (j < nw) ? ~0ull : 0ull;
+                    if (j == 0) valid &= head_mask;
+                    if (j == nw - 1) valid &= tail_mask;
+                    w[i] = ~w[i] & valid;
+                    c += __popcll(w[i]);
+                }
+                incl = group_inclusive_scan<G>(c, s);
             }
-        } else {
-            for (int t = 0; t < G; ++t) owner += ((uint32_t) __shfl(incl, t, G) <= local) ? 1 : 0;
-        }
-        owner = owner < G ? owner : G - 1;
-        uint64_t wo[W];
-        int32_t own_total = 0;
-#pragma unroll
-        for (int i = 0; i < W; ++i) {
-            wo[i] = __shfl(w[i], owner, G);
-            own_total += __popcll(wo[i]);
-        }
-        const int32_t incl_owner = __shfl(incl, owner, G);
-        if (mine) {
-            int32_t rest = (int32_t) local - (incl_owner - own_total);       // rank inside the owner's words
-            int which = 0;
-            uint64_t word = wo[0];
-#pragma unroll
-            for (int i = 0; i < W - 1; ++i) {
-                const int32_t c = __popcll(wo[i]);
-                if (which == i && rest >= c) { rest -= c; which = i + 1; word = wo[i + 1]; }
+            const uint32_t step_total = (uint32_t) __shfl(incl, G - 1, G);
+            const bool mine = s < count && entry < 0 && want >= run && want < run + step_total;
+            const uint32_t local = want - run;
+            // owner = number of lanes whose inclusive count is <= local
+            int owner = 0;
+            if (G == 64) {
+                // the whole wave is one group: one ballot per drawn slot instead of one shuffle per lane
+                for (int q = 0; q < k; ++q) {
+                    const uint32_t local_q = (uint32_t) __shfl((int) local, q, G);
+                    const int below = __popcll(__ballot((uint32_t) incl <= local_q));
+                    if (s == q) owner = below;
+                }
+            } else {
+                for (int t = 0; t < G; ++t) owner += ((uint32_t) __shfl(incl, t, G) <= local) ? 1 : 0;
             }
-            const int bit = select_bit64(word, rest);
-            entry = (g0 + ((int64_t) it * G + owner) * W + which) * 64 + bit;
+            owner = owner < G ? owner : G - 1;
+            uint64_t wo[W];
+            int32_t own_total = 0;
+#pragma unroll
+            for (int i = 0; i < W; ++i) {
+                wo[i] = __shfl(w[i], owner, G);
+                own_total += __popcll(wo[i]);
+            }
+            const int32_t incl_owner = __shfl(incl, owner, G);
+            if (mine) {
+                int32_t rest = (int32_t) local - (incl_owner - own_total);       // rank inside the owner's words
+                int which = 0;
+                uint64_t word = wo[0];
+#pragma unroll
+                for (int i = 0; i < W - 1; ++i) {
+                    const int32_t c = __popcll(wo[i]);
+                    if (which == i && rest >= c) { rest -= c; which = i + 1; word = wo[i + 1]; }
+                }
+                const int bit = select_bit64(word, rest);
+                entry = (g0 + ((int64_t) it * G + owner) * W + which) * 64 + bit;
+            }
+            run += step_total;
         }
-        run += step_total;
-    }
+        return entry;
+    };
 
+    const int64_t entry = locate(val, cnt, false);
     if (live && s < cnt) {
         const int32_t u = a.indices[entry];
         // Section 3.4: coefficient p^C_u * k / min(k, N_C(v)), weight = 1 / coefficient; p^C_u comes
@@ -444,8 +468,35 @@ __device__ __forceinline__ void select_row(const SampleArgs& a, int64_t row, boo
         a.s_w[row * k + pos] = wgt;
         mark_if_new(a, (uint32_t) u);
     }
+
+    // Section 3.3: a row with fewer than k cached neighbors fills up from its other neighbors, drawn
+    // uniformly without replacement with the row's next Philox slots (cnt, cnt + 1, ...).
+    int total = cnt;
+    if (a.policy == GNS_CACHE_FIRST) {
+        const uint32_t others = live ? (uint32_t) (end - start) - m : 0u;        // |N(v) \ C|
+        const int room = k - cnt;
+        const int fill = (others > (uint32_t) room) ? room : (int) others;
+        if (__any(fill > 0)) {
+            uint32_t fval;
+            int fpos;
+            floyd_in_group<G>(others > (uint32_t) room ? others : (uint32_t) room + 1u, room, k, a.st->key0,
+                              a.st->key1, a.layer_number, (uint32_t) vi, s, &fval, &fpos, cnt);
+            if (others <= (uint32_t) room) { fval = (uint32_t) s; fpos = s; }
+            const int64_t fentry = locate(fval, fill, true);
+            if (live && s < fill) {
+                const int32_t u = a.indices[fentry];
+                // fill neighbors: weight 1 (a node-wise sample), or the inverse inclusion probability of a
+                // uniform subset of the uncached neighbors in the unbiased mode
+                const float wgt = (a.wmode == GNS_W_UNBIASED) ? (float) others / (float) fill : 1.0f;
+                a.s_nbr[row * k + cnt + fpos] = u;
+                a.s_w[row * k + cnt + fpos] = wgt;
+                mark_if_new(a, (uint32_t) u);
+            }
+            total = cnt + fill;
+        }
+    }
     if (live && s == 0) {
-        a.s_cnt[row] = cnt;
+        a.s_cnt[row] = total;
         a.row_eligible[row] = (int32_t) m;
     }
 }
@@ -526,6 +577,7 @@ static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nod
     a.layer_number = (uint32_t) (c->config.num_layers - layer_index);
     a.fanout = c->config.fanout[layer_index];
     a.wmode = c->config.wmode;
+    a.policy = c->config.policy[layer_index];
     a.num_nodes = c->graph.num_nodes;
     a.indptr = c->graph.indptr;
     a.indices = c->graph.indices;

@@ -18,7 +18,7 @@ if torch.cuda.is_available():
     from paper_2106_06150_amd import binding as B
     from gpu_harness import GpuGns, full_parity, compare_cache, compare_blocks
 
-U, C = 0, 1
+U, C, CF = 0, 1, 2          # UNIFORM, CACHE_ONLY, CACHE_FIRST
 
 
 def _small(n=3000, avg=14, seed=3, hub=1):
@@ -34,7 +34,8 @@ def _feat(n, F, seed=0):
 @pytest.mark.parametrize("flag_mode", [0, 1])
 @pytest.mark.parametrize("offsets", [torch.int32, torch.int64])
 @pytest.mark.parametrize("fanouts,policies", [((10, 5), (U, C)), ((15, 10, 5), (U, U, C)), ((3, 2, 1), (C, C, C)),
-                                              ((4, 4), (U, U)), ((20, 17), (U, C)), ((6, 12), (U, C))])
+                                              ((4, 4), (U, U)), ((20, 17), (U, C)), ((6, 12), (U, C)),
+                                              ((15, 10, 5), (CF, CF, C)), ((6, 9), (CF, CF)), ((20, 40), (U, CF))])
 def test_small_graph_parity(offsets, fanouts, policies, flag_mode):
     ip, ix = _small()
     n = ip.numel() - 1
@@ -63,10 +64,11 @@ def test_feature_widths_and_host_store(F):
             gns.close()
 
 
-def test_unbiased_weight_mode():
+@pytest.mark.parametrize("policies", [(U, C), (CF, CF)])
+def test_unbiased_weight_mode(policies):
     ip, ix = _small()
     n = ip.numel() - 1
-    gns = GpuGns(ip, ix, _feat(n, 32), fanouts=(8, 3), policies=(U, C), cache_size=400, max_seeds=128,
+    gns = GpuGns(ip, ix, _feat(n, 32), fanouts=(8, 3), policies=policies, cache_size=400, max_seeds=128,
                  wmode=B.GNS_W_UNBIASED)
     try:
         full_parity(gns, cache_seed=4, epoch=2, batch_seed=5, seeds=synth.uniform_seed_batch(n, 128, 9))
@@ -95,12 +97,14 @@ def _star_graph(n, hub_degree, extra_avg, seed):
 
 
 @pytest.mark.parametrize("flag_mode", [0, 1])
+@pytest.mark.parametrize("policy", [C, CF])
 @pytest.mark.parametrize("hub_degree", [1000, 16385, 40000])
-def test_hub_row_spanning_many_flag_words(hub_degree, flag_mode):
+def test_hub_row_spanning_many_flag_words(hub_degree, policy, flag_mode):
     n = 60000
     ip, ix = _star_graph(n, hub_degree, 6, hub_degree)
     assert int(ip[1] - ip[0]) == hub_degree
-    gns = GpuGns(ip, ix, None, fanouts=(5, 7), policies=(C, C), cache_size=3000, max_seeds=16, flag_mode=flag_mode)
+    gns = GpuGns(ip, ix, None, fanouts=(5, 7), policies=(policy, policy), cache_size=3000, max_seeds=16,
+                 flag_mode=flag_mode)
     try:
         seeds = torch.tensor([0, 5, 17, 9, 33], dtype=torch.int32)       # the hub is a seed
         full_parity(gns, cache_seed=2, epoch=0, batch_seed=3, seeds=seeds)
@@ -222,8 +226,8 @@ def test_create_rejects_bad_graphs_and_configs():
         create(ip, ix, cache_size=n + 1)
     assert err.value.status == B.GNS_EINVAL
     with pytest.raises(B.GnsError) as err:
-        create(ip, ix, policies=(B.GNS_CACHE_FIRST,))
-    assert err.value.status == B.GNS_ENOTIMPL
+        create(ip, ix, policies=(7,))
+    assert err.value.status == B.GNS_EINVAL
     with pytest.raises(B.GnsError) as err:
         create(ip, ix, ws_shrink=256)
     assert err.value.status == B.GNS_ECAPACITY
@@ -251,7 +255,7 @@ def _release_cached_memory():
     torch._C._host_emptyCache()
 
 
-def _config_parity(cfg_id, batches, device_gen="cpu", flag_mode=0, check_features=True):
+def _config_parity(cfg_id, batches, device_gen="cpu", flag_mode=0, check_features=True, upper=U):
     """Whole path on one of the five workloads against the oracle.  The big graphs are generated
     on the GPU (same recipe) and copied to the host for the oracle."""
     import time
@@ -272,7 +276,7 @@ def _config_parity(cfg_id, batches, device_gen="cpu", flag_mode=0, check_feature
     print("cfg%d: features ready after %.1fs" % (cfg_id, time.time() - t0), flush=True)
     cache_size = int(c["n"] * c["cache_frac"])
     L = len(c["fanouts"])
-    policies = [U] * (L - 1) + [C]
+    policies = [upper] * (L - 1) + [C]
     gns = GpuGns(indptr, indices, feat, fanouts=c["fanouts"], policies=policies, cache_size=cache_size,
                  max_seeds=c["batch"], feat_on_host=c["feat_on_host"], flag_mode=flag_mode)
     try:
@@ -301,6 +305,13 @@ def test_config1_tiny_graph():
 @pytest.mark.parametrize("flag_mode", [0, 1])
 def test_config2_medium_graph(flag_mode):
     _config_parity(2, batches=2, flag_mode=flag_mode)
+
+
+@pytest.mark.parametrize("flag_mode", [0, 1])
+def test_config2_cache_first_on_the_upper_layers(flag_mode):
+    """The paper's experimental setting (Section 4.1): GNS sampling on layers 3 and 2 with fan-outs
+    15 and 10, the input layer only from the cache."""
+    _config_parity(2, batches=1, flag_mode=flag_mode, upper=CF)
 
 
 def test_async_pipeline_on_forked_contexts():
