@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--flag-mode", type=int, default=1,
                     help="cache-membership flags of the CSR entries: 1 (default) once per cache draw, inside the timed "
                          "region like the draw itself; 0 per mini-batch, for the dst rows' CSR segments only")
+    ap.add_argument("--upper-policy", choices=["uniform", "cache_first"], default="uniform",
+                    help="policy of the layers above the input layer: uniform node-wise sampling (the workload the "
+                         "metric is quoted on) or the paper's cache-first-then-fill (its Section 4.1 setting)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference point for rocprofv3 byte counters)")
     ap.add_argument("--skip-pass-a", action="store_true", help="profiling aid: only the single-stream pass")
@@ -79,7 +82,8 @@ def main():
     fanouts = list(c["fanouts"])
     L = len(fanouts)
     last = L - 1
-    policies = [B.GNS_UNIFORM] * (L - 1) + [B.GNS_CACHE_ONLY]
+    upper = B.GNS_UNIFORM if args.upper_policy == "uniform" else B.GNS_CACHE_FIRST
+    policies = [upper] * (L - 1) + [B.GNS_CACHE_ONLY]
     cache_size = int(n * c["cache_frac"])
     refresh = c.get("refresh_every", 20)
     K, W = args.steps, args.warmup
@@ -281,6 +285,7 @@ def main():
                                   cache_size, refresh, fanouts, batch),
                    "max_degree": g.max_degree, "batches_in_flight": S,
                    "cache_flags": "per mini-batch (CSR-segment scan)" if args.flag_mode == 0 else "per cache draw",
+                   "upper_layers": args.upper_policy,
                    "avg_per_batch": {k: round(v, 1) for k, v in avg.items()}},
         "roofline": roofline,
         "cpu_baseline": cpu,
