@@ -7,7 +7,8 @@
  * benchmark's cpu_baseline leg may load it.
  *
  * What is computed (paper: arxiv 2106.06150, KDD'21):
- *   - cache draw ............ Section 3.2, Eq. (1) (degree-proportional probability),
+ *   - cache draw ............ Section 3.2, Eq. (1) (degree-proportional probability) or
+ *                             the random-walk probability P^L = (DA + I)^L P^0,
  *                             Theorem 1 (drawn without replacement, |C| nodes)
  *   - layer sampling ........ Algorithm 1 top-down loop, Section 3.3 (neighbors
  *                             from the cache first, a shortfall filled uniformly from
@@ -157,6 +158,78 @@ int64_t gns_oracle_sample_cache(int64_t n, const int64_t* indptr, uint64_t seed,
 }
 
 /* ------------------------------------------------------------------------ */
+/* Section 3.2, second approach: the cache probability from short random walks,
+ *   P^0_i = 1/|V_S| on the training nodes, 0 elsewhere,
+ *   P^l   = (D_l A + I) P^(l-1),   D_l = diag(N_l(v)/deg(v)),   l = 1..L,
+ * and the cache is drawn with probability proportional to P^L.
+ * Readings: N_l(v), "the number of sampled neighbors of v in layer l", is
+ * min(k_l, deg(v)); step l of the walk uses the fan-out of the l-th layer counted
+ * from the seeds (fanouts[l-1], the same indexing as everywhere else here); the
+ * product is taken as printed, (D A P)_i = d_i * sum over j in N(i) of P_j.
+ * So that two implementations can agree bit for bit the vector is kept in integer
+ * units of 2^-scale_log2 of one training node's initial mass (the common factor
+ * 1/|V_S| does not change a proportional draw) and every step rounds down:
+ *   W^l_i = W^(l-1)_i + floor(min(k_l, deg_i) * S_i / deg_i),  S_i = sum_j W^(l-1)_j
+ * (computed as k'*(S div deg) + (k'*(S mod deg)) div deg, which is that floor exactly).
+ * weights[i] = W^L_i, prefix = its exclusive prefix sum (prefix[n] = total).
+ * Returns 0; -1 on bad arguments; -2 if a row sum, a product or the total would
+ * not fit in 62 bits (lower scale_log2).                                        */
+int gns_oracle_walk_weights(int64_t n, const int64_t* indptr, const int32_t* indices,
+                            int64_t num_train, const int32_t* train_nodes,
+                            int32_t num_layers, const int32_t* fanouts, int32_t scale_log2,
+                            uint64_t* weights, int64_t* prefix)
+{
+    if (n <= 0 || num_train <= 0 || num_layers < 1 || scale_log2 < 0 || scale_log2 > 40) return -1;
+    const uint64_t limit = (uint64_t)1 << 62;
+    uint64_t* cur = (uint64_t*)calloc((size_t)n, sizeof(uint64_t));
+    uint64_t* nxt = (uint64_t*)calloc((size_t)n, sizeof(uint64_t));
+    if (!cur || !nxt) { free(cur); free(nxt); return -1; }
+    int rc = 0;
+    for (int64_t t = 0; t < num_train; ++t) {
+        int64_t v = train_nodes[t];
+        if (v < 0 || v >= n) { rc = -1; goto done; }
+        cur[v] = (uint64_t)1 << scale_log2;
+    }
+    for (int32_t l = 0; l < num_layers && rc == 0; ++l) {
+        int64_t k = fanouts[l];
+        if (k < 1) { rc = -1; break; }
+        for (int64_t i = 0; i < n; ++i) {
+            int64_t deg = indptr[i + 1] - indptr[i];
+            uint64_t sum = 0;
+            for (int64_t e = indptr[i]; e < indptr[i + 1]; ++e) {
+                sum += cur[indices[e]];
+                if (sum >= limit) { rc = -2; break; }
+            }
+            if (rc) break;
+            uint64_t add = 0;
+            if (deg > 0) {
+                uint64_t kk = (uint64_t)(k < deg ? k : deg);
+                uint64_t q = sum / (uint64_t)deg, rem = sum % (uint64_t)deg;
+                if (q >= limit / 64) { rc = -2; break; }
+                add = kk * q + (kk * rem) / (uint64_t)deg;
+            }
+            nxt[i] = cur[i] + add;
+            if (nxt[i] >= limit) { rc = -2; break; }
+        }
+        uint64_t* tmp = cur; cur = nxt; nxt = tmp;
+    }
+    if (rc == 0) {
+        uint64_t total = 0;
+        for (int64_t i = 0; i < n; ++i) {
+            prefix[i] = (int64_t)total;
+            weights[i] = cur[i];
+            total += cur[i];
+            if (total >= limit) { rc = -2; break; }
+        }
+        prefix[n] = (int64_t)total;
+    }
+done:
+    free(cur);
+    free(nxt);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------ */
 /* Robert Floyd's subset algorithm: a uniformly random k-subset of {0..m-1}
  * from k random words.  For s = 0..k-1: j = m-k+s; t = floor(word_s*(j+1)/2^32);
  * take t unless already taken, else take j.  Requires 0 < k < m.  The ranks
@@ -241,15 +314,35 @@ static int32_t pick_ranks(int64_t m, int32_t k, uint64_t seed, int32_t layer, in
  * Section 2.1), |E_N|/r in the unbiased mode (inverse inclusion probability of a
  * uniform r-subset, given the cache).
  * Returns 0, or -1 on bad arguments.                                          */
+int gns_oracle_sample_layer_p(int64_t n, const int64_t* indptr, const int32_t* indices,
+                              const uint64_t* cache_bitmap, int64_t cache_size, const int64_t* prob_prefix,
+                              uint64_t seed, int32_t layer, int32_t policy, int32_t wmode, int32_t k,
+                              int64_t num_dst, const int32_t* dst_nodes,
+                              int32_t* out_nbr, float* out_w, int32_t* out_cnt, int32_t* out_elig);
+
 int gns_oracle_sample_layer(int64_t n, const int64_t* indptr, const int32_t* indices,
                             const uint64_t* cache_bitmap, int64_t cache_size,
                             uint64_t seed, int32_t layer, int32_t policy, int32_t wmode, int32_t k,
                             int64_t num_dst, const int32_t* dst_nodes,
                             int32_t* out_nbr, float* out_w, int32_t* out_cnt, int32_t* out_elig)
 {
+    /* Eq. (1): the cache probability of node u is deg(u) / nnz, i.e. the prefix is indptr itself */
+    return gns_oracle_sample_layer_p(n, indptr, indices, cache_bitmap, cache_size, indptr, seed, layer, policy,
+                                     wmode, k, num_dst, dst_nodes, out_nbr, out_w, out_cnt, out_elig);
+}
+
+/* The same with the cache probability given as an integer prefix array over the nodes:
+ * p_u = (prob_prefix[u+1] - prob_prefix[u]) / prob_prefix[n]  (Section 3.2: either Eq. (1)
+ * or the random-walk probability; Section 3.4 only needs p_u).                          */
+int gns_oracle_sample_layer_p(int64_t n, const int64_t* indptr, const int32_t* indices,
+                              const uint64_t* cache_bitmap, int64_t cache_size, const int64_t* prob_prefix,
+                              uint64_t seed, int32_t layer, int32_t policy, int32_t wmode, int32_t k,
+                              int64_t num_dst, const int32_t* dst_nodes,
+                              int32_t* out_nbr, float* out_w, int32_t* out_cnt, int32_t* out_elig)
+{
     if (k <= 0 || k > 64) return -1;
-    if (policy != GNS_ORACLE_UNIFORM && !cache_bitmap) return -1;
-    int64_t nnz = indptr[n];
+    if (policy != GNS_ORACLE_UNIFORM && (!cache_bitmap || !prob_prefix)) return -1;
+    int64_t nnz = prob_prefix ? prob_prefix[n] : indptr[n];
     for (int64_t r = 0; r < num_dst; ++r) {
         int64_t v = dst_nodes[r];
         if (v < 0 || v >= n) return -1;
@@ -273,8 +366,8 @@ int gns_oracle_sample_layer(int64_t n, const int64_t* indptr, const int32_t* ind
             if (policy == GNS_ORACLE_UNIFORM) {
                 out_w[r * k + s] = 1.0f;
             } else {
-                int64_t deg_u = indptr[(int64_t)u + 1] - indptr[u];
-                out_w[r * k + s] = gns_oracle_edge_weight(deg_u, nnz, cache_size, k, m, wmode);
+                int64_t mass_u = prob_prefix[(int64_t)u + 1] - prob_prefix[u];
+                out_w[r * k + s] = gns_oracle_edge_weight(mass_u, nnz, cache_size, k, m, wmode);
             }
         }
         if (policy == GNS_ORACLE_CACHE_FIRST && cnt < k && m_rest > 0) {

@@ -57,6 +57,11 @@ def _load():
     L.gns_oracle_sample_layer.argtypes = [i64, P(i64), P(i32), P(u64), i64, u64, i32, i32, i32, i32,
                                           i64, P(i32), P(i32), P(ctypes.c_float), P(i32), P(i32)]
     L.gns_oracle_sample_layer.restype = ctypes.c_int
+    L.gns_oracle_sample_layer_p.argtypes = [i64, P(i64), P(i32), P(u64), i64, P(i64), u64, i32, i32, i32, i32,
+                                            i64, P(i32), P(i32), P(ctypes.c_float), P(i32), P(i32)]
+    L.gns_oracle_sample_layer_p.restype = ctypes.c_int
+    L.gns_oracle_walk_weights.argtypes = [i64, P(i64), P(i32), i64, P(i32), i32, P(i32), i32, P(u64), P(i64)]
+    L.gns_oracle_walk_weights.restype = ctypes.c_int
     L.gns_oracle_build_block.argtypes = [i64, P(i32), i32, P(i32), P(ctypes.c_float), P(i32),
                                          P(i32), P(i32), P(ctypes.c_float), P(i32)]
     L.gns_oracle_build_block.restype = i64
@@ -121,19 +126,40 @@ def edge_weight(deg_u, nnz, cache_size, k, n_c, wmode=W_PRINTED):
     return float(_load().gns_oracle_edge_weight(deg_u, nnz, cache_size, k, n_c, wmode))
 
 
-def sample_layer(indptr, indices, cache_bitmap, cache_size, seed, layer, policy, wmode, k, dst_nodes):
-    """One layer; returns (nbr[R,k], w[R,k], cnt[R], eligible[R]); unused slots are -1 / 0."""
+def walk_weights(indptr, indices, train_nodes, fanouts, scale_log2=20):
+    """Section 3.2's random-walk cache probability in integer units; returns (weights u64[n],
+    prefix i64[n+1]).  The prefix plays the role of indptr in sample_cache / sample_layer."""
+    ip, ix, tr = _i64(indptr), _i32(indices), _i32(train_nodes)
+    fo = _i32(fanouts)
+    n = len(ip) - 1
+    w = np.zeros(n, dtype=np.uint64)
+    pre = np.zeros(n + 1, dtype=np.int64)
+    rc = _load().gns_oracle_walk_weights(n, _p(ip, ctypes.c_int64), _p(ix, ctypes.c_int32), len(tr),
+                                         _p(tr, ctypes.c_int32), len(fo), _p(fo, ctypes.c_int32), scale_log2,
+                                         _p(w, ctypes.c_uint64), _p(pre, ctypes.c_int64))
+    if rc == -2:
+        raise OverflowError("walk weights do not fit: lower scale_log2")
+    if rc != 0:
+        raise RuntimeError("oracle walk_weights failed (%d)" % rc)
+    return w, pre
+
+
+def sample_layer(indptr, indices, cache_bitmap, cache_size, seed, layer, policy, wmode, k, dst_nodes,
+                 prob_prefix=None):
+    """One layer; returns (nbr[R,k], w[R,k], cnt[R], eligible[R]); unused slots are -1 / 0.
+    prob_prefix: integer prefix array of the cache probability (default: indptr, Eq. (1))."""
     ip, ix, dst = _i64(indptr), _i32(indices), _i32(dst_nodes)
+    pp = ip if prob_prefix is None else _i64(prob_prefix)
     n, R = len(ip) - 1, len(dst)
     nbr = np.full((R, k), -1, dtype=np.int32)
     w = np.zeros((R, k), dtype=np.float32)
     cnt = np.zeros(R, dtype=np.int32)
     elig = np.zeros(R, dtype=np.int32)
     bm = None if cache_bitmap is None else np.ascontiguousarray(cache_bitmap, dtype=np.uint64)
-    rc = _load().gns_oracle_sample_layer(n, _p(ip, ctypes.c_int64), _p(ix, ctypes.c_int32),
-                                         _p(bm, ctypes.c_uint64), cache_size, seed, layer, policy, wmode, k,
-                                         R, _p(dst, ctypes.c_int32), _p(nbr, ctypes.c_int32),
-                                         _p(w, ctypes.c_float), _p(cnt, ctypes.c_int32), _p(elig, ctypes.c_int32))
+    rc = _load().gns_oracle_sample_layer_p(n, _p(ip, ctypes.c_int64), _p(ix, ctypes.c_int32),
+                                           _p(bm, ctypes.c_uint64), cache_size, _p(pp, ctypes.c_int64), seed, layer,
+                                           policy, wmode, k, R, _p(dst, ctypes.c_int32), _p(nbr, ctypes.c_int32),
+                                           _p(w, ctypes.c_float), _p(cnt, ctypes.c_int32), _p(elig, ctypes.c_int32))
     if rc != 0:
         raise RuntimeError("oracle sample_layer failed (%d)" % rc)
     return nbr, w, cnt, elig
@@ -180,7 +206,8 @@ def build_block(dst_nodes, k, nbr, w, cnt, elig):
     return OracleBlock(indptr, indices, weights, src[:ns].copy(), dst, np.asarray(elig, dtype=np.int32))
 
 
-def sample_blocks(indptr, indices, cache_bitmap, cache_size, seed, seeds, fanouts, policies, wmode=W_PRINTED):
+def sample_blocks(indptr, indices, cache_bitmap, cache_size, seed, seeds, fanouts, policies, wmode=W_PRINTED,
+                  prob_prefix=None):
     """Algorithm 1's top-down loop.  fanouts[0]/policies[0] belong to layer L
     (next to the seeds); the paper's layer number of list index i is L - i.
     Returns the list of blocks in the same order."""
@@ -190,7 +217,7 @@ def sample_blocks(indptr, indices, cache_bitmap, cache_size, seed, seeds, fanout
     for i in range(L):
         layer = L - i
         nbr, w, cnt, elig = sample_layer(indptr, indices, cache_bitmap, cache_size, seed, layer,
-                                         policies[i], wmode, fanouts[i], dst)
+                                         policies[i], wmode, fanouts[i], dst, prob_prefix=prob_prefix)
         blk = build_block(dst, fanouts[i], nbr, w, cnt, elig)
         blocks.append(blk)
         dst = blk.src_nodes
