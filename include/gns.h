@@ -98,6 +98,14 @@ typedef struct {
  *      costs num_entries/8 bytes of workspace and one pass over the graph per cache. */
 enum { GNS_FLAGS_PER_BATCH = 0, GNS_FLAGS_PER_CACHE = 1 };
 
+/* The probability the cache is drawn with (Section 3.2).
+ *  GNS_PROB_DEGREE: Eq. (1), p_i = deg(i) / sum of degrees.
+ *  GNS_PROB_WALK:   the random-walk probability P^L = (D_L A + I) ... (D_1 A + I) P^0 of the same
+ *      section, P^0 uniform on the training nodes, D_l = diag(min(k_l, deg)/deg) with k_l the
+ *      fan-out of the l-th layer counted from the seeds.  gns_cache_walk_probability must run
+ *      before gns_sample_cache; the workspace grows by about 24 bytes per node. */
+enum { GNS_PROB_DEGREE = 0, GNS_PROB_WALK = 1 };
+
 typedef struct {
     int32_t num_layers;               /* L, 1..GNS_MAX_LAYERS                                       */
     int32_t fanout[GNS_MAX_LAYERS];   /* k per layer; index 0 is layer L (next to the seeds), index
@@ -107,7 +115,7 @@ typedef struct {
     int32_t wmode;                    /* GNS_W_PRINTED / GNS_W_UNBIASED                             */
     int32_t max_seeds;                /* largest mini-batch |B| the context must accept             */
     int32_t flag_mode;                /* GNS_FLAGS_PER_BATCH / GNS_FLAGS_PER_CACHE                  */
-    int32_t reserved;                 /* must be 0                                                  */
+    int32_t cache_probability;        /* GNS_PROB_DEGREE (0) / GNS_PROB_WALK                          */
 } gns_config;
 
 /* One layer's block: a CSR over (dst rows) x (src columns) in local ids.
@@ -178,6 +186,23 @@ gns_status gns_sample_cache(gns_ctx* ctx, uint64_t seed, uint64_t epoch, void* h
  * be NULL.  GNS_ESTATE before the first draw. */
 gns_status gns_cache_view(gns_ctx* ctx, const int32_t** cache_nodes, int64_t* cache_size,
                           const uint64_t** bitmap, int64_t* num_draws);
+
+/* Section 3.2, second approach (config.cache_probability == GNS_PROB_WALK): computes the cache
+ * probability from L steps of the recursion above, starting from train_nodes_dev (num_train
+ * distinct node ids on the device).  The vector is kept in integers, 2^scale_log2 units per
+ * training node (0 <= scale_log2 <= 40), every step rounded down, so the result does not depend on
+ * the order of the additions; a draw then picks a uniform integer below the total and takes the
+ * node whose prefix interval holds it, and Section 3.4 uses p_u = weight_u / total.
+ * GNS_ECAPACITY if a row sum, a product or the total reaches 2^62 (lower scale_log2);
+ * GNS_EINVAL for a node id outside [0, n) or an all-zero result.  Synchronises the stream.
+ * Call it on the context made by gns_create; it invalidates the current cache. */
+gns_status gns_cache_walk_probability(gns_ctx* ctx, const int32_t* train_nodes_dev, int64_t num_train,
+                                      int32_t scale_log2, void* hip_stream);
+
+/* Read-only device views of what gns_cache_walk_probability left: weights uint64[n], their
+ * exclusive prefix sum int64[n + 1] (prefix[n] = *total), the number of non-zero weights. */
+gns_status gns_cache_probability_view(gns_ctx* ctx, const uint64_t** weights, const int64_t** prefix,
+                                      uint64_t* total, int64_t* support);
 
 /* Algorithm 1's top-down loop for one mini-batch.  seeds_dev: num_seeds
  * distinct node ids in [0, n) (1 <= num_seeds <= max_seeds).  `seed` keys the

@@ -16,6 +16,7 @@ GNS_OK, GNS_EINVAL, GNS_ECAPACITY, GNS_ESTATE, GNS_EHIP, GNS_ENOMEM, GNS_ENOTIMP
 GNS_UNIFORM, GNS_CACHE_ONLY, GNS_CACHE_FIRST = 0, 1, 2
 GNS_W_PRINTED, GNS_W_UNBIASED = 0, 1
 GNS_FLAGS_PER_BATCH, GNS_FLAGS_PER_CACHE = 0, 1
+GNS_PROB_DEGREE, GNS_PROB_WALK = 0, 1
 GNS_MAX_LAYERS = 8
 GNS_MAX_FANOUT = 64
 
@@ -33,7 +34,7 @@ class gns_config(ctypes.Structure):
     _fields_ = [("num_layers", ctypes.c_int32), ("fanout", ctypes.c_int32 * GNS_MAX_LAYERS),
                 ("policy", ctypes.c_int32 * GNS_MAX_LAYERS), ("cache_size", ctypes.c_int64),
                 ("wmode", ctypes.c_int32), ("max_seeds", ctypes.c_int32),
-                ("flag_mode", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("flag_mode", ctypes.c_int32), ("cache_probability", ctypes.c_int32)]
 
 
 class gns_block(ctypes.Structure):
@@ -64,6 +65,10 @@ def _load():
     lib.gns_destroy.restype = ctypes.c_int
     lib.gns_sample_cache.argtypes = [vp, u64, u64, vp]
     lib.gns_sample_cache.restype = ctypes.c_int
+    lib.gns_cache_walk_probability.argtypes = [vp, vp, i64, i32, vp]
+    lib.gns_cache_walk_probability.restype = ctypes.c_int
+    lib.gns_cache_probability_view.argtypes = [vp, P(vp), P(vp), P(u64), P(i64)]
+    lib.gns_cache_probability_view.restype = ctypes.c_int
     lib.gns_cache_view.argtypes = [vp, P(vp), P(i64), P(vp), P(i64)]
     lib.gns_cache_view.restype = ctypes.c_int
     lib.gns_sample_blocks.argtypes = [vp, u64, vp, i32, P(gns_block), vp]
@@ -90,7 +95,7 @@ lib = _load()
 EXPORTED = ["gns_workspace_bytes", "gns_block_capacity", "gns_create", "gns_destroy", "gns_sample_cache",
             "gns_cache_view", "gns_sample_blocks", "gns_gather_features", "gns_aggregate", "gns_last_error",
             "gns_profile_begin", "gns_profile_collect", "gns_sample_blocks_async", "gns_sample_blocks_wait",
-            "gns_fork", "gns_fork_workspace_bytes"]
+            "gns_fork", "gns_fork_workspace_bytes", "gns_cache_walk_probability", "gns_cache_probability_view"]
 
 GNS_STAGE_SAMPLE, GNS_STAGE_FINISH, GNS_STAGE_GATHER, GNS_STAGE_AGGREGATE = 0, 8, 16, 17
 GNS_STAGE_PLAN, GNS_STAGE_FLAG, GNS_STAGE_SELECT = 18, 19, 20
@@ -136,7 +141,8 @@ def make_graph(indptr, indices, feat_dev=None, feat_host_pinned=None, feat_dim=N
     return g
 
 
-def make_config(fanouts, policies, cache_size, max_seeds, wmode=GNS_W_PRINTED, flag_mode=GNS_FLAGS_PER_BATCH):
+def make_config(fanouts, policies, cache_size, max_seeds, wmode=GNS_W_PRINTED, flag_mode=GNS_FLAGS_PER_BATCH,
+                cache_probability=0):
     c = gns_config()
     c.num_layers = len(fanouts)
     for i, (k, p) in enumerate(zip(fanouts, policies)):
@@ -146,6 +152,7 @@ def make_config(fanouts, policies, cache_size, max_seeds, wmode=GNS_W_PRINTED, f
     c.wmode = wmode
     c.max_seeds = max_seeds
     c.flag_mode = flag_mode
+    c.cache_probability = cache_probability
     return c
 
 
@@ -187,6 +194,21 @@ def gns_destroy(ctx):
 
 def gns_sample_cache(ctx, seed, epoch, stream=None):
     _check(lib.gns_sample_cache(ctx, seed, epoch, _stream_ptr(stream)), ctx)
+
+
+def gns_cache_walk_probability(ctx, train_nodes_dev, scale_log2, stream=None):
+    assert train_nodes_dev.is_cuda and train_nodes_dev.dtype == torch.int32 and train_nodes_dev.is_contiguous()
+    _check(lib.gns_cache_walk_probability(ctx, train_nodes_dev.data_ptr(), train_nodes_dev.numel(), scale_log2,
+                                          _stream_ptr(stream)), ctx)
+
+
+def gns_cache_probability_view(ctx):
+    """Returns (weights_ptr, prefix_ptr, total, support) -- raw device pointers and host scalars."""
+    w, pre = ctypes.c_void_p(), ctypes.c_void_p()
+    total, support = ctypes.c_uint64(), ctypes.c_int64()
+    _check(lib.gns_cache_probability_view(ctx, ctypes.byref(w), ctypes.byref(pre), ctypes.byref(total),
+                                          ctypes.byref(support)), ctx)
+    return w.value, pre.value, total.value, support.value
 
 
 def gns_cache_view(ctx):

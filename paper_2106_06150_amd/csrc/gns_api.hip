@@ -41,7 +41,8 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     if (cfg->max_seeds < 1) GNS_BAD("max_seeds must be >= 1");
     if (cfg->wmode != GNS_W_PRINTED && cfg->wmode != GNS_W_UNBIASED) GNS_BAD("unknown weight mode");
     if (cfg->flag_mode != GNS_FLAGS_PER_BATCH && cfg->flag_mode != GNS_FLAGS_PER_CACHE) GNS_BAD("unknown flag mode");
-    if (cfg->reserved != 0) GNS_BAD("reserved config field must be 0");
+    if (cfg->cache_probability != GNS_PROB_DEGREE && cfg->cache_probability != GNS_PROB_WALK)
+        GNS_BAD("unknown cache_probability");
     for (int i = 0; i < cfg->num_layers; ++i) {
         if (cfg->fanout[i] < 1 || cfg->fanout[i] > GNS_MAX_FANOUT) GNS_BAD("fanout out of range");
         if (cfg->policy[i] != GNS_UNIFORM && cfg->policy[i] != GNS_CACHE_ONLY && cfg->policy[i] != GNS_CACHE_FIRST)
@@ -124,6 +125,14 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
         L.draw_slot = take((size_t) L.draw_chunk * 4);
         L.edge_flags = take((size_t) (g->num_entries / 64 + 1) * 8);
         L.node_pc = take((size_t) n * 4);
+        if (cfg->cache_probability == GNS_PROB_WALK) {
+            L.walk_a = take((size_t) n * 8);
+            L.walk_b = take((size_t) n * 8);
+            L.prob_prefix = take((size_t) (n + 1) * 8);
+            const size_t tiles = (size_t) ((n + kTile - 1) / kTile);
+            L.walk_tiles = take((tiles + 1) * 8);
+            L.walk_tiles_nz = take((tiles + 1) * 4);
+        }
     }
     L.total = off;
     *out = L;
@@ -131,7 +140,7 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
 #undef GNS_BAD
 }
 
-static gns_status ctx_fail(gns_ctx* c, gns_status st, const char* what, hipError_t e = hipSuccess)
+gns_status ctx_fail(gns_ctx* c, gns_status st, const char* what, hipError_t e)
 {
     if (e != hipSuccess) snprintf(c->err, sizeof(c->err), "%s: %s", what, hipGetErrorString(e));
     else snprintf(c->err, sizeof(c->err), "%s", what);
@@ -483,7 +492,38 @@ gns_status gns_sample_cache(gns_ctx* ctx, uint64_t seed, uint64_t epoch, void* h
     if (!ctx->uses_cache) return ctx_fail(ctx, GNS_ESTATE, "no layer of this config uses the cache");
     if (ctx->root != ctx) return ctx_fail(ctx, GNS_EINVAL, "draw the cache on the context made by gns_create, not on a fork");
     if (epoch >> 32) return ctx_fail(ctx, GNS_EINVAL, "epoch must be < 2^32");
+    if (ctx->config.cache_probability == GNS_PROB_WALK) {
+        if (!ctx->prob_valid) return ctx_fail(ctx, GNS_ESTATE, "gns_cache_walk_probability must run before gns_sample_cache");
+        if (ctx->config.cache_size > ctx->prob_support)
+            return ctx_fail(ctx, GNS_EINVAL, "cache_size exceeds the number of nodes the walk probability reaches");
+    }
     return run_sample_cache(ctx, seed, epoch, static_cast<hipStream_t>(hip_stream));
+}
+
+gns_status gns_cache_walk_probability(gns_ctx* ctx, const int32_t* train_nodes_dev, int64_t num_train,
+                                      int32_t scale_log2, void* hip_stream)
+{
+    if (!ctx) return GNS_EINVAL;
+    if (ctx->root != ctx) return ctx_fail(ctx, GNS_EINVAL, "set the cache probability on the context made by gns_create, not on a fork");
+    if (!ctx->uses_cache || ctx->config.cache_probability != GNS_PROB_WALK)
+        return ctx_fail(ctx, GNS_ESTATE, "the config does not ask for GNS_PROB_WALK");
+    if (!train_nodes_dev || num_train < 1) return ctx_fail(ctx, GNS_EINVAL, "no training nodes");
+    if (scale_log2 < 0 || scale_log2 > 40) return ctx_fail(ctx, GNS_EINVAL, "scale_log2 must be in [0, 40]");
+    ctx->cache_valid = false;
+    return run_walk_probability(ctx, train_nodes_dev, num_train, scale_log2, static_cast<hipStream_t>(hip_stream));
+}
+
+gns_status gns_cache_probability_view(gns_ctx* ctx, const uint64_t** weights, const int64_t** prefix,
+                                      uint64_t* total, int64_t* support)
+{
+    if (!ctx) return GNS_EINVAL;
+    gns_ctx* root = ctx->root;
+    if (!root->prob_valid) return ctx_fail(ctx, GNS_ESTATE, "no cache probability has been computed");
+    if (weights) *weights = reinterpret_cast<const uint64_t*>(root->prob_weights);
+    if (prefix) *prefix = ws_ptr<int64_t>(root, root->lay.prob_prefix);
+    if (total) *total = root->prob_total;
+    if (support) *support = root->prob_support;
+    return GNS_OK;
 }
 
 gns_status gns_cache_view(gns_ctx* ctx, const int32_t** cache_nodes, int64_t* cache_size, const uint64_t** bitmap,

@@ -281,11 +281,16 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
     GNS_HIP_TRY(launch_fill_u32(ws_ptr<uint32_t>(c, L.draw_keys), L.draw_hash_cap, 0xFFFFFFFFu, s), "clear draw keys");
     GNS_HIP_TRY(launch_fill_u32(ws_ptr<uint32_t>(c, L.draw_vals), L.draw_hash_cap, 0xFFFFFFFFu, s), "clear draw vals");
 
+    // The draw picks a uniform integer below the total mass and takes the node whose prefix interval
+    // holds it: the CSR offsets for Eq. (1), the prefix of the walk weights for the other probability.
+    const bool walk = c->config.cache_probability == GNS_PROB_WALK;
+    const void* prob_prefix = walk ? static_cast<const void*>(ws_ptr<int64_t>(c, L.prob_prefix)) : c->graph.indptr;
+    const uint64_t prob_total = walk ? (uint64_t) c->prob_total : (uint64_t) c->graph.num_entries;
     DrawArgs a;
     a.st = c->d_state;
-    a.indptr = c->graph.indptr;
+    a.indptr = prob_prefix;
     a.n = c->graph.num_nodes;
-    a.nnz = (uint64_t) c->graph.num_entries;
+    a.nnz = prob_total;
     a.key0 = (uint32_t) seed;
     a.key1 = (uint32_t) (seed >> 32);
     a.epoch = (uint32_t) epoch;
@@ -305,7 +310,7 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
     if (draw_limit > 0xFFFFFFFFull) draw_limit = 0xFFFFFFFFull;
     uint64_t j0 = 0;
     int64_t distinct = 0;
-    const bool i64 = c->graph.indptr_is_i64 != 0;
+    const bool i64 = walk || c->graph.indptr_is_i64 != 0;
     while (distinct < C) {
         const int64_t count = L.draw_chunk;
         if (j0 + (uint64_t) count > draw_limit)
@@ -348,8 +353,8 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
     {
         const unsigned pc_blocks = (unsigned) ((C + kBlock - 1) / kBlock);
         float* node_pc = ws_ptr<float>(c, L.node_pc);
-        if (i64) hipLaunchKernelGGL((k_cache_pc<int64_t>), dim3(pc_blocks), dim3(kBlock), 0, s, x.cache_nodes, C, c->graph.indptr, c->graph.num_entries, node_pc);
-        else     hipLaunchKernelGGL((k_cache_pc<int32_t>), dim3(pc_blocks), dim3(kBlock), 0, s, x.cache_nodes, C, c->graph.indptr, c->graph.num_entries, node_pc);
+        if (i64) hipLaunchKernelGGL((k_cache_pc<int64_t>), dim3(pc_blocks), dim3(kBlock), 0, s, x.cache_nodes, C, prob_prefix, (int64_t) prob_total, node_pc);
+        else     hipLaunchKernelGGL((k_cache_pc<int32_t>), dim3(pc_blocks), dim3(kBlock), 0, s, x.cache_nodes, C, prob_prefix, (int64_t) prob_total, node_pc);
         GNS_HIP_TRY(hipGetLastError(), "cache weight table launch");
     }
     if (c->config.flag_mode == GNS_FLAGS_PER_CACHE)

@@ -20,11 +20,16 @@ struct DeviceState {
     int32_t chunk_distinct;               // cache draw: first occurrences found in the current chunk
     int32_t plan_chunks;                  // CACHE_ONLY sampler: aligned chunks in the current work list
     unsigned long long cut_draw;          // cache draw: stream index of the draw that completed the cache
+    unsigned long long walk_total;        // random-walk probability: sum of the weights
+    int32_t walk_support;                 //   number of nodes with a non-zero weight
+    int32_t walk_error;                   //   1: bad training node, 2: does not fit in 62 bits
 };
 
 struct Layout {
     // persistent cache structures
     size_t cache_bitmap, cache_prefix, cache_nodes, cache_feat;
+    // random-walk cache probability (only with GNS_PROB_WALK): two weight vectors, their prefix, scan partials
+    size_t walk_a, walk_b, prob_prefix, walk_tiles, walk_tiles_nz;
     size_t node_pc;           // [n] floats: 1 / p^C_u (Section 3.4), filled for the nodes of the current cache
     // cache-draw scratch
     size_t draw_keys, draw_vals, draw_node, draw_slot;
@@ -93,6 +98,11 @@ struct gns_ctx {
     bool uses_cache;
     bool cache_valid;
     int64_t cache_draws;
+    // cache probability other than Eq. (1): set by gns_cache_walk_probability on the root context
+    bool prob_valid;
+    const unsigned long long* prob_weights;   // device, [n]
+    unsigned long long prob_total;
+    int64_t prob_support;            // nodes with non-zero weight
     int64_t nonzero_degree_nodes;
     int num_cus;
     size_t lds_bitmap_limit;         // largest cache bitmap (bytes) the flag kernel stages in LDS
@@ -123,6 +133,7 @@ static inline T* ws_ptr(const gns_ctx* c, size_t off)
     return reinterpret_cast<T*>((off >= c->lay.shared_begin ? c->shared_ws : c->ws) + off);
 }
 
+gns_status ctx_fail(gns_ctx* c, gns_status st, const char* what, hipError_t e = hipSuccess);
 bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char* err, size_t errlen);
 
 // Brackets a stage's launches with events when that stage is being timed.
@@ -142,6 +153,10 @@ struct StageTimer {
         if (slot >= 0) (void) hipEventRecord(c->prof[slot].stop, s);
     }
 };
+
+// gns_walk.hip
+gns_status run_walk_probability(gns_ctx* c, const int32_t* train_nodes, int64_t num_train, int32_t scale_log2,
+                                hipStream_t s);
 
 // gns_cache.hip
 hipError_t launch_count_nonzero_rows(gns_ctx* c, hipStream_t s, int32_t* d_out);

@@ -12,7 +12,7 @@ AGG_RTOL = 1e-5        # aggregates: error relative to (1/n_v) * sum |w_e x_e| p
 
 class GpuGns:
     def __init__(self, indptr, indices, feat=None, *, fanouts, policies, cache_size, max_seeds,
-                 wmode=B.GNS_W_PRINTED, feat_on_host=False, device="cuda:0", flag_mode=0):
+                 wmode=B.GNS_W_PRINTED, feat_on_host=False, device="cuda:0", flag_mode=0, cache_probability=0):
         self.device = torch.device(device)
         self.indptr_cpu = indptr
         self.indices_cpu = indices
@@ -27,7 +27,8 @@ class GpuGns:
             else:
                 self.feat_dev = feat.to(self.device)
         self.graph = B.make_graph(self.indptr, self.indices, self.feat_dev, self.feat_host)
-        self.config = B.make_config(fanouts, policies, cache_size, max_seeds, wmode, flag_mode)
+        self.config = B.make_config(fanouts, policies, cache_size, max_seeds, wmode, flag_mode, cache_probability)
+        self.prob_prefix = None          # oracle-side prefix of the cache probability (None: the CSR offsets)
         self.fanouts, self.policies, self.cache_size, self.wmode = list(fanouts), list(policies), cache_size, wmode
         self.workspace = B.alloc_workspace(self.graph, self.config, self.device)
         self.ctx = B.gns_create(self.graph, self.config, self.workspace)
@@ -39,6 +40,15 @@ class GpuGns:
             self.ctx = None
 
     # -- cache ---------------------------------------------------------------
+    def walk_probability(self, train_nodes, scale_log2):
+        """Random-walk cache probability on the GPU; returns (weights u64[n], prefix i64[n+1], total, support)."""
+        B.gns_cache_walk_probability(self.ctx, train_nodes.to(self.device).contiguous(), scale_log2)
+        w_ptr, pre_ptr, total, support = B.gns_cache_probability_view(self.ctx)
+        n = self.indptr.numel() - 1
+        w = B.device_view_u64(w_ptr, n, self.device).cpu().numpy().view(np.uint64)
+        pre = B.device_view_u64(pre_ptr, n + 1, self.device).cpu().numpy().view(np.int64)
+        return w, pre, total, support
+
     def sample_cache(self, seed, epoch):
         B.gns_sample_cache(self.ctx, seed, epoch)
         nodes_ptr, size, bitmap_ptr, draws = B.gns_cache_view(self.ctx)
@@ -115,11 +125,11 @@ def full_parity(gns, *, cache_seed, epoch, batch_seed, seeds, check_gather=True,
     ix = gns.indices_cpu.numpy()
     bitmap = None
     if any(p != B.GNS_UNIFORM for p in gns.policies):
-        ref_cache = oracle.sample_cache(ip, cache_seed, epoch, gns.cache_size)
+        ref_cache = oracle.sample_cache(ip if gns.prob_prefix is None else gns.prob_prefix, cache_seed, epoch, gns.cache_size)
         compare_cache(gns.sample_cache(cache_seed, epoch), ref_cache)
         bitmap = ref_cache[1]
     ref_blocks = oracle.sample_blocks(ip, ix, bitmap, gns.cache_size, batch_seed, seeds.numpy(), gns.fanouts,
-                                      gns.policies, gns.wmode)
+                                      gns.policies, gns.wmode, prob_prefix=gns.prob_prefix)
     views = gns.sample_blocks(batch_seed, seeds)
     compare_blocks(views, ref_blocks)
     if gns.feat_cpu is None:

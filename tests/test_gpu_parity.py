@@ -233,6 +233,41 @@ def test_create_rejects_bad_graphs_and_configs():
     assert err.value.status == B.GNS_ECAPACITY
 
 
+@pytest.mark.parametrize("offsets", [torch.int32, torch.int64])
+def test_walk_probability_cache_and_weights(offsets):
+    """Section 3.2's random-walk cache probability: the integer weight vector, its prefix, the cache
+    drawn from it and the Section 3.4 weights that use it, all against the oracle."""
+    ip, ix = _small(n=5000, avg=12, seed=21)
+    n = ip.numel() - 1
+    train = torch.from_numpy(np.random.default_rng(4).permutation(n)[:150].astype(np.int32))
+    fanouts, policies = (6, 4, 3), (CF, CF, C)
+    gns = GpuGns(ip.to(offsets), ix, _feat(n, 16), fanouts=fanouts, policies=policies, cache_size=120, max_seeds=64,
+                 cache_probability=B.GNS_PROB_WALK)
+    try:
+        with pytest.raises(B.GnsError) as err:                     # the probability has to be computed first
+            B.gns_sample_cache(gns.ctx, 1, 0)
+        assert err.value.status == B.GNS_ESTATE
+        for scale in (12, 30):
+            w, pre, total, support = gns.walk_probability(train, scale)
+            w_ref, pre_ref = oracle.walk_weights(ip.numpy(), ix.numpy(), train.numpy(), list(fanouts), scale_log2=scale)
+            assert np.array_equal(w, w_ref) and np.array_equal(pre, pre_ref)
+            assert total == int(pre_ref[-1]) and support == int(np.count_nonzero(w_ref))
+            gns.prob_prefix = pre_ref
+            for trial in range(2):
+                seeds = train[trial * 64:(trial + 1) * 64]
+                full_parity(gns, cache_seed=31, epoch=trial, batch_seed=700 + trial, seeds=seeds)
+        with pytest.raises(B.GnsError) as err:                     # 40 bits per node times fan-outs up to 6: too much
+            big = GpuGns(ip, ix, None, fanouts=(60, 60, 60, 60, 60, 60, 60, 60), policies=(U,) * 7 + (C,), cache_size=50,
+                         max_seeds=8, cache_probability=B.GNS_PROB_WALK)
+            try:
+                B.gns_cache_walk_probability(big.ctx, torch.arange(0, 200, dtype=torch.int32).cuda(), 40)
+            finally:
+                big.close()
+        assert err.value.status == B.GNS_ECAPACITY
+    finally:
+        gns.close()
+
+
 def test_cache_nearly_all_nodes():
     # the cache takes every node that has a neighbor: the stream must run until the rarest node shows up
     ip, ix = _small(n=300, avg=6)
