@@ -60,6 +60,10 @@ def main():
     ap.add_argument("--upper-policy", choices=["uniform", "cache_first"], default="uniform",
                     help="policy of the layers above the input layer: uniform node-wise sampling (the workload the "
                          "metric is quoted on) or the paper's cache-first-then-fill (its Section 4.1 setting)")
+    ap.add_argument("--cache-probability", choices=["degree", "walk"], default="degree",
+                    help="degree: Eq. (1), the workload the metric is quoted on; walk: Section 3.2's random-walk "
+                         "probability from the workload's training split (computed once, outside the timed region, "
+                         "and reported on its own)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference point for rocprofv3 byte counters)")
     ap.add_argument("--skip-pass-a", action="store_true", help="profiling aid: only the single-stream pass")
@@ -99,9 +103,29 @@ def main():
 
     graph = B.make_graph(g.indptr, g.indices, feat_dev=None if on_host else feat,
                          feat_host_pinned=feat if on_host else None)
-    config = B.make_config(fanouts, policies, cache_size, batch, flag_mode=args.flag_mode)
+    walk = args.cache_probability == "walk"
+    config = B.make_config(fanouts, policies, cache_size, batch, flag_mode=args.flag_mode,
+                           cache_probability=B.GNS_PROB_WALK if walk else B.GNS_PROB_DEGREE)
     ws = B.alloc_workspace(graph, config, dev)
     ctx = B.gns_create(graph, config, ws)
+    walk_info = None
+    if walk:
+        # the training split of the workload (a seeded 10 % of the nodes where the workload names none)
+        split = synth.training_split(n, c.get("split", max(batch, n // 10)), sd["split"]).to(dev)
+        scale = 24
+        B.gns_cache_walk_probability(ctx, split, scale)                 # warm-up (also validates)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        B.gns_cache_walk_probability(ctx, split, scale)                 # synchronises before it returns
+        dt = time.perf_counter() - t0
+        _, _, total_mass, support = B.gns_cache_probability_view(ctx)
+        # per step: every CSR entry (4 B) and the 8-B weight it points to, per node two offsets, one weight read
+        # and one written; then the prefix scan reads the weights twice and writes the prefix
+        step_bytes = g.nnz * (4 + 8) + n * (2 * off_bytes + 16)
+        walk_bytes = L * step_bytes + n * 24
+        walk_info = {"ms": round(1e3 * dt, 3), "steps": L, "training_nodes": int(split.numel()),
+                     "nodes_reached": int(support), "scale_log2": scale,
+                     "algorithmic_GBps": round(walk_bytes / dt / 1e9, 1)}
     S = max(1, args.slots)
     ctxs, fork_ws = [ctx], []
     for _ in range(S - 1):
@@ -285,10 +309,11 @@ def main():
                                   cache_size, refresh, fanouts, batch),
                    "max_degree": g.max_degree, "batches_in_flight": S,
                    "cache_flags": "per mini-batch (CSR-segment scan)" if args.flag_mode == 0 else "per cache draw",
-                   "upper_layers": args.upper_policy,
+                   "upper_layers": args.upper_policy, "cache_probability": args.cache_probability,
                    "avg_per_batch": {k: round(v, 1) for k, v in avg.items()}},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "walk_probability": walk_info,
         "single_stream": {"value": round(K / elapsed_b, 2), "ms_per_step": round(1e3 * elapsed_b / K, 4),
                           "stage_us": stage_us},
     }
