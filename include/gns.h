@@ -124,7 +124,7 @@ typedef struct {
  *   indptr[0..num_dst]          = exclusive prefix sum of the per-row counts
  *   indices[e], weights[e]      = local src id and Section 3.4 weight of edge e;
  *                                 a row's edges are in ascending CSR position
- *   row_eligible[r]             = deg(v) (UNIFORM) or N_C(v) (CACHE_ONLY) of dst row r
+ *   row_eligible[r]             = deg(v) (UNIFORM) or N_C(v) (CACHE_ONLY, CACHE_FIRST) of dst row r
  * The five arrays are caller-allocated device buffers with the capacities
  * below (see gns_block_capacity); the three counts are written by the library
  * on the host.  src_nodes of layer l is the dst list of layer l-1.            */
