@@ -20,6 +20,7 @@
  *   - frontier union ........ Algorithm 1, B^{l-1} <- B^{l-1} U N_l(u)
  *   - gather ................ Section 2.2 steps 2-3 (slice the input-node features)
  *   - aggregation ........... Algorithm 1 bottom-up loop, mean aggregator (Section 2.1)
+ *   - update ................ Algorithm 1, h_u = g(W . (h_u, h_N(u))) (forward only)
  *
  * Conventions of this build that the paper leaves open (random source, order
  * inside a frontier, how a without-replacement draw is realised) are stated at
@@ -487,4 +488,26 @@ void gns_oracle_aggregate(int64_t num_dst, const int32_t* indptr, const int32_t*
         for (int64_t f = 0; f < feat_dim; ++f) out[r * feat_dim + f] = (float)(acc[f] * inv);
     }
     free(acc);
+}
+
+/* ------------------------------------------------------------------------ */
+/* The update step of Algorithm 1 for one layer (GraphSAGE form, Section 2.1):
+ *   h_u^l = g( W^l . (h_u^(l-1), h_N(u)^l) )
+ * with the concatenation written out: out[r, :] = g( h_self[r, :] . W[0:F1, :] +
+ * h_neigh[r, :] . W[F1:F1+F2, :] + bias ),  g = max(0, .) if relu else identity.
+ * W is (F1+F2) x H row-major (the paper's W^l transposed, so that rows of W match
+ * the entries of the concatenated vector), bias may be NULL.  fp64 accumulation in
+ * index order, one rounding to fp32.                                           */
+void gns_oracle_sage_dense(int64_t rows, int64_t f1, const float* h_self, int64_t f2, const float* h_neigh,
+                           int64_t hdim, const float* w, const float* bias, int32_t relu, float* out)
+{
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t j = 0; j < hdim; ++j) {
+            double acc = bias ? (double)bias[j] : 0.0;
+            for (int64_t k = 0; k < f1; ++k) acc += (double)h_self[r * f1 + k] * (double)w[k * hdim + j];
+            for (int64_t k = 0; k < f2; ++k) acc += (double)h_neigh[r * f2 + k] * (double)w[(f1 + k) * hdim + j];
+            if (relu && acc < 0.0) acc = 0.0;
+            out[r * hdim + j] = (float)acc;
+        }
+    }
 }

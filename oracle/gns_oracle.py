@@ -70,6 +70,9 @@ def _load():
     L.gns_oracle_aggregate.argtypes = [i64, P(i32), P(i32), P(ctypes.c_float), i64,
                                        P(ctypes.c_float), P(ctypes.c_float)]
     L.gns_oracle_aggregate.restype = None
+    L.gns_oracle_sage_dense.argtypes = [i64, i64, P(ctypes.c_float), i64, P(ctypes.c_float), i64, P(ctypes.c_float),
+                                        P(ctypes.c_float), i32, P(ctypes.c_float)]
+    L.gns_oracle_sage_dense.restype = None
     _lib = L
     return L
 
@@ -241,4 +244,21 @@ def aggregate(indptr, indices, weights, x_src):
     out = np.zeros((R, F), dtype=np.float32)
     _load().gns_oracle_aggregate(R, _p(ip, ctypes.c_int32), _p(ix, ctypes.c_int32), _p(w, ctypes.c_float), F,
                                  _p(xs, ctypes.c_float), _p(out, ctypes.c_float))
+    return out
+
+
+def sage_dense(h_self, h_neigh, w, bias=None, relu=True):
+    """out = g(h_self @ W[:F1] + h_neigh @ W[F1:] + bias), fp64 accumulation, fp32 result."""
+    hs = np.ascontiguousarray(h_self, dtype=np.float32)
+    hn = np.ascontiguousarray(h_neigh, dtype=np.float32)
+    ww = np.ascontiguousarray(w, dtype=np.float32)
+    rows, f1 = hs.shape
+    f2 = hn.shape[1]
+    assert hn.shape[0] == rows and ww.shape[0] == f1 + f2
+    hdim = ww.shape[1]
+    bb = None if bias is None else np.ascontiguousarray(bias, dtype=np.float32)
+    out = np.zeros((rows, hdim), dtype=np.float32)
+    _load().gns_oracle_sage_dense(rows, f1, _p(hs, ctypes.c_float), f2, _p(hn, ctypes.c_float), hdim,
+                                  _p(ww, ctypes.c_float), _p(bb, ctypes.c_float), 1 if relu else 0,
+                                  _p(out, ctypes.c_float))
     return out

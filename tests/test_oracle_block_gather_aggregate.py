@@ -127,3 +127,34 @@ def test_mean_of_printed_weights_closed_form(small_graph):
             acc += x[b.indices[e]].astype(np.float64) / pc
         assert np.allclose(out[r], acc / k, rtol=2e-6, atol=1e-6)
         assert abs(ones[r, 0] - b.weights[lo:hi].astype(np.float64).mean()) < 1e-6 * ones[r, 0]
+
+
+# ---------------------------------------------------------------------------
+# the update step h_u = g(W . (h_u, h_N(u)))  (Algorithm 1; GraphSAGE form of Section 2.1)
+
+def test_sage_dense_matches_the_concatenated_matrix_product():
+    rng = np.random.default_rng(3)
+    rows, f1, f2, hdim = 37, 12, 20, 9
+    hs = rng.standard_normal((rows, f1)).astype(np.float32)
+    hn = rng.standard_normal((rows, f2)).astype(np.float32)
+    w = rng.standard_normal((f1 + f2, hdim)).astype(np.float32)
+    b = rng.standard_normal(hdim).astype(np.float32)
+    pre = np.concatenate([hs, hn], axis=1).astype(np.float64) @ w.astype(np.float64) + b.astype(np.float64)
+    got = oracle.sage_dense(hs, hn, w, b, relu=False)
+    assert np.allclose(got, pre, rtol=0, atol=1e-6 * np.abs(pre).max())
+    got_relu = oracle.sage_dense(hs, hn, w, b, relu=True)
+    assert np.array_equal(got_relu, np.maximum(got, 0.0)) and (got < 0).any()
+    # without bias; the self part multiplies the first F1 rows of W, the neighbor part the rest
+    only_self = oracle.sage_dense(hs, np.zeros_like(hn), w, None, relu=False)
+    assert np.allclose(only_self, hs.astype(np.float64) @ w[:f1].astype(np.float64), atol=1e-5)
+    only_neigh = oracle.sage_dense(np.zeros_like(hs), hn, w, None, relu=False)
+    assert np.allclose(only_neigh, hn.astype(np.float64) @ w[f1:].astype(np.float64), atol=1e-5)
+
+
+def test_sage_dense_hand_computed():
+    hs = np.array([[1.0, 2.0]], dtype=np.float32)
+    hn = np.array([[3.0]], dtype=np.float32)
+    w = np.array([[1.0, -1.0], [0.5, 0.0], [2.0, -4.0]], dtype=np.float32)     # rows: self0, self1, neigh0
+    b = np.array([0.25, 1.0], dtype=np.float32)
+    assert oracle.sage_dense(hs, hn, w, b, relu=False).tolist() == [[8.25, -12.0]]
+    assert oracle.sage_dense(hs, hn, w, b, relu=True).tolist() == [[8.25, 0.0]]
