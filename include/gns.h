@@ -253,6 +253,20 @@ gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t n
 gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_src_dev, int32_t feat_dim,
                          float* out_dev, void* hip_stream);
 
+/* The update step of Algorithm 1 for one layer in its GraphSAGE form (Section 2.1), forward only:
+ *   out_dev[r, :] = g( h_self_dev[r, :] . W[0:f1, :] + h_neigh_dev[r, :] . W[f1:f1+f2, :] + bias ),
+ * g = max(0, .) if relu != 0, identity otherwise.  h_self_dev is fp32[num_rows x f1] (the dst
+ * nodes' own rows: the first num_dst rows of what gns_gather_features wrote), h_neigh_dev
+ * fp32[num_rows x f2] (what gns_aggregate wrote), w_dev fp32[(f1 + f2) x hdim] row-major, bias_dev
+ * fp32[hdim] or NULL, out_dev fp32[num_rows x hdim]; all row-major device buffers, 16-byte aligned,
+ * f1, f2 and hdim multiples of 4 (GNS_EINVAL otherwise).  fp32 matrix-core arithmetic with fp32
+ * accumulation; the order of the additions is the kernel's own.  num_rows may be
+ * GNS_DEVICE_COUNTS(i): the dst rows of layer index i of the last gns_sample_blocks(_async), read on
+ * the device (buffers must then hold that layer's cap_dst rows).  Enqueue only. */
+gns_status gns_sage_dense(gns_ctx* ctx, const float* h_self_dev, int32_t f1, const float* h_neigh_dev, int32_t f2,
+                          const float* w_dev, const float* bias_dev, int32_t hdim, int32_t relu, float* out_dev,
+                          int32_t num_rows, void* hip_stream);
+
 /* Stage timing for benchmarks (no part of the method).  Stages: GNS_STAGE_SAMPLE + i
  * = the sampler launches of layer index i (the first of them also carries the relabel
  * of layer index i - 1); GNS_STAGE_FINISH + i = the union kernels of layer index i (and
@@ -272,6 +286,7 @@ gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_sr
 #define GNS_STAGE_PLAN 18   /* CACHE_ONLY, GNS_FLAGS_PER_BATCH: the two work-list kernels          */
 #define GNS_STAGE_FLAG 19   /* CACHE_ONLY, GNS_FLAGS_PER_BATCH: the CSR-segment scan (one kernel)  */
 #define GNS_STAGE_SELECT 20 /* CACHE_ONLY: the per-row selection kernel                            */
+#define GNS_STAGE_DENSE 21  /* gns_sage_dense                                                      */
 gns_status gns_profile_begin(gns_ctx* ctx, uint32_t stage_mask, int32_t capacity);
 gns_status gns_profile_collect(gns_ctx* ctx, int32_t stage, double* total_ms, int32_t* launches);
 

@@ -81,6 +81,8 @@ def _load():
     lib.gns_gather_features.restype = ctypes.c_int
     lib.gns_aggregate.argtypes = [vp, P(gns_block), vp, i32, vp, vp]
     lib.gns_aggregate.restype = ctypes.c_int
+    lib.gns_sage_dense.argtypes = [vp, vp, i32, vp, i32, vp, vp, i32, i32, vp, i32, vp]
+    lib.gns_sage_dense.restype = ctypes.c_int
     lib.gns_profile_begin.argtypes = [vp, ctypes.c_uint32, i32]
     lib.gns_profile_begin.restype = ctypes.c_int
     lib.gns_profile_collect.argtypes = [vp, i32, P(ctypes.c_double), P(i32)]
@@ -95,9 +97,10 @@ lib = _load()
 EXPORTED = ["gns_workspace_bytes", "gns_block_capacity", "gns_create", "gns_destroy", "gns_sample_cache",
             "gns_cache_view", "gns_sample_blocks", "gns_gather_features", "gns_aggregate", "gns_last_error",
             "gns_profile_begin", "gns_profile_collect", "gns_sample_blocks_async", "gns_sample_blocks_wait",
-            "gns_fork", "gns_fork_workspace_bytes", "gns_cache_walk_probability", "gns_cache_probability_view"]
+            "gns_fork", "gns_fork_workspace_bytes", "gns_cache_walk_probability", "gns_cache_probability_view", "gns_sage_dense"]
 
 GNS_STAGE_SAMPLE, GNS_STAGE_FINISH, GNS_STAGE_GATHER, GNS_STAGE_AGGREGATE = 0, 8, 16, 17
+GNS_STAGE_DENSE = 21
 GNS_STAGE_PLAN, GNS_STAGE_FLAG, GNS_STAGE_SELECT = 18, 19, 20
 
 
@@ -243,6 +246,14 @@ def gns_gather_features(ctx, nodes_dev, num_nodes, out_dev, stream=None):
 def gns_aggregate(ctx, block, x_src_dev, feat_dim, out_dev, stream=None):
     _check(lib.gns_aggregate(ctx, ctypes.byref(block), x_src_dev.data_ptr(), feat_dim, out_dev.data_ptr(),
                              _stream_ptr(stream)), ctx)
+
+
+def gns_sage_dense(ctx, h_self_dev, h_neigh_dev, w_dev, bias_dev, relu, out_dev, num_rows, stream=None):
+    f1, f2, hdim = h_self_dev.shape[1], h_neigh_dev.shape[1], w_dev.shape[1]
+    assert w_dev.shape[0] == f1 + f2 and all(t.is_contiguous() for t in (h_self_dev, h_neigh_dev, w_dev, out_dev))
+    _check(lib.gns_sage_dense(ctx, h_self_dev.data_ptr(), f1, h_neigh_dev.data_ptr(), f2, w_dev.data_ptr(),
+                              None if bias_dev is None else bias_dev.data_ptr(), hdim, 1 if relu else 0,
+                              out_dev.data_ptr(), num_rows, _stream_ptr(stream)), ctx)
 
 
 def gns_profile_begin(ctx, stage_mask, capacity):

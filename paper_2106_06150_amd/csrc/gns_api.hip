@@ -612,6 +612,25 @@ gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t n
     return GNS_OK;
 }
 
+gns_status gns_sage_dense(gns_ctx* ctx, const float* h_self_dev, int32_t f1, const float* h_neigh_dev, int32_t f2,
+                          const float* w_dev, const float* bias_dev, int32_t hdim, int32_t relu, float* out_dev,
+                          int32_t num_rows, void* hip_stream)
+{
+    if (!ctx) return GNS_EINVAL;
+    if (!h_self_dev || !h_neigh_dev || !w_dev || !out_dev) return ctx_fail(ctx, GNS_EINVAL, "null input, weight or output");
+    if (f1 < 4 || f2 < 4 || hdim < 4 || (f1 & 3) || (f2 & 3) || (hdim & 3))
+        return ctx_fail(ctx, GNS_EINVAL, "f1, f2 and hdim must be positive multiples of 4");
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(h_self_dev) | reinterpret_cast<uintptr_t>(h_neigh_dev) |
+                           reinterpret_cast<uintptr_t>(w_dev) | reinterpret_cast<uintptr_t>(out_dev);
+    if (bits & 15u) return ctx_fail(ctx, GNS_EINVAL, "inputs, weights and output must be 16-byte aligned");
+    if (num_rows < 0 && -1 - num_rows >= ctx->config.num_layers) return ctx_fail(ctx, GNS_EINVAL, "bad device-count placeholder");
+    StageTimer t(ctx, GNS_STAGE_DENSE, static_cast<hipStream_t>(hip_stream));
+    hipError_t e = launch_sage_dense(ctx, h_self_dev, f1, h_neigh_dev, f2, w_dev, bias_dev, hdim, relu, out_dev, num_rows,
+                                     static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "dense launch", e);
+    return GNS_OK;
+}
+
 gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_src_dev, int32_t feat_dim,
                          float* out_dev, void* hip_stream)
 {

@@ -154,6 +154,11 @@ struct StageTimer {
     }
 };
 
+// gns_dense.hip
+hipError_t launch_sage_dense(gns_ctx* c, const float* h_self, int32_t f1, const float* h_neigh, int32_t f2,
+                             const float* w, const float* bias, int32_t hdim, int32_t relu, float* out,
+                             int32_t num_rows, hipStream_t s);
+
 // gns_walk.hip
 gns_status run_walk_probability(gns_ctx* c, const int32_t* train_nodes, int64_t num_train, int32_t scale_log2,
                                 hipStream_t s);

@@ -414,3 +414,34 @@ def test_config4_int64_offsets_and_host_features():
 
 def test_config5_giant_graph():
     _config_parity(5, batches=2, device_gen="cuda", flag_mode=0)
+
+
+@pytest.mark.parametrize("rows,f1,f2,hdim,relu,use_bias", [(1000, 128, 128, 256, True, True), (1, 4, 8, 12, False, False),
+                                                            (129, 100, 128, 132, True, False), (517, 64, 32, 40, False, True)])
+def test_sage_dense_update_step(rows, f1, f2, hdim, relu, use_bias):
+    """h_u = g(W . (h_u, h_N(u))) on the matrix cores against the fp64 oracle.  fp32 products are
+    exact in the fp32 accumulator up to one rounding per addition: K + 1 additions of terms bounded
+    by S = sum |a||w| + |b| give an error of at most (K + 2) * 2^-24 * S; the oracle's own final
+    rounding adds 2^-24 of the result."""
+    ip, ix = _small(n=600)
+    gns = GpuGns(ip, ix, None, fanouts=(2,), policies=(U,), cache_size=0, max_seeds=8)
+    try:
+        g = torch.Generator().manual_seed(rows + hdim)
+        hs = torch.randn((rows, f1), generator=g)
+        hn = torch.randn((rows, f2), generator=g)
+        w = torch.randn((f1 + f2, hdim), generator=g) / np.sqrt(f1 + f2)
+        b = torch.randn(hdim, generator=g) if use_bias else None
+        out = torch.full((rows, hdim), float("nan"), device=gns.device)
+        B.gns_sage_dense(gns.ctx, hs.cuda(), hn.cuda(), w.cuda(), None if b is None else b.cuda(), relu, out, rows)
+        torch.cuda.synchronize()
+        ref = oracle.sage_dense(hs.numpy(), hn.numpy(), w.numpy(), None if b is None else b.numpy(), relu)
+        a = np.concatenate([hs.numpy(), hn.numpy()], axis=1).astype(np.float64)
+        scale = np.abs(a) @ np.abs(w.numpy().astype(np.float64)) + (0.0 if b is None else np.abs(b.numpy().astype(np.float64)))
+        bound = (f1 + f2 + 3) * 2.0 ** -24 * scale
+        err = np.abs(out.cpu().numpy().astype(np.float64) - ref.astype(np.float64))
+        assert np.all(err <= bound), float(np.max(err / bound))
+        with pytest.raises(B.GnsError):                           # widths must be multiples of 4
+            B.gns_sage_dense(gns.ctx, hs.cuda()[:, :f1 - 1].contiguous(), hn.cuda(),
+                             w.cuda()[1:].contiguous(), None, relu, out, rows)
+    finally:
+        gns.close()
