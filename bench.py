@@ -64,6 +64,9 @@ def main():
                     help="degree: Eq. (1), the workload the metric is quoted on; walk: Section 3.2's random-walk "
                          "probability from the workload's training split (computed once, outside the timed region, "
                          "and reported on its own)")
+    ap.add_argument("--dense-hidden", type=int, default=0,
+                    help="if > 0 every step also runs the input layer's update step h = relu(W.(h_self, h_neigh)+b) "
+                         "with this many output features (synthetic W; outside the metric's path, reported on its own)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference point for rocprofv3 byte counters)")
     ap.add_argument("--skip-pass-a", action="store_true", help="profiling aid: only the single-stream pass")
@@ -137,6 +140,13 @@ def main():
     x_in = [torch.empty((bufs[i].array[last].cap_src, F), dtype=torch.float32, device=dev) for i in range(S)]
     h_out = [torch.empty((bufs[i].array[last].cap_dst, F), dtype=torch.float32, device=dev) for i in range(S)]
 
+    H = args.dense_hidden
+    if H > 0:
+        gen = torch.Generator(device=dev).manual_seed(sd["feat"] + 17)
+        w_dense = torch.randn((2 * F, H), device=dev, generator=gen) / (2 * F) ** 0.5
+        b_dense = torch.randn(H, device=dev, generator=gen)
+        z_out = [torch.empty((bufs[i].array[last].cap_dst, H), dtype=torch.float32, device=dev) for i in range(S)]
+
     def refresh_cache(b):
         torch.cuda.synchronize()                          # no batch may be in flight while the cache changes
         B.gns_sample_cache(ctx, sd["cache"], b // refresh, streams[0])
@@ -149,6 +159,8 @@ def main():
         B.gns_sample_blocks_async(ctxs[i], sd["batch"] + b, seeds[b], bufs[i].array, st)
         B.gns_gather_features(ctxs[i], bufs[i].tensors[last]["src_nodes"], -1, x_in[i], st)
         B.gns_aggregate(ctxs[i], bufs[i].array[last], x_in[i], F, h_out[i], st)
+        if H > 0:   # the dst nodes are the first rows of the gathered input features
+            B.gns_sage_dense(ctxs[i], x_in[i], h_out[i], w_dense, b_dense, True, z_out[i], -1 - last, st)
 
     torch.cuda.synchronize()
     if args.calib_copy:
@@ -177,11 +189,11 @@ def main():
     stages = {"sample_layer_%d" % (L - i): B.GNS_STAGE_SAMPLE + i for i in range(L)}
     stages.update({"finish_layer_%d" % (L - i): B.GNS_STAGE_FINISH + i for i in range(L)})
     stages.update({"plan": B.GNS_STAGE_PLAN, "flag": B.GNS_STAGE_FLAG, "select": B.GNS_STAGE_SELECT,
-                   "gather": B.GNS_STAGE_GATHER, "aggregate": B.GNS_STAGE_AGGREGATE})
+                   "gather": B.GNS_STAGE_GATHER, "aggregate": B.GNS_STAGE_AGGREGATE, "dense": B.GNS_STAGE_DENSE})
     mask = 0
     for sid in stages.values():
         mask |= 1 << sid
-    B.gns_profile_begin(ctx, mask, K * (2 * L + 6))
+    B.gns_profile_begin(ctx, mask, K * (2 * L + 7))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for b in range(W, total):
@@ -314,6 +326,11 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "walk_probability": walk_info,
+        "dense_update": None if H == 0 or "dense" not in stage_us else {
+            "hidden": H, "avg_launch_us": stage_us["dense"], "bound": "mfma", "dtype": "f32",
+            "achieved": round(2.0 * avg["rows"] * 2 * F * H / (stage_us["dense"] * 1e-6) / 1e12, 2),
+            "peak": 157.3, "unit": "TFLOP/s",
+            "frac": round(2.0 * avg["rows"] * 2 * F * H / (stage_us["dense"] * 1e-6) / 1e12 / 157.3, 4)},
         "single_stream": {"value": round(K / elapsed_b, 2), "ms_per_step": round(1e3 * elapsed_b / K, 4),
                           "stage_us": stage_us},
     }
