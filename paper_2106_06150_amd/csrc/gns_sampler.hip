@@ -103,10 +103,11 @@ __device__ __forceinline__ void mark_if_new(const SampleArgs& a, uint32_t u)
 template <int G>
 __global__ void __launch_bounds__(kBlock) k_sample_uniform(SampleArgs a, FinishArgs prev, int relabel_blocks)
 {
-    // the first relabel_blocks blocks finish the previous layer's block instead (see relabel_body)
-    if ((int) blockIdx.x < relabel_blocks) { relabel_body(prev, blockIdx.x, relabel_blocks); return; }
-    const int64_t block = (int64_t) blockIdx.x - relabel_blocks;
+    // the last relabel_blocks blocks finish the previous layer's block instead (see relabel_body); they are
+    // dispatched after this layer's rows, whose dependent loads set the length of the launch
     const int64_t nblocks = (int64_t) gridDim.x - relabel_blocks;
+    if ((int64_t) blockIdx.x >= nblocks) { relabel_body(prev, (int64_t) blockIdx.x - nblocks, relabel_blocks); return; }
+    const int64_t block = (int64_t) blockIdx.x;
     const int32_t R = a.st->num_dst[a.layer_index];
     const int k = a.fanout;
     constexpr int kRowsPerWave = kWave / G;
@@ -175,8 +176,9 @@ constexpr int kPlanTile = kBlock;
 __global__ void __launch_bounds__(kBlock) k_plan_count(SampleArgs a, FinishArgs prev, int relabel_blocks)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
-    if ((int) blockIdx.x < relabel_blocks) { relabel_body(prev, blockIdx.x, relabel_blocks); return; }
-    const int64_t tile = (int64_t) blockIdx.x - relabel_blocks;
+    const int64_t ntiles = (int64_t) gridDim.x - relabel_blocks;
+    if ((int64_t) blockIdx.x >= ntiles) { relabel_body(prev, (int64_t) blockIdx.x - ntiles, relabel_blocks); return; }
+    const int64_t tile = (int64_t) blockIdx.x;
     const int32_t R = a.st->num_dst[a.layer_index];
     const int64_t r = tile * kPlanTile + threadIdx.x;
     if (tile * kPlanTile >= R) return;
@@ -504,16 +506,17 @@ __device__ __forceinline__ void select_row(const SampleArgs& a, int64_t row, boo
 // G lanes per dst row, one flag word per lane and step.  Hub rows (listed when their nodes joined
 // the batch) would keep the rest of their wave waiting, so for G < 64 the row blocks skip them
 // and hub_blocks further blocks give each of them a whole wave (64 * kHubWords words per step).
-// Block order: relabel blocks of the previous layer, hub blocks, row blocks.
+// Block order: hub blocks, row blocks, relabel blocks of the previous layer.
 template <int G>
 __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs prev, int relabel_blocks, int hub_blocks)
 {
-    if ((int) blockIdx.x < relabel_blocks) { relabel_body(prev, blockIdx.x, relabel_blocks); return; }
+    const int64_t own_blocks = (int64_t) gridDim.x - relabel_blocks;
+    if ((int64_t) blockIdx.x >= own_blocks) { relabel_body(prev, (int64_t) blockIdx.x - own_blocks, relabel_blocks); return; }
     const int wave_in_block = __builtin_amdgcn_readfirstlane((int) (threadIdx.x >> 6));
-    if ((int) blockIdx.x < relabel_blocks + hub_blocks) {
+    if ((int) blockIdx.x < hub_blocks) {
         const int32_t H = a.st->hub_count;
         const int32_t nhw = hub_blocks * (kBlock / kWave);
-        for (int32_t h = ((int32_t) blockIdx.x - relabel_blocks) * (kBlock / kWave) + wave_in_block; h < H; h += nhw) {
+        for (int32_t h = (int32_t) blockIdx.x * (kBlock / kWave) + wave_in_block; h < H; h += nhw) {
             const int lane = opaque_lane_id();
             const int32_t row = a.hub_rows[h];
             const RowExtent ext = a.row_ext[row];
@@ -522,8 +525,8 @@ __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs
         }
         return;
     }
-    const int64_t block = (int64_t) blockIdx.x - relabel_blocks - hub_blocks;
-    const int64_t nblocks = (int64_t) gridDim.x - relabel_blocks - hub_blocks;
+    const int64_t block = (int64_t) blockIdx.x - hub_blocks;
+    const int64_t nblocks = own_blocks - hub_blocks;
     const int32_t R = a.st->num_dst[a.layer_index];
     constexpr int kRowsPerWave = kWave / G;
     const int64_t wave_global = block * (kBlock / kWave) + wave_in_block;
