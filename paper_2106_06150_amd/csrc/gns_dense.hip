@@ -4,14 +4,14 @@
 //
 // Tiling: a block of 256 threads (4 waves, 2 x 2) owns a 128 x 128 tile of the output and walks K in
 // steps of 32.  The A (activations, concatenated on the fly from the two inputs) and B (weights)
-// tiles of a step are staged in LDS k-major; lane l feeds A[m = l % 32][k = l / 32] and
-// B[k = l / 32][n = l % 32] of a 32 x 32 product.  Inside an LDS row the 128 columns are permuted so
-// that the two 32 x 32 tiles a wave needs sit side by side (column c = 64*w + 32*t + i is stored at
-// 64*w + 2*i + t): one 8-byte LDS read then brings a lane's operands for both tiles, and every read of
-// the K loop is the same base address plus a constant.  The tiles of the next step are fetched into
-// registers while the current step multiplies.  Each wave keeps
-// 2 x 2 accumulator tiles of 32 x 32 (64 VGPRs); element v of lane l is row 8*(v/4) + 4*(l/32) + v%4,
-// column l % 32 of its tile.
+// tiles of a step are staged in LDS; lane l feeds A[m = l % 32][k = l / 32] and
+// B[k = l / 32][n = l % 32] of a 32 x 32 product.  A is kept row-major with a row stride of 33 floats,
+// B k-major: both the staging writes (a thread's four consecutive k of one row, or its float4 of one
+// k-row) and the operand reads (32 consecutive rows of one k, or 32 consecutive columns) then spread
+// over the LDS banks.  The tiles of the next step are fetched into registers while the current step
+// multiplies, and the operands of step kk + 2 are read before the products of step kk are issued.  Each
+// wave keeps 2 x 2 accumulator tiles of 32 x 32 (64 registers); element v of lane l is row
+// 8*(v/4) + 4*(l/32) + v%4, column l % 32 of its tile.
 #include "gns_internal.h"
 #include "gns_device.hpp"
 
@@ -21,10 +21,8 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kDM = 128, kDN = 128, kDK = 32;
 constexpr int kDFetch = kDM * kDK / 4 / kBlock;  // float4 per thread and operand tile
-constexpr int kDPad = 4;                      // keeps 16-byte alignment of LDS rows, spreads the transposed writes
-
-// position of tile column c (0..127) inside an LDS row
-__device__ __forceinline__ int dense_slot(int c) { return (c & 64) | ((c & 31) << 1) | ((c >> 5) & 1); }
+constexpr int kDPad = 4;                      // B rows: keeps their 16-byte alignment
+constexpr int kDAStride = kDK + 1;            // A rows: an odd stride spreads rows over the banks
 
 struct DenseArgs {
     const float* a1;
@@ -40,7 +38,7 @@ struct DenseArgs {
 // at least two blocks per CU: one block's fetch, staging and epilogue run under another's products
 __global__ void __launch_bounds__(kBlock, 2) k_sage_dense(DenseArgs a)
 {
-    __shared__ float As[kDK][kDM + kDPad];
+    __shared__ float As[kDM][kDAStride];
     __shared__ float Bs[kDK][kDN + kDPad];
     const int32_t rows = a.rows_dev ? *a.rows_dev : a.rows;
     const int32_t m0 = (int32_t) blockIdx.x * kDM, n0 = (int32_t) blockIdx.y * kDN;
@@ -78,16 +76,13 @@ __global__ void __launch_bounds__(kBlock, 2) k_sage_dense(DenseArgs a)
 #pragma unroll
         for (int j = 0; j < kDFetch; ++j) {
             const int idx = tid + j * kBlock;
-            const int row = dense_slot(idx / kA4), kc = (idx % kA4) * 4;
-            As[kc + 0][row] = ra[j].x;
-            As[kc + 1][row] = ra[j].y;
-            As[kc + 2][row] = ra[j].z;
-            As[kc + 3][row] = ra[j].w;
+            const int row = idx / kA4, kc = (idx % kA4) * 4;
+            As[row][kc + 0] = ra[j].x;
+            As[row][kc + 1] = ra[j].y;
+            As[row][kc + 2] = ra[j].z;
+            As[row][kc + 3] = ra[j].w;
             const int kr = idx >> 5, nc = (idx & 31) * 4;
-            Bs[kr][dense_slot(nc + 0)] = rb[j].x;
-            Bs[kr][dense_slot(nc + 1)] = rb[j].y;
-            Bs[kr][dense_slot(nc + 2)] = rb[j].z;
-            Bs[kr][dense_slot(nc + 3)] = rb[j].w;
+            *reinterpret_cast<float4*>(&Bs[kr][nc]) = rb[j];
         }
     };
 
@@ -106,26 +101,29 @@ __global__ void __launch_bounds__(kBlock, 2) k_sage_dense(DenseArgs a)
     for (int32_t k0 = 0; k0 < K; k0 += kDK) {
         const bool more = k0 + kDK < K;
         if (more) fetch(k0 + kDK);
-        // a lane's operands of both tiles in one 8-byte read; the reads of step kk + 2 are issued before
-        // the products of step kk
-        const float2* arow = reinterpret_cast<const float2*>(&As[kh][wm * 64 + l32 * 2]);
-        const float2* brow = reinterpret_cast<const float2*>(&Bs[kh][wn * 64 + l32 * 2]);
-        constexpr int kRow2 = (kDM + kDPad) / 2;                       // LDS row stride in float2
-        float2 af[2], bf[2];
-        af[0] = arow[0];
-        bf[0] = brow[0];
+        const float* arow = &As[wm * 64 + l32][kh];
+        const float* brow = &Bs[kh][wn * 64 + l32];
+        float af[2][2], bf[2][2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            af[0][t] = arow[t * 32 * kDAStride];
+            bf[0][t] = brow[t * 32];
+        }
 #pragma unroll
         for (int kk = 0; kk < kDK; kk += 2) {
             const int cur = (kk >> 1) & 1;
             if (kk + 2 < kDK) {
-                af[cur ^ 1] = arow[(kk + 2) * kRow2];
-                bf[cur ^ 1] = brow[(kk + 2) * kRow2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    af[cur ^ 1][t] = arow[t * 32 * kDAStride + kk + 2];
+                    bf[cur ^ 1][t] = brow[(kk + 2) * (kDN + kDPad) + t * 32];
+                }
             }
             __builtin_amdgcn_sched_barrier(0);          // the reads above stay ahead of the products below
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur].x, bf[cur].x, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur].x, bf[cur].y, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur].y, bf[cur].x, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur].y, bf[cur].y, acc[1][1], 0, 0, 0);
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][0], bf[cur][0], acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][0], bf[cur][1], acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][1], bf[cur][0], acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][1], bf[cur][1], acc[1][1], 0, 0, 0);
         }
         __syncthreads();
         if (more) {
