@@ -119,7 +119,7 @@ void fill_begin_args(gns_ctx* c, const int32_t* seeds, BeginArgsHost* out)
     a->row_ext = ws_ptr<RowExtent>(c, L.row_ext);
     a->g_indptr = c->graph.indptr;
     a->g_i64 = c->graph.indptr_is_i64;
-    a->hub_rows = ws_ptr<int32_t>(c, L.hub_rows);
+    a->hub_rows = c->uses_cache ? ws_ptr<int32_t>(c, L.hub_rows) : nullptr;
     a->seed_copy = ws_ptr<int32_t>(c, L.seed_copy);
 }
 
@@ -292,7 +292,7 @@ void fill_finish_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, con
     a.row_ext = ws_ptr<RowExtent>(c, L.row_ext);
     a.g_indptr = c->graph.indptr;
     a.g_i64 = c->graph.indptr_is_i64;
-    a.hub_rows = ws_ptr<int32_t>(c, L.hub_rows);
+    a.hub_rows = c->uses_cache ? ws_ptr<int32_t>(c, L.hub_rows) : nullptr;
 }
 
 int relabel_grid(const gns_ctx* c, int layer_index)

@@ -67,14 +67,14 @@ __device__ __forceinline__ bool is_hub_extent(int64_t start, int64_t end)
 // Appends `row` for the calling lanes that have is_hub set: one atomic per wave.
 __device__ __forceinline__ void append_hub_rows(DeviceState* st, int32_t* hub_rows, bool is_hub, int32_t row)
 {
-    const uint64_t m = __ballot(is_hub);
+    const uint64_t m = __ballot(is_hub && hub_rows != nullptr);      // no list without a cache layer
     if (m == 0) return;
     const int lane = lane_id();
     const int leader = __builtin_ctzll(m);
     int32_t base = 0;
     if (lane == leader) base = atomicAdd(&st->hub_count, (int32_t) __popcll(m));
     base = __shfl(base, leader, kWave);
-    if (is_hub) hub_rows[base + __popcll(m & ((1ull << lane) - 1ull))] = row;
+    if (is_hub && hub_rows) hub_rows[base + __popcll(m & ((1ull << lane) - 1ull))] = row;
 }
 
 void fill_finish_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, const gns_block* blk, FinishArgs* out);
