@@ -317,22 +317,13 @@ hipError_t launch_finish_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
 
 // The last layer's relabel has no following sampler to ride with; it also leaves the context's
 // other hash map empty for the next mini-batch (nothing in this batch touches that map).
-__global__ void __launch_bounds__(kBlock) k_relabel_last(FinishArgs a, unsigned long long* other_slots, size_t cap,
-                                                         int relabel_blocks)
+__global__ void __launch_bounds__(kBlock) k_relabel_last(FinishArgs a, unsigned long long* other_slots, size_t cap)
 {
-    if ((int) blockIdx.x < relabel_blocks) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) a.st->hub_count = 0;      // the next batch starts a new hub list
-        relabel_body(a, blockIdx.x, relabel_blocks);
-        return;
-    }
-    // the remaining blocks empty the other map with 16-byte stores: few waves, each with a long stream
-    // of independent stores, so the clear holds few of the chip's wave slots
-    ulonglong2* p = reinterpret_cast<ulonglong2*>(other_slots);
-    const size_t n2 = cap / 2;                                              // cap is a power of two >= 2
-    size_t i = ((size_t) blockIdx.x - relabel_blocks) * kBlock + threadIdx.x;
-    const size_t stride = ((size_t) gridDim.x - relabel_blocks) * kBlock;
-    const ulonglong2 empty = make_ulonglong2(kEmptySlot, kEmptySlot);
-    for (; i < n2; i += stride) p[i] = empty;
+    relabel_body(a, blockIdx.x, gridDim.x);
+    size_t i = (size_t) blockIdx.x * kBlock + threadIdx.x;
+    if (i == 0) a.st->hub_count = 0;                 // the next batch starts a new hub list
+    const size_t stride = (size_t) gridDim.x * kBlock;
+    for (; i < cap; i += stride) other_slots[i] = kEmptySlot;
 }
 
 hipError_t launch_relabel(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s)
@@ -340,10 +331,10 @@ hipError_t launch_relabel(gns_ctx* c, int layer_index, const int32_t* dst_nodes,
     FinishArgs a;
     fill_finish_args(c, layer_index, dst_nodes, blk, &a);
     unsigned long long* other = ws_ptr<unsigned long long>(c, c->lay.hash_slots[c->hash_parity ^ 1]);
-    const int rl = relabel_grid(c, layer_index);
-    const int clear_blocks = c->num_cus * 2;
-    hipLaunchKernelGGL(k_relabel_last, dim3((unsigned) (rl + clear_blocks)), dim3(kBlock), 0, s, a, other,
-                       (size_t) c->lay.hash_cap, rl);
+    unsigned grid = (unsigned) relabel_grid(c, layer_index);
+    const unsigned fill = fill_grid(c->lay.hash_cap);
+    if (grid < fill) grid = fill;
+    hipLaunchKernelGGL(k_relabel_last, dim3(grid), dim3(kBlock), 0, s, a, other, (size_t) c->lay.hash_cap);
     return hipGetLastError();
 }
 
