@@ -8,6 +8,16 @@
 
 namespace gns {
 
+// Output rows are written once and not read again by the writing kernel: a non-temporal store keeps
+// them from displacing the rows other waves still want from L2.
+__device__ __forceinline__ void store_streaming(float4* p, const float4& v)
+{
+    __builtin_nontemporal_store(v.x, &p->x);
+    __builtin_nontemporal_store(v.y, &p->y);
+    __builtin_nontemporal_store(v.z, &p->z);
+    __builtin_nontemporal_store(v.w, &p->w);
+}
+
 struct GatherArgs {
     const int32_t* nodes;
     int32_t num_nodes;
@@ -47,7 +57,7 @@ __global__ void __launch_bounds__(kBlock) k_gather(GatherArgs a)
             const float4* s4 = reinterpret_cast<const float4*>(src);
             float4* d4 = reinterpret_cast<float4*>(dst);
             for (int i = lane; i < (int) (F >> 2); i += kLanes)
-                d4[i] = valid ? s4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+                store_streaming(d4 + i, valid ? s4[i] : make_float4(0.f, 0.f, 0.f, 0.f));
         } else {
             for (int i = lane; i < (int) F; i += kLanes) dst[i] = valid ? src[i] : 0.f;
         }
@@ -198,7 +208,7 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggArgs a)
                 const float n_v = (float) (e0 - b0);
                 acc.x /= n_v; acc.y /= n_v; acc.z /= n_v; acc.w /= n_v;
             }
-            if (has) reinterpret_cast<float4*>(a.out + row * F)[lane] = acc;
+            if (has) store_streaming(reinterpret_cast<float4*>(a.out + row * F) + lane, acc);
             b0 = b1; e0 = e1; b1 = b2; e1 = e2; b2 = b3; e2 = e3;
         }
         return;
