@@ -323,7 +323,7 @@ __global__ void __launch_bounds__(kBlock) k_relabel_last(FinishArgs a, unsigned 
     size_t i = (size_t) blockIdx.x * kBlock + threadIdx.x;
     if (i == 0) a.st->hub_count = 0;                 // the next batch starts a new hub list
     const size_t stride = (size_t) gridDim.x * kBlock;
-    for (; i < cap; i += stride) other_slots[i] = kEmptySlot;
+    for (; i < cap; i += stride) __builtin_nontemporal_store((unsigned long long) kEmptySlot, &other_slots[i]);   // streamed, not re-read soon
 }
 
 hipError_t launch_relabel(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s)
