@@ -4,15 +4,19 @@
 // The sampler leaves, per dst row, up to k global neighbor ids at a fixed
 // stride and has set one bit per sampled id in a node-indexed mark bitmap.
 // Here:
+//   begin    the batch's first kernel: scalars, seeds with their local ids into the batch's
+//            hash map, the seeds' CSR extents and hub entries
 //   phase 1  per-tile sums of the row counts and of the mark bitmap's
 //            population (the sampler marks only ids without a local id)
 //   phase 3  every block adds up the sums of the tiles before its own, scans
 //            its tile and writes: indptr for row tiles; for bitmap tiles the
 //            marked ids in ascending order behind the dst prefix, one thread
-//            per new id, each inserted into the hash map with its local id;
-//            the bitmap words are cleared for the next layer
+//            per new id, each inserted into the hash map with its local id, its
+//            CSR extent recorded; the bitmap words are cleared for the next layer
 //   relabel  every sampled edge looks its neighbor's local id up and is
-//            compacted to its CSR position
+//            compacted to its CSR position (inside the next layer's first sampler
+//            launch; the last layer's own launch also empties the hash map the
+//            next batch will use)
 // Sorted order comes from walking the bitmap, so the result does not depend on
 // the order in which threads ran.
 #include "gns_kernels.hpp"

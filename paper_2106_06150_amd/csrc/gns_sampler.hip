@@ -6,6 +6,8 @@
 //   CACHE_ONLY  Sections 3.3 and 4.1: the eligible list is the row's entries
 //               whose node is in the cache, in CSR order; min(k, N_C(v)) of
 //               them are chosen; each carries the Section 3.4 weight.
+//   CACHE_FIRST Section 3.3: as CACHE_ONLY; a row with N_C(v) < k then draws the
+//               shortfall uniformly from its entries outside the cache.
 //
 // The without-replacement choice is Robert Floyd's subset algorithm on ranks
 // of the eligible list, driven by k Philox words keyed by (seed, layer, node,
