@@ -188,6 +188,12 @@ def test_error_paths():
         with pytest.raises(B.GnsError) as e:                               # no features configured
             B.gns_gather_features(gns.ctx, seeds, 4, torch.empty(4, device="cuda"))
         assert e.value.status == B.GNS_ESTATE
+        with pytest.raises(B.GnsError) as e:                               # the config draws the cache by degree
+            B.gns_cache_walk_probability(gns.ctx, seeds, 10)
+        assert e.value.status == B.GNS_ESTATE
+        with pytest.raises(B.GnsError) as e:
+            B.gns_cache_probability_view(gns.ctx)
+        assert e.value.status == B.GNS_ESTATE
     finally:
         gns.close()
 
@@ -375,6 +381,12 @@ def test_async_pipeline_on_forked_contexts():
         last = len(fanouts) - 1
         xin = [torch.zeros((b.array[last].cap_src, F), dtype=torch.float32, device=gns.device) for b in bufs]
         out = [torch.zeros((b.array[last].cap_dst, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        H = 24                                                # the update step rides along, counts on the device too
+        gw = torch.Generator().manual_seed(77)
+        w_dense = torch.randn((2 * F, H), generator=gw) / np.sqrt(2 * F)
+        b_dense = torch.randn(H, generator=gw)
+        w_dev, b_dev = w_dense.cuda(), b_dense.cuda()
+        z = [torch.zeros((b.array[last].cap_dst, H), dtype=torch.float32, device=gns.device) for b in bufs]
         for rnd in range(2):
             seeds = [synth.uniform_seed_batch(n, bs - 7 * i, 300 + 10 * rnd + i).cuda() for i in range(len(ctxs))]
             torch.cuda.synchronize()
@@ -384,6 +396,7 @@ def test_async_pipeline_on_forked_contexts():
                     assert bufs[i].array[last].num_dst == -1 - last
                     B.gns_gather_features(ctx, bufs[i].tensors[last]["src_nodes"], -1, xin[i], streams[i])
                     B.gns_aggregate(ctx, bufs[i].array[last], xin[i], F, out[i], streams[i])
+                    B.gns_sage_dense(ctx, xin[i], out[i], w_dev, b_dev, True, z[i], -1 - last, streams[i])
             for i, ctx in enumerate(ctxs):
                 B.gns_sample_blocks_wait(ctx, bufs[i].array, streams[i])
             torch.cuda.synchronize()
@@ -396,6 +409,14 @@ def test_async_pipeline_on_forked_contexts():
                 o_ref = oracle.aggregate(ref[last].indptr, ref[last].indices, ref[last].weights, x_ref)
                 from gpu_harness import compare_aggregate, aggregate_scale
                 compare_aggregate(out[i][:ref[last].num_dst].cpu().numpy(), o_ref, aggregate_scale(ref[last], x_ref))
+                # the update step saw the GPU's own aggregate; feed the oracle the same fp32 rows
+                nd = ref[last].num_dst
+                hs, hn = xin[i][:nd].cpu().numpy(), out[i][:nd].cpu().numpy()
+                z_ref = oracle.sage_dense(hs, hn, w_dense.numpy(), b_dense.numpy(), True)
+                scale = np.abs(np.concatenate([hs, hn], axis=1).astype(np.float64)) @ np.abs(w_dense.numpy().astype(np.float64)) \
+                    + np.abs(b_dense.numpy().astype(np.float64))
+                err = np.abs(z[i][:nd].cpu().numpy().astype(np.float64) - z_ref.astype(np.float64))
+                assert np.all(err <= (2 * F + 3) * 2.0 ** -24 * scale)
         with pytest.raises(B.GnsError):                       # the cache belongs to the created context
             B.gns_sample_cache(forks[0], 1, 0)
     finally:
