@@ -116,6 +116,21 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     L.shared_begin = off;
     L.cache_bitmap = take((size_t) L.words * 8);
     L.cache_prefix = take((size_t) L.words * 4);
+    // A cache bitmap too big for LDS gets a coarse companion that does fit: one bit per 2^shift ids.  With a
+    // cache of about 1 % of the nodes it answers "not cached" for most entries without leaving the CU as long as
+    // the groups stay small.
+    L.coarse_shift = 0;
+    L.coarse_words = 0;
+    L.coarse_bitmap = 0;
+    if (uses_cache && (size_t) L.words * 8 > kLdsBitmapBytes) {
+        int sh = 1;
+        while (sh <= 4 && (size_t) (((n >> sh) + 63) / 64 + 1) * 8 > kLdsBitmapBytes) ++sh;
+        if (sh <= 4) {
+            L.coarse_shift = sh;
+            L.coarse_words = ((n >> sh) + 63) / 64 + 1;
+            L.coarse_bitmap = take((size_t) (L.coarse_words + 1) * 8);
+        }
+    }
     L.cache_nodes = take((size_t) (C > 0 ? C : 1) * 4);
     L.cache_feat = take((size_t) (C > 0 ? C : 1) * (size_t) (g->feat_dim > 0 ? g->feat_dim : 1) * 4);
     if (uses_cache) {
@@ -329,7 +344,7 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
     if (e != hipSuccess) return bail(GNS_EHIP, "hipGetDeviceProperties", e);
     c->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     // the flag kernel may keep the whole cache bitmap in LDS (one 1024-thread block per CU)
-    c->lds_bitmap_limit = prop.sharedMemPerBlock > 1024 ? prop.sharedMemPerBlock - 1024 : 0;
+    c->lds_bitmap_limit = prop.sharedMemPerBlock >= kLdsBitmapBytes + 1024 ? kLdsBitmapBytes : 0;
     e = hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(DeviceState), hipHostMallocDefault);
     if (e != hipSuccess) { c->h_state = nullptr; return bail(GNS_EHIP, "hipHostMalloc", e); }
     if (!getenv("GNS_NO_GRAPH")) {

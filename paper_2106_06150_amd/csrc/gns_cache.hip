@@ -256,6 +256,26 @@ __global__ void __launch_bounds__(kBlock) k_cache_pc(const int32_t* cache_nodes,
     node_inv_pc[u] = (float) (1.0 / pc);
 }
 
+// Coarse companion of the cache bitmap: bit g of the result is set iff some node of
+// [g << shift, (g + 1) << shift) is cached.  One thread per 64-bit coarse word.
+__global__ void __launch_bounds__(kBlock) k_cache_coarse(const uint64_t* bitmap, int64_t words, int shift,
+                                                         uint64_t* coarse, int64_t coarse_words)
+{
+    const int64_t cw = (int64_t) blockIdx.x * kBlock + threadIdx.x;
+    if (cw >= coarse_words) return;
+    const int fine_per_coarse = 1 << shift;                    // fine words folded into one coarse word
+    const int groups_per_fine = 64 >> shift;                   // coarse bits one fine word yields
+    const uint64_t group_mask = (shift == 6) ? ~0ull : ((1ull << (1 << shift)) - 1ull);
+    uint64_t out = 0;
+    for (int f = 0; f < fine_per_coarse; ++f) {
+        const int64_t w = cw * fine_per_coarse + f;
+        const uint64_t x = (w < words) ? bitmap[w] : 0ull;
+        for (int g = 0; g < groups_per_fine; ++g)
+            if ((x >> (g << shift)) & group_mask) out |= 1ull << (f * groups_per_fine + g);
+    }
+    coarse[cw] = out;
+}
+
 // ---------------------------------------------------------------------------
 static gns_status fail(gns_ctx* c, gns_status st, const char* what, hipError_t e)
 {
@@ -356,6 +376,12 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
         if (i64) hipLaunchKernelGGL((k_cache_pc<int64_t>), dim3(pc_blocks), dim3(kBlock), 0, s, x.cache_nodes, C, prob_prefix, (int64_t) prob_total, node_pc);
         else     hipLaunchKernelGGL((k_cache_pc<int32_t>), dim3(pc_blocks), dim3(kBlock), 0, s, x.cache_nodes, C, prob_prefix, (int64_t) prob_total, node_pc);
         GNS_HIP_TRY(hipGetLastError(), "cache weight table launch");
+    }
+    if (L.coarse_shift > 0) {
+        const unsigned cb = (unsigned) ((L.coarse_words + kBlock - 1) / kBlock);
+        hipLaunchKernelGGL(k_cache_coarse, dim3(cb), dim3(kBlock), 0, s, bitmap, (int64_t) L.words, (int) L.coarse_shift,
+                           ws_ptr<uint64_t>(c, L.coarse_bitmap), (int64_t) L.coarse_words);
+        GNS_HIP_TRY(hipGetLastError(), "coarse bitmap launch");
     }
     if (c->config.flag_mode == GNS_FLAGS_PER_CACHE)
         GNS_HIP_TRY(launch_flag_all_entries(c, s), "flag all entries");

@@ -25,9 +25,15 @@ struct DeviceState {
     int32_t walk_error;                   //   1: bad training node, 2: does not fit in 62 bits
 };
 
+// LDS a flag-kernel block may fill with a membership bitmap (the chip's 160 KB minus the block's own needs)
+constexpr size_t kLdsBitmapBytes = 160 * 1024 - 1024;
+
 struct Layout {
     // persistent cache structures
     size_t cache_bitmap, cache_prefix, cache_nodes, cache_feat;
+    size_t coarse_bitmap;     // one bit per 2^coarse_shift node ids: "some node of the group is cached" (0: unused)
+    int32_t coarse_shift;
+    int64_t coarse_words;
     // random-walk cache probability (only with GNS_PROB_WALK): two weight vectors, their prefix, scan partials
     size_t walk_a, walk_b, prob_prefix, walk_tiles, walk_tiles_nz;
     size_t node_pc;           // [n] floats: 1 / p^C_u (Section 3.4), filled for the nodes of the current cache

@@ -54,6 +54,9 @@ struct SampleArgs {
     int32_t* plan_desc;        // [chunks] ids of the aligned chunks to flag
     uint64_t* flags;           // [ceil(nnz / 64)] bit e & 63 of word e >> 6: entry e points into the cache
     int64_t bitmap_words;
+    const uint64_t* coarse_bitmap;   // one bit per 2^coarse_shift ids (flag kernel, mode 2)
+    int64_t coarse_words;
+    int coarse_shift;
 };
 
 // Floyd's subset draw inside a group of G consecutive lanes (G a power of two
@@ -237,7 +240,9 @@ constexpr int kFlagBatch = 64;      // work-list entries a wave fetches at once 
 // bitmap reads, all tests -- so that the loads of the whole set are in flight together.
 //   kCareful: the set may hold the last chunk of the entry array, whose tail lanes lie beyond
 //   num_entries; those lanes re-read the last entry and are masked out of the ballot.
-template <bool kLds, bool kCareful>
+//   kMode 0: the bitmap is read from global memory; 1: from LDS; 2: LDS holds the coarse bitmap (one bit
+//   per group of ids): only the entries whose group has a cached node go on to read the exact bitmap.
+template <int kMode, bool kCareful>
 __device__ __forceinline__ void flag_chunk_set(const SampleArgs& a, const uint32_t* lds32, int32_t my_chunk, int sub,
                                                int lane, uint32_t* lo, uint32_t* hi)
 {
@@ -253,11 +258,20 @@ __device__ __forceinline__ void flag_chunk_set(const SampleArgs& a, const uint32
         const int off = (kCareful && g == last_chunk) ? lane_clamped : lane;
         u[i] = (uint32_t) row[off];
     }
+    const uint32_t* exact32 = reinterpret_cast<const uint32_t*>(a.cache_bitmap);
     uint32_t w[kFlagUnroll];
 #pragma unroll
     for (int i = 0; i < kFlagUnroll; ++i) {
-        if (kLds) w[i] = lds32[u[i] >> 5];
-        else      w[i] = reinterpret_cast<const uint32_t*>(a.cache_bitmap)[u[i] >> 5];
+        if (kMode == 1)      w[i] = lds32[u[i] >> 5];
+        else if (kMode == 0) w[i] = exact32[u[i] >> 5];
+        else                 w[i] = lds32[(u[i] >> a.coarse_shift) >> 5];
+    }
+    if (kMode == 2) {
+#pragma unroll
+        for (int i = 0; i < kFlagUnroll; ++i) {
+            const bool maybe = (w[i] >> ((u[i] >> a.coarse_shift) & 31u)) & 1u;
+            w[i] = maybe ? exact32[u[i] >> 5] : 0u;
+        }
     }
 #pragma unroll
     for (int i = 0; i < kFlagUnroll; ++i) {
@@ -267,15 +281,15 @@ __device__ __forceinline__ void flag_chunk_set(const SampleArgs& a, const uint32
     }
 }
 
-// kLds: the cache bitmap is first copied into dynamic LDS (rounded up to 16 bytes).
-// Every wave takes an equal, contiguous share of the work list.
-template <bool kLds>
+// kMode 1 / 2: the cache bitmap / its coarse companion is first copied into dynamic LDS (rounded up to
+// 16 bytes).  Every wave takes an equal, contiguous share of the work list.
+template <int kMode>
 __global__ void k_flag_chunks(SampleArgs a, int use_plan, int64_t all_chunks)
 {
     extern __shared__ uint4 lds_bitmap16[];
-    if (kLds) {
-        const uint4* src = reinterpret_cast<const uint4*>(a.cache_bitmap);
-        const int64_t n16 = (a.bitmap_words + 1) / 2;
+    if (kMode != 0) {
+        const uint4* src = reinterpret_cast<const uint4*>(kMode == 1 ? a.cache_bitmap : a.coarse_bitmap);
+        const int64_t n16 = ((kMode == 1 ? a.bitmap_words : a.coarse_words) + 1) / 2;
         constexpr int kFill = 4;
         for (int64_t base = 0; base < n16; base += (int64_t) blockDim.x * kFill) {
             uint4 v[kFill];
@@ -314,8 +328,8 @@ __global__ void k_flag_chunks(SampleArgs a, int use_plan, int64_t all_chunks)
         const bool careful = last_is_partial && __ballot((int64_t) my_chunk == last_chunk) != 0ull;
         uint32_t lo = 0, hi = 0;
         for (int sub = 0; sub < here; sub += kFlagUnroll) {                            // scalar bounds
-            if (careful) flag_chunk_set<kLds, true>(a, lds32, my_chunk, sub, lane, &lo, &hi);
-            else         flag_chunk_set<kLds, false>(a, lds32, my_chunk, sub, lane, &lo, &hi);
+            if (careful) flag_chunk_set<kMode, true>(a, lds32, my_chunk, sub, lane, &lo, &hi);
+            else         flag_chunk_set<kMode, false>(a, lds32, my_chunk, sub, lane, &lo, &hi);
         }
         if (lane < here) a.flags[my_chunk] = ((uint64_t) hi << 32) | lo;
     }
@@ -557,10 +571,13 @@ static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nod
 static void launch_flag_kernel(gns_ctx* c, const SampleArgs& a, int use_plan, int64_t all_chunks, hipStream_t s)
 {
     const size_t lds_bytes = (size_t) ((c->lay.words + 1) / 2) * 16;
+    const size_t coarse_bytes = (size_t) ((c->lay.coarse_words + 1) / 2) * 16;
     if (lds_bytes <= c->lds_bitmap_limit)
-        hipLaunchKernelGGL((k_flag_chunks<true>), dim3((unsigned) c->num_cus), dim3(1024), lds_bytes, s, a, use_plan, all_chunks);
+        hipLaunchKernelGGL((k_flag_chunks<1>), dim3((unsigned) c->num_cus), dim3(1024), lds_bytes, s, a, use_plan, all_chunks);
+    else if (c->lay.coarse_shift > 0 && coarse_bytes <= c->lds_bitmap_limit)
+        hipLaunchKernelGGL((k_flag_chunks<2>), dim3((unsigned) c->num_cus), dim3(1024), coarse_bytes, s, a, use_plan, all_chunks);
     else
-        hipLaunchKernelGGL((k_flag_chunks<false>), dim3((unsigned) c->num_cus * 8), dim3(kBlock), 0, s, a, use_plan, all_chunks);
+        hipLaunchKernelGGL((k_flag_chunks<0>), dim3((unsigned) c->num_cus * 8), dim3(kBlock), 0, s, a, use_plan, all_chunks);
 }
 
 // GNS_FLAGS_PER_CACHE: one pass over every aligned chunk of the CSR entry array.
@@ -609,6 +626,9 @@ static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nod
     a.plan_desc = ws_ptr<int32_t>(c, L.plan_desc);
     a.flags = ws_ptr<uint64_t>(c, L.edge_flags);
     a.bitmap_words = L.words;
+    a.coarse_bitmap = L.coarse_shift ? ws_ptr<uint64_t>(c, L.coarse_bitmap) : nullptr;
+    a.coarse_words = L.coarse_words;
+    a.coarse_shift = L.coarse_shift;
 }
 
 hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, int32_t* row_eligible,
