@@ -33,8 +33,8 @@ struct FinishArgs {
     int32_t* hub_rows;             // phase 3 appends the new nodes that are hubs
 };
 
-// Relabel: every sampled edge of a finished layer looks its neighbor's local id up in the batch's
-// hash map and is compacted to its CSR position.  `block` of `nblocks` blocks of kBlock threads.
+// Relabel: every sampled edge of a finished layer gets its neighbor's local id (from the scratch slot if
+// the sampler already found one, else from the batch's hash map) and is compacted to its CSR position.  `block` of `nblocks` blocks of kBlock threads.
 // It only needs that layer's phase 3, so it shares a launch with the next layer's first kernel.
 __device__ __forceinline__ void relabel_body(const FinishArgs& a, int64_t block, int64_t nblocks)
 {
@@ -46,9 +46,9 @@ __device__ __forceinline__ void relabel_body(const FinishArgs& a, int64_t block,
         const int32_t row = (int32_t) (t / a.fanout);
         const int32_t s = (int32_t) (t - (int64_t) row * a.fanout);
         if (s < a.s_cnt[row]) {
-            const int32_t u = a.s_nbr[t];
+            const int32_t u = a.s_nbr[t];          // -(local id + 1) if the sampler already knew it, else the global id
             const int32_t o = a.indptr[row] + s;
-            a.indices[o] = hash_lookup(a.slots, a.hmask, a.hshift, (uint32_t) u);
+            a.indices[o] = u < 0 ? -1 - u : hash_lookup(a.slots, a.hmask, a.hshift, (uint32_t) u);
             a.weights[o] = a.s_w[t];
         }
     }

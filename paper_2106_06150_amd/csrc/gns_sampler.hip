@@ -14,7 +14,8 @@
 // slot); the chosen ranks are emitted in ascending order.  All decisions are
 // integer arithmetic, so the sample does not depend on scheduling.
 //
-// Output per row r (fixed stride k): s_nbr[r*k + i], s_w[r*k + i] for
+// Output per row r (fixed stride k): s_nbr[r*k + i] (the neighbor's local id as -(id+1) if it has
+// one, else its global id), s_w[r*k + i] for
 // i < s_cnt[r], row_eligible[r]; every emitted id that has no local id yet
 // (it is not a dst node of this layer) also sets its bit in the node-indexed
 // mark bitmap that the frontier stage turns into the src list.
@@ -96,11 +97,15 @@ __device__ __forceinline__ void floyd_in_group(uint32_t m, int k, int k_loop, ui
     *pos = rank;
 }
 
-// A sampled id becomes a new src node unless it already owns a local id.
-__device__ __forceinline__ void mark_if_new(const SampleArgs& a, uint32_t u)
+// A sampled id becomes a new src node unless it already owns a local id.  Returns what the relabel
+// step should find in the scratch slot: the node's local id as -(id + 1) if it has one (no second
+// lookup then), else the global id (>= 0), whose local id is assigned by the union step.
+__device__ __forceinline__ int32_t mark_if_new(const SampleArgs& a, uint32_t u)
 {
-    if (hash_lookup(a.slots, a.hmask, a.hshift, u) < 0)
-        atomicOr(reinterpret_cast<unsigned long long*>(&a.mark[u >> 6]), 1ull << (u & 63u));
+    const int32_t local = hash_lookup(a.slots, a.hmask, a.hshift, u);
+    if (local >= 0) return -1 - local;
+    atomicOr(reinterpret_cast<unsigned long long*>(&a.mark[u >> 6]), 1ull << (u & 63u));
+    return (int32_t) u;
 }
 
 // ---------------------------------------------------------------------------
@@ -143,9 +148,8 @@ __global__ void __launch_bounds__(kBlock) k_sample_uniform(SampleArgs a, FinishA
         if (m <= (uint32_t) k) { val = (uint32_t) s; pos = s; }
         if (live && s < cnt) {
             const int32_t u = a.indices[start + val];
-            a.s_nbr[row * k + pos] = u;
             a.s_w[row * k + pos] = 1.0f;
-            mark_if_new(a, (uint32_t) u);
+            a.s_nbr[row * k + pos] = mark_if_new(a, (uint32_t) u);
         }
         if (live && s == 0) {
             a.s_cnt[row] = cnt;
@@ -482,9 +486,8 @@ __device__ __forceinline__ void select_row(const SampleArgs& a, int64_t row, boo
         float wgt;
         if (a.wmode == GNS_W_UNBIASED) wgt = inv_pc * ((float) m / (float) cnt);
         else                           wgt = inv_pc * ((float) cnt / (float) k);
-        a.s_nbr[row * k + pos] = u;
         a.s_w[row * k + pos] = wgt;
-        mark_if_new(a, (uint32_t) u);
+        a.s_nbr[row * k + pos] = mark_if_new(a, (uint32_t) u);
     }
 
     // Section 3.3: a row with fewer than k cached neighbors fills up from its other neighbors, drawn
@@ -506,9 +509,8 @@ __device__ __forceinline__ void select_row(const SampleArgs& a, int64_t row, boo
                 // fill neighbors: weight 1 (a node-wise sample), or the inverse inclusion probability of a
                 // uniform subset of the uncached neighbors in the unbiased mode
                 const float wgt = (a.wmode == GNS_W_UNBIASED) ? (float) others / (float) fill : 1.0f;
-                a.s_nbr[row * k + cnt + fpos] = u;
                 a.s_w[row * k + cnt + fpos] = wgt;
-                mark_if_new(a, (uint32_t) u);
+                a.s_nbr[row * k + cnt + fpos] = mark_if_new(a, (uint32_t) u);
             }
             total = cnt + fill;
         }
