@@ -429,6 +429,30 @@ def test_config3_products_shaped_graph():
     _config_parity(3, batches=2, device_gen="cuda")
 
 
+def test_config3_cache_first_per_cache_flags():
+    _config_parity(3, batches=1, device_gen="cuda", flag_mode=1, upper=CF, check_features=False)
+
+
+def test_config2_walk_probability_at_scale():
+    """The random-walk cache probability on the medium graph from a 10 % training split: weights and prefix
+    bit for bit, then one mini-batch drawn with that cache."""
+    c = synth.CONFIGS[2]
+    sd = synth.config_seeds(2)
+    g = synth.make_config_graph(2)
+    ip, ix = g.indptr, g.indices
+    train = synth.training_split(c["n"], 100_000, sd["split"])
+    gns = GpuGns(ip, ix, None, fanouts=c["fanouts"], policies=(CF, CF, C), cache_size=int(c["n"] * c["cache_frac"]),
+                 max_seeds=c["batch"], flag_mode=1, cache_probability=B.GNS_PROB_WALK)
+    try:
+        w, pre, total, support = gns.walk_probability(train, 24)
+        w_ref, pre_ref = oracle.walk_weights(ip.numpy(), ix.numpy(), train.numpy(), list(c["fanouts"]), scale_log2=24)
+        assert np.array_equal(w, w_ref) and np.array_equal(pre, pre_ref) and total == int(pre_ref[-1])
+        gns.prob_prefix = pre_ref
+        full_parity(gns, cache_seed=sd["cache"], epoch=0, batch_seed=sd["batch"], seeds=train[:c["batch"]])
+    finally:
+        gns.close()
+
+
 def test_config4_int64_offsets_and_host_features():
     _config_parity(4, batches=1, device_gen="cuda", flag_mode=1)
 
