@@ -92,6 +92,8 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     L.seed_copy = take((size_t) cfg->max_seeds * 4);
     L.row_ext = take((size_t) L.rows[cfg->num_layers] * 16);
     L.hub_rows = take((size_t) L.rows[cfg->num_layers] * 4);
+    L.slot_list[0] = take((size_t) L.rows[cfg->num_layers] * 4);
+    L.slot_list[1] = take((size_t) L.rows[cfg->num_layers] * 4);
     L.hash_slots[0] = take((size_t) L.hash_cap * 8);
     L.hash_slots[1] = take((size_t) L.hash_cap * 8);
     for (int par = 0; par < 2; ++par) {

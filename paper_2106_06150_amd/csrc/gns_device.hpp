@@ -71,19 +71,19 @@ __device__ __forceinline__ uint32_t hash_start(uint32_t key, uint32_t shift)
     return (key * 0x9E3779B1u) >> shift;    // shift = 32 - log2(capacity)
 }
 
-// returns true if inserted, false if the key was already present
-__device__ __forceinline__ bool hash_insert(unsigned long long* slots, uint32_t mask, uint32_t shift,
-                                            uint32_t key, uint32_t val)
+// returns the slot the entry went into, or -1 if the key was already present (or the table is full)
+__device__ __forceinline__ int64_t hash_insert(unsigned long long* slots, uint32_t mask, uint32_t shift,
+                                               uint32_t key, uint32_t val)
 {
     const unsigned long long entry = ((unsigned long long) val << 32) | key;
     uint32_t h = hash_start(key, shift);
     for (uint32_t probe = 0; probe <= mask; ++probe) {
         const unsigned long long old = atomicCAS(&slots[h], (unsigned long long) kEmptySlot, entry);
-        if (old == kEmptySlot) return true;
-        if ((uint32_t) old == key) return false;
+        if (old == kEmptySlot) return (int64_t) h;
+        if ((uint32_t) old == key) return -1;
         h = (h + 1) & mask;
     }
-    return false;
+    return -1;
 }
 
 // local id of `key`, or -1 if absent

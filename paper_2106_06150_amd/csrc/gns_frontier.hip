@@ -77,6 +77,7 @@ struct BeginArgs {
     int g_i64;
     int32_t* hub_rows;
     int32_t* seed_copy;
+    uint32_t* slot_list;
 };
 
 __global__ void __launch_bounds__(kBlock) k_batch_begin(BeginArgs a, int32_t num_seeds, uint32_t key0, uint32_t key1,
@@ -100,8 +101,9 @@ __global__ void __launch_bounds__(kBlock) k_batch_begin(BeginArgs a, int32_t num
         a.seed_copy[q] = u;
         a.row_ext[q] = ext;
         append_hub_rows(a.st, a.hub_rows, is_hub_extent(ext.start, ext.end), (int32_t) q);
-        const bool ok = in_range && hash_insert(a.slots, a.hmask, a.hshift, (uint32_t) u, (uint32_t) q);
-        if (!ok) a.st->bad_seed = batch_id;
+        const int64_t slot = in_range ? hash_insert(a.slots, a.hmask, a.hshift, (uint32_t) u, (uint32_t) q) : -1;
+        a.slot_list[q] = slot >= 0 ? (uint32_t) slot : 0xFFFFFFFFu;
+        if (slot < 0) a.st->bad_seed = batch_id;
     }
 }
 
@@ -125,6 +127,7 @@ void fill_begin_args(gns_ctx* c, const int32_t* seeds, BeginArgsHost* out)
     a->g_i64 = c->graph.indptr_is_i64;
     a->hub_rows = c->uses_cache ? ws_ptr<int32_t>(c, L.hub_rows) : nullptr;
     a->seed_copy = ws_ptr<int32_t>(c, L.seed_copy);
+    a->slot_list = ws_ptr<uint32_t>(c, L.slot_list[c->hash_parity]);
 }
 
 hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, uint32_t batch_id,
@@ -261,7 +264,8 @@ __global__ void __launch_bounds__(kBlock) k_finish_phase3(FinishArgs a)
             a.src_nodes[pos] = (int32_t) node;
             a.row_ext[pos] = ext;
             append_hub_rows(a.st, a.hub_rows, is_hub_extent(ext.start, ext.end), pos);
-            hash_insert(a.slots, a.hmask, a.hshift, node, (uint32_t) pos);
+            const int64_t slot = hash_insert(a.slots, a.hmask, a.hshift, node, (uint32_t) pos);
+            a.slot_list[pos] = slot >= 0 ? (uint32_t) slot : 0xFFFFFFFFu;
         }
     }
 }
@@ -297,6 +301,8 @@ void fill_finish_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, con
     a.g_indptr = c->graph.indptr;
     a.g_i64 = c->graph.indptr_is_i64;
     a.hub_rows = c->uses_cache ? ws_ptr<int32_t>(c, L.hub_rows) : nullptr;
+    a.slot_list = ws_ptr<uint32_t>(c, L.slot_list[c->hash_parity]);
+    a.parity = c->hash_parity;
 }
 
 int relabel_grid(const gns_ctx* c, int layer_index)
@@ -319,26 +325,34 @@ hipError_t launch_finish_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
     return hipGetLastError();
 }
 
-// The last layer's relabel has no following sampler to ride with; it also leaves the context's
-// other hash map empty for the next mini-batch (nothing in this batch touches that map).
-__global__ void __launch_bounds__(kBlock) k_relabel_last(FinishArgs a, unsigned long long* other_slots, size_t cap)
+// The last layer's relabel has no following sampler to ride with; its launch also leaves the context's
+// other hash map empty for the next mini-batch (nothing in this batch touches that map).  The map was
+// filled by the batch before this one; every insertion recorded its slot, so emptying it means
+// resetting exactly those slots -- a few hundred KB instead of the whole table.
+__global__ void __launch_bounds__(kBlock) k_relabel_last(FinishArgs a, unsigned long long* other_slots,
+                                                         const uint32_t* other_slot_list, int total_layers)
 {
     relabel_body(a, blockIdx.x, gridDim.x);
-    size_t i = (size_t) blockIdx.x * kBlock + threadIdx.x;
-    if (i == 0) a.st->hub_count = 0;                 // the next batch starts a new hub list
+    const int32_t stale = a.st->map_nodes[a.parity ^ 1];
     const size_t stride = (size_t) gridDim.x * kBlock;
-    for (; i < cap; i += stride) __builtin_nontemporal_store((unsigned long long) kEmptySlot, &other_slots[i]);   // streamed, not re-read soon
+    for (size_t i = (size_t) blockIdx.x * kBlock + threadIdx.x; i < (size_t) stale; i += stride) {
+        const uint32_t slot = other_slot_list[i];
+        if (slot != 0xFFFFFFFFu) other_slots[slot] = kEmptySlot;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        a.st->hub_count = 0;                                     // the next batch starts a new hub list
+        a.st->map_nodes[a.parity] = a.st->num_dst[total_layers]; // what the clear of this batch's map will have to undo
+    }
 }
 
 hipError_t launch_relabel(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s)
 {
     FinishArgs a;
     fill_finish_args(c, layer_index, dst_nodes, blk, &a);
-    unsigned long long* other = ws_ptr<unsigned long long>(c, c->lay.hash_slots[c->hash_parity ^ 1]);
-    unsigned grid = (unsigned) relabel_grid(c, layer_index);
-    const unsigned fill = fill_grid(c->lay.hash_cap);
-    if (grid < fill) grid = fill;
-    hipLaunchKernelGGL(k_relabel_last, dim3(grid), dim3(kBlock), 0, s, a, other, (size_t) c->lay.hash_cap);
+    const int other = c->hash_parity ^ 1;
+    hipLaunchKernelGGL(k_relabel_last, dim3((unsigned) relabel_grid(c, layer_index)), dim3(kBlock), 0, s, a,
+                       ws_ptr<unsigned long long>(c, c->lay.hash_slots[other]),
+                       ws_ptr<uint32_t>(c, c->lay.slot_list[other]), (int) c->config.num_layers);
     return hipGetLastError();
 }
 

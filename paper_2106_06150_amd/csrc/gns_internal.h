@@ -16,6 +16,7 @@ struct DeviceState {
     int32_t num_edges[GNS_MAX_LAYERS];
     uint32_t key0, key1;                  // Philox key of the current batch (lo32(seed), hi32(seed))
     uint32_t bad_seed;                    // id of the last batch that had a seed out of range or repeated
+    int32_t map_nodes[2];                 // entries of each of the two hash maps (what its next clear has to undo)
     int32_t hub_count;                    // entries of the batch's hub-row list (reset by the batch's last kernel)
     int32_t chunk_distinct;               // cache draw: first occurrences found in the current chunk
     int32_t plan_chunks;                  // CACHE_ONLY sampler: aligned chunks in the current work list
@@ -44,6 +45,7 @@ struct Layout {
     size_t seed_copy;         // [max_seeds] the batch's seeds, copied by its first kernel
     size_t hub_rows;          // [max nodes of a batch] rows whose CSR segment spans more than kHubChunks chunks
     size_t row_ext;           // [max nodes of a batch] CSR extent of every node of the batch's list (append-only)
+    size_t slot_list[2];      // [max nodes of a batch] per hash map: the slot each of the batch's nodes went into
     size_t hash_slots[2];     // consecutive batches alternate: each one leaves the other map empty for the next
     // per-layer sampler scratch (fixed stride fanout)
     size_t s_nbr[2], s_w[2], s_cnt[2];     // double-buffered by layer parity

@@ -31,6 +31,8 @@ struct FinishArgs {
     const void* g_indptr;          // the graph's offsets
     int g_i64;
     int32_t* hub_rows;             // phase 3 appends the new nodes that are hubs
+    uint32_t* slot_list;           // phase 3 records the hash slot of every new node (for the sparse clear)
+    int parity;                    // which of the two hash maps this batch uses
 };
 
 // Relabel: every sampled edge of a finished layer gets its neighbor's local id (from the scratch slot if
