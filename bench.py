@@ -264,6 +264,11 @@ def main():
         "timed_in": "pass B (same K steps, one stream, HIP events on that stream)",
         "other_kernels_GBps": {kernel_of[s_]: round(alg[s_] / (1e3 * stage_us[s_]), 1) for s_ in candidates if s_ != dom},
     }
+    if dom == "aggregate":
+        # its edge rows come from a few thousand distinct source rows that stay in L2: the HBM side is the
+        # output stream, the kernel itself is bound by L2 reads
+        roofline["note"] = ("%d edge rows of %d B are read from %d distinct L2-resident source rows: L2-read bound, "
+                            "HBM sees the output rows" % (avg["edges"], F * 4, avg["read_rows"]))
     if dom == "flag":
         # what a layout that stores only the cached neighbors (Section 3.3's induced subgraph) would read
         roofline["induced_subgraph_bytes_per_launch"] = int(avg["eligible"] * 4 + avg["chunks"] * 8)
