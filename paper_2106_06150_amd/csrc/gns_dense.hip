@@ -40,9 +40,8 @@ __global__ void __launch_bounds__(kBlock, 2) k_sage_dense(DenseArgs a)
 {
     __shared__ float As[kDM][kDAStride];
     __shared__ float Bs[kDK][kDN + kDPad];
-    const int32_t rows = a.rows_dev ? *a.rows_dev : a.rows;
     const int32_t m0 = (int32_t) blockIdx.x * kDM, n0 = (int32_t) blockIdx.y * kDN;
-    if (m0 >= rows) return;
+    if (m0 >= a.rows) return;
     const int32_t K = a.f1 + a.f2;
     const int tid = (int) threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -58,7 +57,7 @@ __global__ void __launch_bounds__(kBlock, 2) k_sage_dense(DenseArgs a)
                 const int row = idx / kA4, k = k0 + (idx % kA4) * 4;
                 const int64_t gr = (int64_t) m0 + row;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (gr < rows && k < K) {
+                if (gr < a.rows && k < K) {              // a.rows: what the buffers hold (the device count may be smaller)
                     const float* p = (k < a.f1) ? a.a1 + gr * a.f1 + k : a.a2 + gr * a.f2 + (k - a.f1);
                     v = *reinterpret_cast<const float4*>(p);
                 }
@@ -95,6 +94,10 @@ __global__ void __launch_bounds__(kBlock, 2) k_sage_dense(DenseArgs a)
             for (int v = 0; v < 16; ++v) acc[mt][nt][v] = 0.f;
 
     fetch(0);
+    // the row count read on the device is needed for the early exit and the stores only, so the first
+    // fetch does not wait for it
+    const int32_t rows = a.rows_dev ? *a.rows_dev : a.rows;
+    if (m0 >= rows) return;
     stage();
     __syncthreads();
     const int kh = lane >> 5, l32 = lane & 31;
