@@ -136,6 +136,25 @@ def test_rows_with_no_neighbors_and_no_cached_neighbors():
         gns.close()
 
 
+def test_maximum_fanout_and_maximum_depth():
+    """The limits of the config: fan-out 64 at every policy, and 8 layers."""
+    ip, ix = _small(n=2000, avg=40, seed=13, hub=4)
+    n = ip.numel() - 1
+    for policies in [(U, C), (CF, CF)]:
+        gns = GpuGns(ip, ix, None, fanouts=(64, 64), policies=policies, cache_size=600, max_seeds=24)
+        try:
+            full_parity(gns, cache_seed=3, epoch=0, batch_seed=14, seeds=synth.uniform_seed_batch(n, 24, 2))
+        finally:
+            gns.close()
+    gns = GpuGns(ip, ix, _feat(n, 8), fanouts=(2, 1, 2, 1, 2, 1, 2, 3), policies=(U, CF, U, CF, U, C, U, C), cache_size=300,
+                 max_seeds=16)
+    try:
+        views, ref = full_parity(gns, cache_seed=5, epoch=1, batch_seed=15, seeds=synth.uniform_seed_batch(n, 16, 3))
+        assert len(ref) == 8
+    finally:
+        gns.close()
+
+
 def test_single_seed_and_repeatability():
     ip, ix = _small()
     n = ip.numel() - 1
