@@ -171,6 +171,31 @@ def test_single_seed_and_repeatability():
         gns.close()
 
 
+def test_graph_replays_and_eager_launches_agree_with_the_oracle():
+    """The batch's launch sequence is captured once per hash-map parity and replayed; with stage timing on
+    it is issued kernel by kernel instead.  Replays, eager runs and replays again, with different seeds and
+    batch sizes on the same buffers, all against the oracle."""
+    ip, ix = _small(n=4000, avg=18, seed=17)
+    n = ip.numel() - 1
+    gns = GpuGns(ip, ix, _feat(n, 32), fanouts=(7, 5, 4), policies=(CF, U, C), cache_size=350, max_seeds=120)
+    try:
+        step = 0
+        for mode in ("graph", "eager", "graph"):
+            if mode == "eager":
+                B.gns_profile_begin(gns.ctx, (1 << B.GNS_STAGE_SAMPLE) | (1 << B.GNS_STAGE_GATHER), 64)
+            else:
+                B.gns_profile_begin(gns.ctx, 0, 0)
+            for _ in range(5):                                            # both parities, several times over
+                seeds = synth.uniform_seed_batch(n, 120 - 11 * (step % 4), 50 + step)
+                full_parity(gns, cache_seed=8, epoch=step // 4, batch_seed=900 + step, seeds=seeds)
+                step += 1
+            if mode == "eager":
+                ms, launches = B.gns_profile_collect(gns.ctx, B.GNS_STAGE_SAMPLE)
+                assert launches == 5 and ms > 0
+    finally:
+        gns.close()
+
+
 def test_error_paths():
     ip, ix = _small(n=500)
     n = ip.numel() - 1
