@@ -148,7 +148,9 @@ def main():
         z_out = [torch.empty((bufs[i].array[last].cap_dst, H), dtype=torch.float32, device=dev) for i in range(S)]
 
     def refresh_cache(b):
-        torch.cuda.synchronize()                          # no batch may be in flight while the cache changes
+        # The draw fills the copy of the cache structures that is not in use: the batches the other slots have in
+        # flight keep reading the old cache, the batches enqueued from here on read the new one.  It runs on slot
+        # 0's stream (measured: a stream of its own makes it compete with slot 0's batch and costs 4 %).
         B.gns_sample_cache(ctx, sd["cache"], b // refresh, streams[0])
 
     def step(b, i):

@@ -161,8 +161,8 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
  * given the cache, as the paper's sampling workers are).  The fork owns its per-batch
  * scratch in `workspace` (gns_fork_workspace_bytes(parent) bytes, 256-byte aligned) and
  * reads the cache structures of the context made by gns_create, which must outlive it.
- * gns_sample_cache is called on that original context only, and only while no fork has
- * work in flight.  Destroy forks with gns_destroy. */
+ * gns_sample_cache is called on that original context only (see there for what may be in
+ * flight meanwhile).  Destroy forks with gns_destroy. */
 size_t gns_fork_workspace_bytes(const gns_ctx* parent);
 gns_status gns_fork(gns_ctx* parent, void* workspace, size_t workspace_bytes, void* hip_stream,
                     gns_ctx** out_child);
@@ -176,7 +176,16 @@ gns_status gns_destroy(gns_ctx* ctx);
  * node -> slot rank index, the per-slot 1/p^C table and, if features were
  * given, the device table of the cached rows' features in slot order.
  * epoch must be < 2^32.  GNS_ECAPACITY if the stream does not yield
- * cache_size distinct nodes within the library's draw limit. */
+ * cache_size distinct nodes within the library's draw limit.  Synchronises hip_stream.
+ * The library keeps two copies of these structures: the draw fills the copy that is not in
+ * use and makes it the current one when it is complete.  So mini-batches that were enqueued
+ * before the call (on this context or on forks, on other streams) may still be in flight:
+ * they keep reading the cache they were enqueued with; mini-batches enqueued after the call
+ * returns read the new one.  The draw after this one overwrites the copy those older
+ * mini-batches read; it waits on the device for them (every draw records an event on the
+ * stream each context last used, the next draw waits for it), so the host may run ahead freely
+ * as long as each context keeps to one stream between two draws.
+ * All calls on a context and its forks are made from one host thread at a time. */
 gns_status gns_sample_cache(gns_ctx* ctx, uint64_t seed, uint64_t epoch, void* hip_stream);
 
 /* Read-only views of the current cache (device pointers into the workspace,

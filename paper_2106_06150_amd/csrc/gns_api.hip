@@ -116,6 +116,24 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     }
     // shared: the cache and everything that is a pure function of (graph, cache)
     L.shared_begin = off;
+    if (uses_cache) {
+        L.draw_keys = take((size_t) L.draw_hash_cap * 4);
+        L.draw_vals = take((size_t) L.draw_hash_cap * 4);
+        L.draw_node = take((size_t) L.draw_chunk * 4);
+        L.draw_slot = take((size_t) L.draw_chunk * 4);
+        if (cfg->cache_probability == GNS_PROB_WALK) {
+            L.walk_a = take((size_t) n * 8);
+            L.walk_b = take((size_t) n * 8);
+            L.prob_prefix = take((size_t) (n + 1) * 8);
+            const size_t tiles = (size_t) ((n + kTile - 1) / kTile);
+            L.walk_tiles = take((tiles + 1) * 8);
+            L.walk_tiles_nz = take((tiles + 1) * 4);
+        }
+    }
+    // The cache block: everything a cache draw writes and the mini-batches read.  There are two copies
+    // (generations): a draw fills the one that is not in use, so it can run while batches that were
+    // enqueued before it still read the other.
+    L.cache_block_begin = off;
     L.cache_bitmap = take((size_t) L.words * 8);
     L.cache_prefix = take((size_t) L.words * 4);
     // A cache bitmap too big for LDS gets a coarse companion that does fit: one bit per 2^shift ids.  With a
@@ -136,21 +154,11 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     L.cache_nodes = take((size_t) (C > 0 ? C : 1) * 4);
     L.cache_feat = take((size_t) (C > 0 ? C : 1) * (size_t) (g->feat_dim > 0 ? g->feat_dim : 1) * 4);
     if (uses_cache) {
-        L.draw_keys = take((size_t) L.draw_hash_cap * 4);
-        L.draw_vals = take((size_t) L.draw_hash_cap * 4);
-        L.draw_node = take((size_t) L.draw_chunk * 4);
-        L.draw_slot = take((size_t) L.draw_chunk * 4);
         L.edge_flags = take((size_t) (g->num_entries / 64 + 1) * 8);
         L.node_pc = take((size_t) n * 4);
-        if (cfg->cache_probability == GNS_PROB_WALK) {
-            L.walk_a = take((size_t) n * 8);
-            L.walk_b = take((size_t) n * 8);
-            L.prob_prefix = take((size_t) (n + 1) * 8);
-            const size_t tiles = (size_t) ((n + kTile - 1) / kTile);
-            L.walk_tiles = take((tiles + 1) * 8);
-            L.walk_tiles_nz = take((tiles + 1) * 4);
-        }
     }
+    L.cache_block_bytes = off - L.cache_block_begin;
+    if (uses_cache) off += L.cache_block_bytes;            // the second generation
     L.total = off;
     *out = L;
     return true;
@@ -197,9 +205,26 @@ static gns_status enqueue_batch(gns_ctx* c, uint64_t seed, const int32_t* seeds_
     return GNS_OK;
 }
 
-static void graph_release(gns_ctx* c, int par)
+static hipError_t events_create(gns_ctx* c)
 {
-    BatchGraph& g = c->bg[par];
+    c->gen_event[0] = c->gen_event[1] = nullptr;
+    c->gen_event_used[0] = c->gen_event_used[1] = false;
+    c->has_stream = false;
+    c->last_stream = nullptr;
+    hipError_t e = hipEventCreateWithFlags(&c->gen_event[0], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->gen_event[1], hipEventDisableTiming);
+    return e;
+}
+
+static void events_destroy(gns_ctx* c)
+{
+    for (int g = 0; g < 2; ++g)
+        if (c->gen_event[g]) { (void) hipEventDestroy(c->gen_event[g]); c->gen_event[g] = nullptr; }
+}
+
+static void graph_release(gns_ctx* c, int par, int gen)
+{
+    BatchGraph& g = c->bg[par][gen];
     if (g.exec) (void) hipGraphExecDestroy(g.exec);
     if (g.graph) (void) hipGraphDestroy(g.graph);
     g.exec = nullptr;
@@ -209,15 +234,15 @@ static void graph_release(gns_ctx* c, int par)
 }
 
 // The batch's launch sequence does not depend on the data (grids are sized for the worst
-// case and counts stay on the device), so it is captured once per set of caller block buffers and
-// hash-map parity, and replayed with hipGraphLaunch; only the first kernel's arguments (seeds
+// case and counts stay on the device), so it is captured once per set of caller block buffers,
+// hash-map parity and cache generation, and replayed with hipGraphLaunch; only the first kernel's arguments (seeds
 // pointer, seed, seed count, batch id) change between replays.
 static gns_status launch_batch_graph(gns_ctx* c, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
                                      gns_block* blocks, hipStream_t s)
 {
     const int nl = c->config.num_layers;
-    const int par = c->hash_parity;
-    BatchGraph& g = c->bg[par];
+    const int par = c->hash_parity, gen = active_gen(c);
+    BatchGraph& g = c->bg[par][gen];
     bool same = g.valid;
     for (int i = 0; same && i < nl; ++i) {
         const gns_block& a = g.blocks[i];
@@ -227,22 +252,22 @@ static gns_status launch_batch_graph(gns_ctx* c, uint64_t seed, const int32_t* s
     }
     hipError_t e;
     if (!same) {
-        graph_release(c, par);
+        graph_release(c, par, gen);
         e = hipStreamBeginCapture(c->cap_stream, hipStreamCaptureModeRelaxed);
         if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "begin capture", e);
         const gns_status st = enqueue_batch(c, seed, seeds_dev, num_seeds, blocks, c->cap_stream);
         e = hipStreamEndCapture(c->cap_stream, &g.graph);
-        if (st != GNS_OK) { graph_release(c, par); return st; }
-        if (e != hipSuccess) { graph_release(c, par); return ctx_fail(c, GNS_EHIP, "end capture", e); }
+        if (st != GNS_OK) { graph_release(c, par, gen); return st; }
+        if (e != hipSuccess) { graph_release(c, par, gen); return ctx_fail(c, GNS_EHIP, "end capture", e); }
         e = hipGraphInstantiate(&g.exec, g.graph, nullptr, nullptr, 0);
-        if (e != hipSuccess) { graph_release(c, par); return ctx_fail(c, GNS_EHIP, "graph instantiate", e); }
+        if (e != hipSuccess) { graph_release(c, par, gen); return ctx_fail(c, GNS_EHIP, "graph instantiate", e); }
         // find the first kernel's node
         size_t count = 0;
         e = hipGraphGetNodes(g.graph, nullptr, &count);
-        if (e != hipSuccess || count == 0 || count > 256) { graph_release(c, par); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
+        if (e != hipSuccess || count == 0 || count > 256) { graph_release(c, par, gen); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
         hipGraphNode_t nodes[256];
         e = hipGraphGetNodes(g.graph, nodes, &count);
-        if (e != hipSuccess) { graph_release(c, par); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
+        if (e != hipSuccess) { graph_release(c, par, gen); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
         for (size_t i = 0; i < count && !g.first; ++i) {
             hipGraphNodeType type;
             if (hipGraphNodeGetType(nodes[i], &type) != hipSuccess || type != hipGraphNodeTypeKernel) continue;
@@ -250,7 +275,7 @@ static gns_status launch_batch_graph(gns_ctx* c, uint64_t seed, const int32_t* s
             if (hipGraphKernelNodeGetParams(nodes[i], &kp) != hipSuccess) continue;
             if (kp.func == batch_first_kernel()) g.first = nodes[i];
         }
-        if (!g.first) { graph_release(c, par); return ctx_fail(c, GNS_EHIP, "first kernel node not found in the captured graph"); }
+        if (!g.first) { graph_release(c, par, gen); return ctx_fail(c, GNS_EHIP, "first kernel node not found in the captured graph"); }
         for (int i = 0; i < nl; ++i) g.blocks[i] = blocks[i];
         g.valid = true;
     }
@@ -334,6 +359,7 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
         else snprintf(g_create_err, sizeof(g_create_err), "%s", what);
         if (c->h_state) (void) hipHostFree(c->h_state);
         if (c->cap_stream) (void) hipStreamDestroy(c->cap_stream);
+        events_destroy(c);
         delete c;
         return st;
     };
@@ -349,6 +375,10 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
     c->lds_bitmap_limit = prop.sharedMemPerBlock >= kLdsBitmapBytes + 1024 ? kLdsBitmapBytes : 0;
     e = hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(DeviceState), hipHostMallocDefault);
     if (e != hipSuccess) { c->h_state = nullptr; return bail(GNS_EHIP, "hipHostMalloc", e); }
+    e = events_create(c);
+    if (e != hipSuccess) return bail(GNS_EHIP, "hipEventCreate", e);
+    c->family[0] = c;
+    c->family_count = 1;
     if (!getenv("GNS_NO_GRAPH")) {
         e = hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking);
         if (e != hipSuccess) { c->cap_stream = nullptr; return bail(GNS_EHIP, "hipStreamCreate", e); }
@@ -357,7 +387,7 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
     // zero the state, the mark bitmap and the cache bitmap; validate the graph
     e = launch_fill_u32(reinterpret_cast<uint32_t*>(c->d_state), (sizeof(DeviceState) + 64) / 4, 0u, s);
     if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.mark_bitmap), (size_t) L.words, 0ull, s);
-    if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.cache_bitmap), (size_t) L.words, 0ull, s);
+    if (e == hipSuccess) e = launch_fill_u64(cache_ptr<unsigned long long>(c, L.cache_bitmap, 0), (size_t) L.words, 0ull, s);
     for (int par = 0; par < 2 && e == hipSuccess; ++par)
         e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.hash_slots[par]), (size_t) L.hash_cap, ~0ull, s);
     if (e != hipSuccess) return bail(GNS_EHIP, "workspace init", e);
@@ -470,12 +500,19 @@ gns_status gns_fork(gns_ctx* parent, void* workspace, size_t workspace_bytes, vo
     c->hash_parity = 0;
     c->batch_id = 0;
     c->cap_stream = nullptr;
+    c->family_count = 0;
+    c->gen_event[0] = c->gen_event[1] = nullptr;
+    if (root->family_count >= (int) (sizeof(root->family) / sizeof(root->family[0]))) {
+        delete c;
+        return ctx_fail(parent, GNS_ECAPACITY, "too many live forks of one context");
+    }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (root->cap_stream && hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking) != hipSuccess) {
         delete c;
         return ctx_fail(parent, GNS_EHIP, "hipStreamCreate");
     }
     hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(DeviceState), hipHostMallocDefault);
+    if (e == hipSuccess) e = events_create(c);
     if (e == hipSuccess) e = launch_fill_u32(reinterpret_cast<uint32_t*>(c->d_state), (sizeof(DeviceState) + 64) / 4, 0u, s);
     if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, c->lay.mark_bitmap), (size_t) c->lay.words, 0ull, s);
     for (int par = 0; par < 2 && e == hipSuccess; ++par)
@@ -484,9 +521,11 @@ gns_status gns_fork(gns_ctx* parent, void* workspace, size_t workspace_bytes, vo
     if (e != hipSuccess) {
         if (c->h_state) (void) hipHostFree(c->h_state);
         if (c->cap_stream) (void) hipStreamDestroy(c->cap_stream);
+        events_destroy(c);
         delete c;
         return ctx_fail(parent, GNS_EHIP, "fork init", e);
     }
+    root->family[root->family_count++] = c;
     *out_child = c;
     return GNS_OK;
 }
@@ -495,10 +534,16 @@ gns_status gns_destroy(gns_ctx* ctx)
 {
     if (!ctx) return GNS_OK;
     profile_release(ctx);
-    graph_release(ctx, 0);
-    graph_release(ctx, 1);
+    for (int par = 0; par < 2; ++par)
+        for (int gen = 0; gen < 2; ++gen) graph_release(ctx, par, gen);
     if (ctx->cap_stream) (void) hipStreamDestroy(ctx->cap_stream);
     if (ctx->h_state) (void) hipHostFree(ctx->h_state);
+    events_destroy(ctx);
+    if (ctx->root != ctx) {                               // a fork leaves its family
+        gns_ctx* root = ctx->root;
+        for (int i = 0; i < root->family_count; ++i)
+            if (root->family[i] == ctx) { root->family[i] = root->family[--root->family_count]; break; }
+    }
     delete ctx;
     return GNS_OK;
 }
@@ -548,9 +593,9 @@ gns_status gns_cache_view(gns_ctx* ctx, const int32_t** cache_nodes, int64_t* ca
 {
     if (!ctx) return GNS_EINVAL;
     if (!ctx->uses_cache || !ctx->root->cache_valid) return ctx_fail(ctx, GNS_ESTATE, "no cache has been drawn");
-    if (cache_nodes) *cache_nodes = ws_ptr<int32_t>(ctx, ctx->lay.cache_nodes);
+    if (cache_nodes) *cache_nodes = cache_ptr<int32_t>(ctx, ctx->lay.cache_nodes, active_gen(ctx));
     if (cache_size) *cache_size = ctx->config.cache_size;
-    if (bitmap) *bitmap = ws_ptr<uint64_t>(ctx, ctx->lay.cache_bitmap);
+    if (bitmap) *bitmap = cache_ptr<uint64_t>(ctx, ctx->lay.cache_bitmap, active_gen(ctx));
     if (num_draws) *num_draws = ctx->root->cache_draws;
     return GNS_OK;
 }
@@ -580,6 +625,7 @@ gns_status gns_sample_blocks_async(gns_ctx* ctx, uint64_t seed, const int32_t* s
     if (c->prof_mask == 0 && c->cap_stream) st = launch_batch_graph(c, seed, seeds_dev, num_seeds, blocks, s);
     else                                     st = enqueue_batch(c, seed, seeds_dev, num_seeds, blocks, s);
     if (st != GNS_OK) return st;
+    note_cache_readers(c, s);
     c->batch_id += 1;
     c->hash_parity ^= 1;             // this batch has left the other map empty
     for (int i = 0; i < nl; ++i) {
@@ -624,7 +670,8 @@ gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t n
     if (num_nodes == 0) return GNS_OK;
     if (!nodes_dev || !out_dev) return ctx_fail(ctx, GNS_EINVAL, "null nodes or output");
     StageTimer t(ctx, GNS_STAGE_GATHER, static_cast<hipStream_t>(hip_stream));
-    hipError_t e = launch_gather(ctx, nodes_dev, num_nodes, out_dev, static_cast<hipStream_t>(hip_stream));
+    hipError_t e = launch_gather(ctx, nodes_dev, num_nodes, out_dev, active_gen(ctx), static_cast<hipStream_t>(hip_stream));
+    note_cache_readers(ctx, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "gather launch", e);
     return GNS_OK;
 }

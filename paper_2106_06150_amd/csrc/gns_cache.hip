@@ -294,9 +294,28 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
 {
     const Layout& L = c->lay;
     const int64_t C = c->config.cache_size;
-    uint64_t* bitmap = ws_ptr<uint64_t>(c, L.cache_bitmap);
-    c->cache_valid = false;
-
+    // The draw fills the generation the mini-batches are not reading and becomes the active one when it is
+    // complete: batches enqueued before this call keep their cache.
+    const int gen = c->cache_valid ? (c->cache_gen ^ 1) : 0;
+    uint64_t* bitmap = cache_ptr<uint64_t>(c, L.cache_bitmap, gen);
+    // That copy was read by the work enqueued before the previous draw (on any context of the family); the
+    // device may not have reached all of it yet if the host runs far ahead.  The previous draw recorded an
+    // event behind it on every context's stream: wait for those, then record the events the next draw needs.
+    {
+        const int par = (int) (c->refresh_count & 1);
+        for (int i = 0; i < c->family_count; ++i) {
+            gns_ctx* m = c->family[i];
+            if (m->gen_event_used[par ^ 1]) {
+                GNS_HIP_TRY(hipStreamWaitEvent(s, m->gen_event[par ^ 1], 0), "wait for the readers of the old cache");
+                m->gen_event_used[par ^ 1] = false;
+            }
+            if (m->has_stream) {
+                GNS_HIP_TRY(hipEventRecord(m->gen_event[par], m->last_stream), "event record");
+                m->gen_event_used[par] = true;
+            }
+        }
+        c->refresh_count += 1;
+    }
     GNS_HIP_TRY(launch_fill_u64(reinterpret_cast<unsigned long long*>(bitmap), (size_t) L.words, 0ull, s), "clear cache bitmap");
     GNS_HIP_TRY(launch_fill_u32(ws_ptr<uint32_t>(c, L.draw_keys), L.draw_hash_cap, 0xFFFFFFFFu, s), "clear draw keys");
     GNS_HIP_TRY(launch_fill_u32(ws_ptr<uint32_t>(c, L.draw_vals), L.draw_hash_cap, 0xFFFFFFFFu, s), "clear draw vals");
@@ -363,8 +382,8 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
     x.words = L.words;
     x.sums = ws_ptr<int32_t>(c, L.sums_words);
     x.tiles = (int32_t) L.word_tiles;
-    x.word_prefix = ws_ptr<int32_t>(c, L.cache_prefix);
-    x.cache_nodes = ws_ptr<int32_t>(c, L.cache_nodes);
+    x.word_prefix = cache_ptr<int32_t>(c, L.cache_prefix, gen);
+    x.cache_nodes = cache_ptr<int32_t>(c, L.cache_nodes, gen);
     hipLaunchKernelGGL(k_cache_index_phase1, dim3((unsigned) x.tiles), dim3(kBlock), 0, s, x);
     hipLaunchKernelGGL(k_cache_index_phase2, dim3(1), dim3(kBlock), 0, s, x);
     hipLaunchKernelGGL(k_cache_index_phase3, dim3((unsigned) x.tiles), dim3(kBlock), 0, s, x);
@@ -372,7 +391,7 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
 
     {
         const unsigned pc_blocks = (unsigned) ((C + kBlock - 1) / kBlock);
-        float* node_pc = ws_ptr<float>(c, L.node_pc);
+        float* node_pc = cache_ptr<float>(c, L.node_pc, gen);
         if (i64) hipLaunchKernelGGL((k_cache_pc<int64_t>), dim3(pc_blocks), dim3(kBlock), 0, s, x.cache_nodes, C, prob_prefix, (int64_t) prob_total, node_pc);
         else     hipLaunchKernelGGL((k_cache_pc<int32_t>), dim3(pc_blocks), dim3(kBlock), 0, s, x.cache_nodes, C, prob_prefix, (int64_t) prob_total, node_pc);
         GNS_HIP_TRY(hipGetLastError(), "cache weight table launch");
@@ -380,19 +399,19 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
     if (L.coarse_shift > 0) {
         const unsigned cb = (unsigned) ((L.coarse_words + kBlock - 1) / kBlock);
         hipLaunchKernelGGL(k_cache_coarse, dim3(cb), dim3(kBlock), 0, s, bitmap, (int64_t) L.words, (int) L.coarse_shift,
-                           ws_ptr<uint64_t>(c, L.coarse_bitmap), (int64_t) L.coarse_words);
+                           cache_ptr<uint64_t>(c, L.coarse_bitmap, gen), (int64_t) L.coarse_words);
         GNS_HIP_TRY(hipGetLastError(), "coarse bitmap launch");
     }
     if (c->config.flag_mode == GNS_FLAGS_PER_CACHE)
-        GNS_HIP_TRY(launch_flag_all_entries(c, s), "flag all entries");
+        GNS_HIP_TRY(launch_flag_all_entries(c, gen, s), "flag all entries");
     if (c->graph.feat_dim > 0) {
         // fill the device table of cached feature rows (slot order) straight from the full store
-        c->cache_valid = false;   // gather below must not consult the table being written
-        GNS_HIP_TRY(launch_gather(c, x.cache_nodes, (int32_t) C, ws_ptr<float>(c, L.cache_feat), s), "cache feature fill");
+        GNS_HIP_TRY(launch_gather(c, x.cache_nodes, (int32_t) C, cache_ptr<float>(c, L.cache_feat, gen), -1, s), "cache feature fill");
     }
     GNS_HIP_TRY(hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s), "cache readback");
     GNS_HIP_TRY(hipStreamSynchronize(s), "cache sync");
     c->cache_draws = (int64_t) c->h_state->cut_draw + 1;
+    c->cache_gen = gen;
     c->cache_valid = true;
     return GNS_OK;
 }

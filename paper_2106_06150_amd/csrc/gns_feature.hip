@@ -83,7 +83,8 @@ static void gather_dispatch(int lanes, unsigned blocks, hipStream_t s, const Gat
     }
 }
 
-hipError_t launch_gather(gns_ctx* c, const int32_t* nodes, int32_t num_nodes, float* out, hipStream_t s)
+hipError_t launch_gather(gns_ctx* c, const int32_t* nodes, int32_t num_nodes, float* out, int use_cache_gen,
+                         hipStream_t s)
 {
     if (num_nodes == 0) return hipSuccess;
     const Layout& L = c->lay;
@@ -98,10 +99,11 @@ hipError_t launch_gather(gns_ctx* c, const int32_t* nodes, int32_t num_nodes, fl
     a.n = c->graph.num_nodes;
     a.feat_dim = c->graph.feat_dim;
     a.out = out;
-    a.use_cache = (c->uses_cache && c->root->cache_valid) ? 1 : 0;
-    a.cache_bitmap = ws_ptr<uint64_t>(c, L.cache_bitmap);
-    a.cache_prefix = ws_ptr<int32_t>(c, L.cache_prefix);
-    a.cache_feat = ws_ptr<float>(c, L.cache_feat);
+    const int gen = use_cache_gen < 0 ? 0 : use_cache_gen;
+    a.use_cache = (use_cache_gen >= 0 && c->uses_cache && c->root->cache_valid) ? 1 : 0;
+    a.cache_bitmap = cache_ptr<uint64_t>(c, L.cache_bitmap, gen);
+    a.cache_prefix = cache_ptr<int32_t>(c, L.cache_prefix, gen);
+    a.cache_feat = cache_ptr<float>(c, L.cache_feat, gen);
     a.store = c->graph.feat_dev ? c->graph.feat_dev : c->graph.feat_host_pinned;
     const int64_t F = a.feat_dim;
     const bool vec = (F % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.store) & 15u) == 0) &&

@@ -56,6 +56,8 @@ struct Layout {
     size_t sums_rows, sums_words, sums_marks, sums_plan;
     size_t state;
     size_t shared_begin;      // sections at or past this offset are shared with forked contexts
+    size_t cache_block_begin; // first of the two copies of what a cache draw writes (bitmap ... 1/p^C table)
+    size_t cache_block_bytes; // the second copy lies this many bytes further
     size_t total;
     // sizes
     int64_t words;            // ceil(n / 64)
@@ -105,6 +107,17 @@ struct gns_ctx {
     gns::DeviceState* h_state;       // pinned host mirror
     bool uses_cache;
     bool cache_valid;
+    int cache_gen;                   // root only: which copy of the cache block the mini-batches read
+    // Who may still read the copy a draw is about to overwrite: work enqueued before the previous draw.
+    // Every draw records an event on the stream each context of the family last used (all that was
+    // enqueued there so far) and waits, on the device, for the events the previous draw recorded.
+    hipEvent_t gen_event[2];         // alternate from draw to draw
+    bool gen_event_used[2];
+    hipStream_t last_stream;         // where this context last enqueued readers of the cache block
+    bool has_stream;
+    int64_t refresh_count;           // root only
+    gns_ctx* family[64];             // root only: the root itself and its live forks
+    int family_count;
     int64_t cache_draws;
     // cache probability other than Eq. (1): set by gns_cache_walk_probability on the root context
     bool prob_valid;
@@ -117,7 +130,7 @@ struct gns_ctx {
     // The launch sequence of one mini-batch, captured once per (seeds pointer, block buffers) and
     // replayed; only the first kernel's arguments (seed, number of seeds) change between replays.
     hipStream_t cap_stream;          // used for capture only, never for execution
-    gns::BatchGraph bg[2];
+    gns::BatchGraph bg[2][2];        // [hash-map parity][cache generation]
     int hash_parity;                 // which hash map the next mini-batch uses
     uint32_t batch_id;               // id of the last mini-batch enqueued on this context (from 1)
     // argument storage of the first kernel (pointed to by the node's parameter list)
@@ -139,6 +152,23 @@ template <typename T>
 static inline T* ws_ptr(const gns_ctx* c, size_t off)
 {
     return reinterpret_cast<T*>((off >= c->lay.shared_begin ? c->shared_ws : c->ws) + off);
+}
+
+// A section of the cache block in the given generation (off is the section's offset in generation 0).
+template <typename T>
+static inline T* cache_ptr(const gns_ctx* c, size_t off, int gen)
+{
+    return reinterpret_cast<T*>(c->shared_ws + off + (gen ? c->lay.cache_block_bytes : 0));
+}
+
+// The generation the mini-batches enqueued now read.
+static inline int active_gen(const gns_ctx* c) { return c->root->cache_gen; }
+
+// Remembers where this context enqueues the kernels that read the cache block.
+static inline void note_cache_readers(gns_ctx* c, hipStream_t s)
+{
+    c->last_stream = s;
+    c->has_stream = true;
 }
 
 gns_status ctx_fail(gns_ctx* c, gns_status st, const char* what, hipError_t e = hipSuccess);
@@ -179,7 +209,7 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
 // prev_dst / prev_blk: the previous layer, whose relabel shares this layer's first launch (null for layer index 0)
 hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, int32_t* row_eligible,
                                const int32_t* prev_dst, const gns_block* prev_blk, hipStream_t s);
-hipError_t launch_flag_all_entries(gns_ctx* c, hipStream_t s);
+hipError_t launch_flag_all_entries(gns_ctx* c, int cache_gen, hipStream_t s);
 
 // gns_frontier.hip
 hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, uint32_t batch_id,
@@ -192,7 +222,9 @@ hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 
 // gns_feature.hip
-hipError_t launch_gather(gns_ctx* c, const int32_t* nodes, int32_t num_nodes, float* out, hipStream_t s);
+// use_cache_gen < 0: every row comes from the full store (used while a cache's own table is being filled)
+hipError_t launch_gather(gns_ctx* c, const int32_t* nodes, int32_t num_nodes, float* out, int use_cache_gen,
+                         hipStream_t s);
 hipError_t launch_aggregate(gns_ctx* c, const gns_block* blk, const float* x_src, int32_t feat_dim, float* out,
                             hipStream_t s);
 

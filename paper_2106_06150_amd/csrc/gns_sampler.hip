@@ -568,7 +568,7 @@ __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs
 }
 
 static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, int32_t* row_eligible,
-                             SampleArgs* out);
+                             int cache_gen, SampleArgs* out);
 
 static void launch_flag_kernel(gns_ctx* c, const SampleArgs& a, int use_plan, int64_t all_chunks, hipStream_t s)
 {
@@ -583,16 +583,16 @@ static void launch_flag_kernel(gns_ctx* c, const SampleArgs& a, int use_plan, in
 }
 
 // GNS_FLAGS_PER_CACHE: one pass over every aligned chunk of the CSR entry array.
-hipError_t launch_flag_all_entries(gns_ctx* c, hipStream_t s)
+hipError_t launch_flag_all_entries(gns_ctx* c, int cache_gen, hipStream_t s)
 {
     SampleArgs a;
-    fill_sample_args(c, 0, nullptr, nullptr, &a);
+    fill_sample_args(c, 0, nullptr, nullptr, cache_gen, &a);
     launch_flag_kernel(c, a, 0, (c->graph.num_entries + 63) / 64, s);
     return hipGetLastError();
 }
 
 static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, int32_t* row_eligible,
-                             SampleArgs* out)
+                             int cache_gen, SampleArgs* out)
 {
     const Layout& L = c->lay;
     SampleArgs& a = *out;
@@ -608,9 +608,10 @@ static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nod
     a.dst_nodes = dst_nodes;
     a.row_ext = ws_ptr<RowExtent>(c, L.row_ext);
     a.hub_rows = ws_ptr<int32_t>(c, L.hub_rows);
-    a.node_inv_pc = c->uses_cache ? ws_ptr<float>(c, L.node_pc) : nullptr;
-    a.cache_bitmap = ws_ptr<uint64_t>(c, L.cache_bitmap);
-    a.cache_prefix = ws_ptr<int32_t>(c, L.cache_prefix);
+    const int gen = cache_gen;
+    a.node_inv_pc = c->uses_cache ? cache_ptr<float>(c, L.node_pc, gen) : nullptr;
+    a.cache_bitmap = cache_ptr<uint64_t>(c, L.cache_bitmap, gen);
+    a.cache_prefix = cache_ptr<int32_t>(c, L.cache_prefix, gen);
     a.cache_size = c->config.cache_size;
     const int par = layer_index & 1;     // double-buffered: the previous layer's relabel may still read the other half
     a.s_nbr = ws_ptr<int32_t>(c, L.s_nbr[par]);
@@ -626,9 +627,9 @@ static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nod
     a.plan_g0 = ws_ptr<int32_t>(c, L.plan_g0);
     a.plan_sums = ws_ptr<int32_t>(c, L.sums_plan);
     a.plan_desc = ws_ptr<int32_t>(c, L.plan_desc);
-    a.flags = ws_ptr<uint64_t>(c, L.edge_flags);
+    a.flags = c->uses_cache ? cache_ptr<uint64_t>(c, L.edge_flags, gen) : nullptr;
     a.bitmap_words = L.words;
-    a.coarse_bitmap = L.coarse_shift ? ws_ptr<uint64_t>(c, L.coarse_bitmap) : nullptr;
+    a.coarse_bitmap = L.coarse_shift ? cache_ptr<uint64_t>(c, L.coarse_bitmap, gen) : nullptr;
     a.coarse_words = L.coarse_words;
     a.coarse_shift = L.coarse_shift;
 }
@@ -638,7 +639,7 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
 {
     const Layout& L = c->lay;
     SampleArgs a;
-    fill_sample_args(c, layer_index, dst_nodes, row_eligible, &a);
+    fill_sample_args(c, layer_index, dst_nodes, row_eligible, active_gen(c), &a);
 
     // The previous layer's relabel rides in front of this layer's first kernel: both only need
     // that layer's phase 3, and they touch disjoint memory (sampler scratch alternates by layer).

@@ -469,6 +469,57 @@ def test_async_pipeline_on_forked_contexts():
         gns.close()
 
 
+def test_cache_refresh_while_batches_are_in_flight():
+    """A cache draw fills the copy of the cache structures that is not in use: batches enqueued before it
+    (here on two forks, not yet waited for) must come out with the old cache, batches enqueued after it
+    with the new one."""
+    ip, ix = _small(n=6000, avg=20, seed=19)
+    n = ip.numel() - 1
+    F = 16
+    feat = _feat(n, F, seed=6)
+    fanouts, policies, csize, bs = (5, 4), (CF, C), 400, 64
+    gns = GpuGns(ip, ix, feat, fanouts=fanouts, policies=policies, cache_size=csize, max_seeds=bs, flag_mode=1)
+    forks, keep = [], []
+    try:
+        caches = [oracle.sample_cache(ip.numpy(), 77, e, csize) for e in range(3)]
+        compare_cache(gns.sample_cache(77, 0), caches[0])
+        for _ in range(2):
+            ws = torch.empty(B.gns_fork_workspace_bytes(gns.ctx), dtype=torch.uint8, device=gns.device)
+            keep.append(ws)
+            forks.append(B.gns_fork(gns.ctx, ws))
+        streams = [torch.cuda.Stream() for _ in forks]
+        draw_stream = torch.cuda.Stream()
+        bufs = [B.BlockBuffers(gns.graph, gns.config, gns.device) for _ in forks]
+        xin = [torch.zeros((b.array[1].cap_src, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        for epoch in (1, 2):
+            seeds = [synth.uniform_seed_batch(n, bs, 40 + 2 * epoch + i).cuda() for i in range(2)]
+            torch.cuda.synchronize()
+            for i, f in enumerate(forks):                       # enqueued with the cache of epoch - 1
+                B.gns_sample_blocks_async(f, 500 + i, seeds[i], bufs[i].array, streams[i])
+                B.gns_gather_features(f, bufs[i].tensors[1]["src_nodes"], -1, xin[i], streams[i])
+            B.gns_sample_cache(gns.ctx, 77, epoch, draw_stream)   # overlaps them
+            for i, f in enumerate(forks):
+                B.gns_sample_blocks_wait(f, bufs[i].array, streams[i])
+            torch.cuda.synchronize()
+            for i in range(2):
+                ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), caches[epoch - 1][1], csize, 500 + i,
+                                           seeds[i].cpu().numpy(), list(fanouts), list(policies))
+                compare_blocks([bufs[i].views(j) for j in range(2)], ref)
+                x_ref = oracle.gather(feat.numpy(), ref[1].src_nodes)
+                assert xin[i][:ref[1].num_src].cpu().numpy().tobytes() == x_ref.tobytes()
+            nodes_ptr, size, bitmap_ptr, _ = B.gns_cache_view(gns.ctx)
+            assert np.array_equal(B.device_view_i32(nodes_ptr, size, gns.device).cpu().numpy(), caches[epoch][0])
+            # and a batch enqueued now sees the new cache
+            B.gns_sample_blocks(forks[0], 900, seeds[0], bufs[0].array, streams[0])
+            ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), caches[epoch][1], csize, 900, seeds[0].cpu().numpy(),
+                                       list(fanouts), list(policies))
+            compare_blocks([bufs[0].views(j) for j in range(2)], ref)
+    finally:
+        for f in forks:
+            B.gns_destroy(f)
+        gns.close()
+
+
 def test_config3_products_shaped_graph():
     _config_parity(3, batches=2, device_gen="cuda")
 
