@@ -520,6 +520,45 @@ def test_cache_refresh_while_batches_are_in_flight():
         gns.close()
 
 
+def test_host_far_ahead_of_the_device_across_cache_refreshes():
+    """Many mini-batches and several cache draws enqueued without waiting for any of them, the draws on a
+    stream of their own: a draw must not overwrite the copy of the cache structures that batches the device
+    has not reached yet still read (the library makes it wait for them on the device)."""
+    ip, ix = _small(n=8000, avg=24, seed=23)
+    n = ip.numel() - 1
+    F = 32
+    feat = _feat(n, F, seed=9)
+    fanouts, policies, csize, bs = (6, 5), (U, C), 500, 128
+    gns = GpuGns(ip, ix, feat, fanouts=fanouts, policies=policies, cache_size=csize, max_seeds=bs, flag_mode=1)
+    try:
+        work, draws = torch.cuda.Stream(), torch.cuda.Stream()
+        nb, period = 24, 3
+        bufs = [B.BlockBuffers(gns.graph, gns.config, gns.device) for _ in range(nb)]
+        xin = [torch.zeros((b.array[1].cap_src, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        seeds = [synth.uniform_seed_batch(n, bs, 600 + b).cuda() for b in range(nb)]
+        torch.cuda.synchronize()
+        for b in range(nb):
+            if b % period == 0:
+                B.gns_sample_cache(gns.ctx, 55, b // period, draws)
+            B.gns_sample_blocks_async(gns.ctx, 1000 + b, seeds[b], bufs[b].array, work)
+            B.gns_gather_features(gns.ctx, bufs[b].tensors[1]["src_nodes"], -1, xin[b], work)
+        torch.cuda.synchronize()
+        for b in range(nb):
+            bufs[b].array[0].num_dst = 0                      # counts were never waited for: take them from the oracle
+            cache = oracle.sample_cache(ip.numpy(), 55, b // period, csize)
+            ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), cache[1], csize, 1000 + b, seeds[b].cpu().numpy(),
+                                       list(fanouts), list(policies))
+            for j, r in enumerate(ref):
+                t = bufs[b].tensors[j]
+                assert np.array_equal(t["indptr"][:r.num_dst + 1].cpu().numpy(), r.indptr)
+                assert np.array_equal(t["indices"][:r.num_edges].cpu().numpy(), r.indices)
+                assert np.array_equal(t["src_nodes"][:r.num_src].cpu().numpy(), r.src_nodes)
+            x_ref = oracle.gather(feat.numpy(), ref[1].src_nodes)
+            assert xin[b][:ref[1].num_src].cpu().numpy().tobytes() == x_ref.tobytes()
+    finally:
+        gns.close()
+
+
 def test_config3_products_shaped_graph():
     _config_parity(3, batches=2, device_gen="cuda")
 
