@@ -188,6 +188,20 @@ gns_status gns_destroy(gns_ctx* ctx);
  * All calls on a context and its forks are made from one host thread at a time. */
 gns_status gns_sample_cache(gns_ctx* ctx, uint64_t seed, uint64_t epoch, void* hip_stream);
 
+/* The same draw for callers that prepare the next cache while mini-batches of the current one
+ * run (the cache of an epoch depends on (seed, epoch) only).  gns_sample_cache_async enqueues
+ * the whole draw into the copy that is not in use and returns without synchronising; it
+ * enqueues a fixed number of chunks of the stream (8; a typical cache needs one or two, the
+ * rest stand down on the device).  gns_activate_cache makes that copy the current one: from
+ * then on gns_sample_blocks / gns_gather_features read it, and the first such call of every
+ * context makes its stream wait, on the device, for the draw.  gns_sample_cache is the two
+ * calls with a host check in between; after an asynchronous draw that check happens in the
+ * next gns_cache_view (GNS_ECAPACITY if the 8 chunks did not yield cache_size distinct nodes:
+ * the cache is then incomplete and what was sampled from it is not to be used).
+ * GNS_ESTATE if gns_activate_cache finds no draw to make current. */
+gns_status gns_sample_cache_async(gns_ctx* ctx, uint64_t seed, uint64_t epoch, void* hip_stream);
+gns_status gns_activate_cache(gns_ctx* ctx);
+
 /* Read-only views of the current cache (device pointers into the workspace,
  * valid until the next gns_sample_cache): cache_nodes int32[*cache_size]
  * ascending; bitmap uint64[ceil(n/64)], bit (i & 63) of word (i >> 6) set iff

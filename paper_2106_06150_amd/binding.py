@@ -65,6 +65,10 @@ def _load():
     lib.gns_destroy.restype = ctypes.c_int
     lib.gns_sample_cache.argtypes = [vp, u64, u64, vp]
     lib.gns_sample_cache.restype = ctypes.c_int
+    lib.gns_sample_cache_async.argtypes = [vp, u64, u64, vp]
+    lib.gns_sample_cache_async.restype = ctypes.c_int
+    lib.gns_activate_cache.argtypes = [vp]
+    lib.gns_activate_cache.restype = ctypes.c_int
     lib.gns_cache_walk_probability.argtypes = [vp, vp, i64, i32, vp]
     lib.gns_cache_walk_probability.restype = ctypes.c_int
     lib.gns_cache_probability_view.argtypes = [vp, P(vp), P(vp), P(u64), P(i64)]
@@ -97,7 +101,7 @@ lib = _load()
 EXPORTED = ["gns_workspace_bytes", "gns_block_capacity", "gns_create", "gns_destroy", "gns_sample_cache",
             "gns_cache_view", "gns_sample_blocks", "gns_gather_features", "gns_aggregate", "gns_last_error",
             "gns_profile_begin", "gns_profile_collect", "gns_sample_blocks_async", "gns_sample_blocks_wait",
-            "gns_fork", "gns_fork_workspace_bytes", "gns_cache_walk_probability", "gns_cache_probability_view", "gns_sage_dense"]
+            "gns_fork", "gns_fork_workspace_bytes", "gns_cache_walk_probability", "gns_cache_probability_view", "gns_sage_dense", "gns_sample_cache_async", "gns_activate_cache"]
 
 GNS_STAGE_SAMPLE, GNS_STAGE_FINISH, GNS_STAGE_GATHER, GNS_STAGE_AGGREGATE = 0, 8, 16, 17
 GNS_STAGE_DENSE = 21
@@ -197,6 +201,14 @@ def gns_destroy(ctx):
 
 def gns_sample_cache(ctx, seed, epoch, stream=None):
     _check(lib.gns_sample_cache(ctx, seed, epoch, _stream_ptr(stream)), ctx)
+
+
+def gns_sample_cache_async(ctx, seed, epoch, stream=None):
+    _check(lib.gns_sample_cache_async(ctx, seed, epoch, _stream_ptr(stream)), ctx)
+
+
+def gns_activate_cache(ctx):
+    _check(lib.gns_activate_cache(ctx), ctx)
 
 
 def gns_cache_walk_probability(ctx, train_nodes_dev, scale_log2, stream=None):

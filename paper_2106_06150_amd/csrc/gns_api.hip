@@ -208,18 +208,27 @@ static gns_status enqueue_batch(gns_ctx* c, uint64_t seed, const int32_t* seeds_
 static hipError_t events_create(gns_ctx* c)
 {
     c->gen_event[0] = c->gen_event[1] = nullptr;
+    c->ready_event[0] = c->ready_event[1] = nullptr;
+    c->pending = false;
+    c->cache_version = 0;
+    c->seen_version = 0;
     c->gen_event_used[0] = c->gen_event_used[1] = false;
     c->has_stream = false;
     c->last_stream = nullptr;
     hipError_t e = hipEventCreateWithFlags(&c->gen_event[0], hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->gen_event[1], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ready_event[0], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ready_event[1], hipEventDisableTiming);
     return e;
 }
 
 static void events_destroy(gns_ctx* c)
 {
     for (int g = 0; g < 2; ++g)
+    {
         if (c->gen_event[g]) { (void) hipEventDestroy(c->gen_event[g]); c->gen_event[g] = nullptr; }
+        if (c->ready_event[g]) { (void) hipEventDestroy(c->ready_event[g]); c->ready_event[g] = nullptr; }
+    }
 }
 
 static void graph_release(gns_ctx* c, int par, int gen)
@@ -502,6 +511,7 @@ gns_status gns_fork(gns_ctx* parent, void* workspace, size_t workspace_bytes, vo
     c->cap_stream = nullptr;
     c->family_count = 0;
     c->gen_event[0] = c->gen_event[1] = nullptr;
+    c->ready_event[0] = c->ready_event[1] = nullptr;
     if (root->family_count >= (int) (sizeof(root->family) / sizeof(root->family[0]))) {
         delete c;
         return ctx_fail(parent, GNS_ECAPACITY, "too many live forks of one context");
@@ -559,7 +569,29 @@ gns_status gns_sample_cache(gns_ctx* ctx, uint64_t seed, uint64_t epoch, void* h
         if (ctx->config.cache_size > ctx->prob_support)
             return ctx_fail(ctx, GNS_EINVAL, "cache_size exceeds the number of nodes the walk probability reaches");
     }
-    return run_sample_cache(ctx, seed, epoch, static_cast<hipStream_t>(hip_stream));
+    return run_sample_cache(ctx, seed, epoch, true, static_cast<hipStream_t>(hip_stream));
+}
+
+gns_status gns_sample_cache_async(gns_ctx* ctx, uint64_t seed, uint64_t epoch, void* hip_stream)
+{
+    if (!ctx) return GNS_EINVAL;
+    if (!ctx->uses_cache) return ctx_fail(ctx, GNS_ESTATE, "no layer of this config uses the cache");
+    if (ctx->root != ctx) return ctx_fail(ctx, GNS_EINVAL, "draw the cache on the context made by gns_create, not on a fork");
+    if (epoch >> 32) return ctx_fail(ctx, GNS_EINVAL, "epoch must be < 2^32");
+    if (ctx->config.cache_probability == GNS_PROB_WALK) {
+        if (!ctx->prob_valid) return ctx_fail(ctx, GNS_ESTATE, "gns_cache_walk_probability must run before gns_sample_cache");
+        if (ctx->config.cache_size > ctx->prob_support)
+            return ctx_fail(ctx, GNS_EINVAL, "cache_size exceeds the number of nodes the walk probability reaches");
+    }
+    return run_sample_cache(ctx, seed, epoch, false, static_cast<hipStream_t>(hip_stream));
+}
+
+gns_status gns_activate_cache(gns_ctx* ctx)
+{
+    if (!ctx) return GNS_EINVAL;
+    if (ctx->root != ctx) return ctx_fail(ctx, GNS_EINVAL, "activate the cache on the context made by gns_create, not on a fork");
+    if (!ctx->pending) return ctx_fail(ctx, GNS_ESTATE, "no cache draw is waiting to be made current");
+    return activate_cache(ctx);
 }
 
 gns_status gns_cache_walk_probability(gns_ctx* ctx, const int32_t* train_nodes_dev, int64_t num_train,
@@ -596,6 +628,10 @@ gns_status gns_cache_view(gns_ctx* ctx, const int32_t** cache_nodes, int64_t* ca
     if (cache_nodes) *cache_nodes = cache_ptr<int32_t>(ctx, ctx->lay.cache_nodes, active_gen(ctx));
     if (cache_size) *cache_size = ctx->config.cache_size;
     if (bitmap) *bitmap = cache_ptr<uint64_t>(ctx, ctx->lay.cache_bitmap, active_gen(ctx));
+    if (ctx->root->cache_draws < 0) {                     // drawn asynchronously: look at the outcome now
+        const gns_status st = finish_pending_draw(ctx->root);
+        if (st != GNS_OK) { snprintf(ctx->err, sizeof(ctx->err), "%s", ctx->root->err); return st; }
+    }
     if (num_draws) *num_draws = ctx->root->cache_draws;
     return GNS_OK;
 }
@@ -621,11 +657,11 @@ gns_status gns_sample_blocks_async(gns_ctx* ctx, uint64_t seed, const int32_t* s
         }
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (before_cache_readers(c, s) != hipSuccess) return ctx_fail(c, GNS_EHIP, "wait for the cache draw");
     gns_status st = GNS_OK;
     if (c->prof_mask == 0 && c->cap_stream) st = launch_batch_graph(c, seed, seeds_dev, num_seeds, blocks, s);
     else                                     st = enqueue_batch(c, seed, seeds_dev, num_seeds, blocks, s);
     if (st != GNS_OK) return st;
-    note_cache_readers(c, s);
     c->batch_id += 1;
     c->hash_parity ^= 1;             // this batch has left the other map empty
     for (int i = 0; i < nl; ++i) {
@@ -669,9 +705,10 @@ gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t n
     if (ctx->graph.feat_dim <= 0) return ctx_fail(ctx, GNS_ESTATE, "the graph was created without features");
     if (num_nodes == 0) return GNS_OK;
     if (!nodes_dev || !out_dev) return ctx_fail(ctx, GNS_EINVAL, "null nodes or output");
+    if (before_cache_readers(ctx, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return ctx_fail(ctx, GNS_EHIP, "wait for the cache draw");
     StageTimer t(ctx, GNS_STAGE_GATHER, static_cast<hipStream_t>(hip_stream));
     hipError_t e = launch_gather(ctx, nodes_dev, num_nodes, out_dev, active_gen(ctx), static_cast<hipStream_t>(hip_stream));
-    note_cache_readers(ctx, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "gather launch", e);
     return GNS_OK;
 }

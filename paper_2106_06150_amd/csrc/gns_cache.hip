@@ -80,9 +80,28 @@ struct DrawArgs {
     int32_t* sums;             // [tiles + 1]
     int32_t tiles;
     uint64_t* cache_bitmap;
-    int32_t limit;             // commit: number of first occurrences of this chunk that enter the cache
-    int32_t is_final;
+    int64_t cache_size;
+    int32_t chunk_index;       // chunks of one draw are numbered from 0
 };
+
+// A draw enqueues its chunks without knowing how many it needs: the chunk that completes the cache says
+// so in the device state and every later chunk stands down.
+__device__ __forceinline__ bool chunk_stands_down(const DrawArgs& a)
+{
+    const int32_t done = a.st->draw_done_chunk;
+    return done >= 0 && done < a.chunk_index;
+}
+
+__global__ void k_cache_draw_reset(DeviceState* st)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        st->draw_distinct = 0;
+        st->draw_done_chunk = -1;
+        st->chunk_distinct = 0;
+        st->chunk_limit = 0;
+        st->chunk_final = 0;
+    }
+}
 
 // the unique row i with indptr[i] <= e < indptr[i+1]
 template <typename OffT>
@@ -100,7 +119,7 @@ template <typename OffT>
 __global__ void __launch_bounds__(kBlock) k_cache_draw(DrawArgs a)
 {
     const int32_t t = (int32_t) (blockIdx.x * blockDim.x + threadIdx.x);
-    if (t >= a.count) return;
+    if (t >= a.count || chunk_stands_down(a)) return;
     const uint64_t j = a.j0 + (uint64_t) t;
     const Philox4 r = philox4x32_10((uint32_t) j, (uint32_t) (j >> 32), a.epoch, kTagCache, a.key0, a.key1);
     const uint64_t r64 = ((uint64_t) r.w[1] << 32) | (uint64_t) r.w[0];
@@ -126,6 +145,7 @@ __device__ __forceinline__ int32_t is_first_occurrence(const DrawArgs& a, int32_
 __global__ void __launch_bounds__(kBlock) k_cache_flags_phase1(DrawArgs a)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
+    if (chunk_stands_down(a)) return;
     const int32_t base = (int32_t) blockIdx.x * kTile;
     int32_t sum = 0;
 #pragma unroll
@@ -137,6 +157,7 @@ __global__ void __launch_bounds__(kBlock) k_cache_flags_phase1(DrawArgs a)
 __global__ void __launch_bounds__(kBlock) k_cache_flags_phase2(DrawArgs a)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
+    if (chunk_stands_down(a)) return;
     int32_t carry = 0;
     for (int32_t base = 0; base < a.tiles; base += kBlock) {
         const int32_t i = base + (int32_t) threadIdx.x;
@@ -146,12 +167,24 @@ __global__ void __launch_bounds__(kBlock) k_cache_flags_phase2(DrawArgs a)
         if (i < a.tiles) a.sums[i] = carry + ex;
         carry += total;
     }
-    if (threadIdx.x == 0) a.st->chunk_distinct = carry;
+    if (threadIdx.x == 0) {
+        // how many of this chunk's first occurrences the cache still takes, and whether that completes it
+        const int64_t need = a.cache_size - (int64_t) a.st->draw_distinct;
+        const int32_t limit = (int32_t) ((int64_t) carry < need ? (int64_t) carry : need);
+        const int32_t final = (int64_t) carry >= need ? 1 : 0;
+        a.st->chunk_distinct = carry;
+        a.st->chunk_limit = limit;
+        a.st->chunk_final = final;
+        a.st->draw_distinct += limit;
+        if (final) a.st->draw_done_chunk = a.chunk_index;
+    }
 }
 
 __global__ void __launch_bounds__(kBlock) k_cache_commit(DrawArgs a)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
+    if (chunk_stands_down(a)) return;
+    const int32_t limit = a.st->chunk_limit, is_final = a.st->chunk_final;
     const int32_t base = (int32_t) blockIdx.x * kTile;
     const int32_t t0 = base + (int32_t) threadIdx.x * kItems;
     int32_t f[kItems];
@@ -163,10 +196,10 @@ __global__ void __launch_bounds__(kBlock) k_cache_commit(DrawArgs a)
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         if (f[i]) {
-            if (g < a.limit) {
+            if (g < limit) {
                 const uint32_t node = (uint32_t) a.draw_node[t0 + i];
                 atomicOr(reinterpret_cast<unsigned long long*>(&a.cache_bitmap[node >> 6]), 1ull << (node & 63u));
-                if (a.is_final && g == a.limit - 1) a.st->cut_draw = a.j0 + (uint64_t) (t0 + i);
+                if (is_final && g == limit - 1) a.st->cut_draw = a.j0 + (uint64_t) (t0 + i);
             }
             ++g;
         }
@@ -290,32 +323,65 @@ static gns_status fail(gns_ctx* c, gns_status st, const char* what, hipError_t e
         if (e__ != hipSuccess) return fail(c, GNS_EHIP, what, e__);    \
     } while (0)
 
-gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream_t s)
+constexpr int kAsyncChunks = 8;     // chunks an asynchronous draw enqueues (a typical cache needs one or two)
+
+// Records, on the stream every context of the family last used, the end of what may still read the copy
+// of the cache block that stops being current now.
+static gns_status mark_last_readers(gns_ctx* c, int old_gen)
+{
+    for (int i = 0; i < c->family_count; ++i) {
+        gns_ctx* m = c->family[i];
+        if (!m->has_stream) continue;
+        GNS_HIP_TRY(hipEventRecord(m->gen_event[old_gen], m->last_stream), "event record");
+        m->gen_event_used[old_gen] = true;
+    }
+    return GNS_OK;
+}
+
+// Makes the copy a finished or enqueued draw filled the current one.
+gns_status activate_cache(gns_ctx* c)
+{
+    if (c->cache_valid) {
+        const gns_status st = mark_last_readers(c, c->cache_gen);
+        if (st != GNS_OK) return st;
+    }
+    c->cache_gen = c->pending_gen;
+    c->cache_valid = true;
+    c->pending = false;
+    c->cache_version += 1;
+    return GNS_OK;
+}
+
+// Reads the outcome of the last draw back (synchronises behind it).
+gns_status finish_pending_draw(gns_ctx* c)
+{
+    const int gen = c->pending ? c->pending_gen : c->cache_gen;
+    GNS_HIP_TRY(hipEventSynchronize(c->ready_event[gen]), "cache draw wait");
+    GNS_HIP_TRY(hipMemcpy(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost), "cache readback");
+    if (c->h_state->draw_done_chunk < 0)
+        return fail(c, GNS_ECAPACITY, "cache draw: the stream did not yield cache_size distinct nodes within the chunks an asynchronous draw enqueues", hipSuccess);
+    c->cache_draws = (int64_t) c->h_state->cut_draw + 1;
+    return GNS_OK;
+}
+
+gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, bool wait_for_it, hipStream_t s)
 {
     const Layout& L = c->lay;
     const int64_t C = c->config.cache_size;
-    // The draw fills the generation the mini-batches are not reading and becomes the active one when it is
-    // complete: batches enqueued before this call keep their cache.
+    // The draw fills the copy of the cache block the mini-batches are not reading.  Whatever was enqueued
+    // while that copy was the current one ended with the events recorded when it stopped being current:
+    // the device may not have reached all of it yet if the host runs far ahead, so the draw waits for them.
     const int gen = c->cache_valid ? (c->cache_gen ^ 1) : 0;
     uint64_t* bitmap = cache_ptr<uint64_t>(c, L.cache_bitmap, gen);
-    // That copy was read by the work enqueued before the previous draw (on any context of the family); the
-    // device may not have reached all of it yet if the host runs far ahead.  The previous draw recorded an
-    // event behind it on every context's stream: wait for those, then record the events the next draw needs.
-    {
-        const int par = (int) (c->refresh_count & 1);
-        for (int i = 0; i < c->family_count; ++i) {
-            gns_ctx* m = c->family[i];
-            if (m->gen_event_used[par ^ 1]) {
-                GNS_HIP_TRY(hipStreamWaitEvent(s, m->gen_event[par ^ 1], 0), "wait for the readers of the old cache");
-                m->gen_event_used[par ^ 1] = false;
-            }
-            if (m->has_stream) {
-                GNS_HIP_TRY(hipEventRecord(m->gen_event[par], m->last_stream), "event record");
-                m->gen_event_used[par] = true;
-            }
-        }
-        c->refresh_count += 1;
+    if (c->pending)                                  // a draw that was never made current: this one replaces it
+        GNS_HIP_TRY(hipStreamWaitEvent(s, c->ready_event[c->pending_gen], 0), "wait for the replaced draw");
+    for (int i = 0; i < c->family_count; ++i) {
+        gns_ctx* m = c->family[i];
+        if (!m->gen_event_used[gen]) continue;
+        GNS_HIP_TRY(hipStreamWaitEvent(s, m->gen_event[gen], 0), "wait for the readers of the old cache");
+        m->gen_event_used[gen] = false;
     }
+    hipLaunchKernelGGL(k_cache_draw_reset, dim3(1), dim3(kWave), 0, s, c->d_state);
     GNS_HIP_TRY(launch_fill_u64(reinterpret_cast<unsigned long long*>(bitmap), (size_t) L.words, 0ull, s), "clear cache bitmap");
     GNS_HIP_TRY(launch_fill_u32(ws_ptr<uint32_t>(c, L.draw_keys), L.draw_hash_cap, 0xFFFFFFFFu, s), "clear draw keys");
     GNS_HIP_TRY(launch_fill_u32(ws_ptr<uint32_t>(c, L.draw_vals), L.draw_hash_cap, 0xFFFFFFFFu, s), "clear draw vals");
@@ -341,40 +407,40 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
     a.draw_slot = ws_ptr<int32_t>(c, L.draw_slot);
     a.sums = ws_ptr<int32_t>(c, L.sums_words);      // sized for max(word tiles, draw tiles)
     a.cache_bitmap = bitmap;
+    a.cache_size = C;
 
     // The draw hash holds every distinct node seen so far: fewer than |C| before the final
     // chunk plus at most one chunk's worth, which is what it was sized for.  Stream indices
-    // are kept in 32 bits; a cache that needs more draws than the limit is refused.
+    // are kept in 32 bits; a cache that needs more draws than the limit is refused.  How many of a
+    // chunk's first occurrences enter the cache, and whether they complete it, is decided on the device
+    // (k_cache_flags_phase2); the host only needs to know when to stop enqueuing chunks.
     uint64_t draw_limit = 256ull * (uint64_t) C + 64ull * (uint64_t) L.draw_chunk;
     if (draw_limit > 0xFFFFFFFFull) draw_limit = 0xFFFFFFFFull;
-    uint64_t j0 = 0;
-    int64_t distinct = 0;
     const bool i64 = walk || c->graph.indptr_is_i64 != 0;
-    while (distinct < C) {
-        const int64_t count = L.draw_chunk;
-        if (j0 + (uint64_t) count > draw_limit)
+    const int64_t count = L.draw_chunk;
+    a.count = (int32_t) count;
+    a.tiles = (int32_t) ((count + kTile - 1) / kTile);
+    const unsigned draw_blocks = (unsigned) ((count + kBlock - 1) / kBlock);
+    for (int chunk = 0;; ++chunk) {
+        const uint64_t j0 = (uint64_t) chunk * (uint64_t) count;
+        if (j0 + (uint64_t) count > draw_limit) {
+            if (!wait_for_it) break;
             return fail(c, GNS_ECAPACITY, "cache draw: the stream did not yield cache_size distinct nodes within the draw limit (cache_size too close to the number of nodes with neighbors)", hipSuccess);
+        }
+        if (!wait_for_it && chunk >= kAsyncChunks) break;
         a.j0 = j0;
-        a.count = (int32_t) count;
-        a.tiles = (int32_t) ((count + kTile - 1) / kTile);
-        a.limit = 0;
-        a.is_final = 0;
-        const unsigned draw_blocks = (unsigned) ((count + kBlock - 1) / kBlock);
+        a.chunk_index = chunk;
         if (i64) hipLaunchKernelGGL((k_cache_draw<int64_t>), dim3(draw_blocks), dim3(kBlock), 0, s, a);
         else     hipLaunchKernelGGL((k_cache_draw<int32_t>), dim3(draw_blocks), dim3(kBlock), 0, s, a);
         hipLaunchKernelGGL(k_cache_flags_phase1, dim3((unsigned) a.tiles), dim3(kBlock), 0, s, a);
         hipLaunchKernelGGL(k_cache_flags_phase2, dim3(1), dim3(kBlock), 0, s, a);
-        GNS_HIP_TRY(hipGetLastError(), "cache draw launch");
-        GNS_HIP_TRY(hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s), "cache draw readback");
-        GNS_HIP_TRY(hipStreamSynchronize(s), "cache draw sync");
-        const int64_t found = c->h_state->chunk_distinct;
-        const int64_t need = C - distinct;
-        a.limit = (int32_t) (found < need ? found : need);
-        a.is_final = (found >= need) ? 1 : 0;
         hipLaunchKernelGGL(k_cache_commit, dim3((unsigned) a.tiles), dim3(kBlock), 0, s, a);
-        GNS_HIP_TRY(hipGetLastError(), "cache commit launch");
-        distinct += a.limit;
-        j0 += (uint64_t) count;
+        GNS_HIP_TRY(hipGetLastError(), "cache draw launch");
+        if (wait_for_it) {
+            GNS_HIP_TRY(hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s), "cache draw readback");
+            GNS_HIP_TRY(hipStreamSynchronize(s), "cache draw sync");
+            if (c->h_state->draw_done_chunk >= 0) break;
+        }
     }
 
     IndexArgs x;
@@ -408,12 +474,14 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream
         // fill the device table of cached feature rows (slot order) straight from the full store
         GNS_HIP_TRY(launch_gather(c, x.cache_nodes, (int32_t) C, cache_ptr<float>(c, L.cache_feat, gen), -1, s), "cache feature fill");
     }
-    GNS_HIP_TRY(hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s), "cache readback");
-    GNS_HIP_TRY(hipStreamSynchronize(s), "cache sync");
-    c->cache_draws = (int64_t) c->h_state->cut_draw + 1;
-    c->cache_gen = gen;
-    c->cache_valid = true;
-    return GNS_OK;
+    GNS_HIP_TRY(hipEventRecord(c->ready_event[gen], s), "event record");
+    c->pending = true;
+    c->pending_gen = gen;
+    c->cache_draws = -1;                           // read back on demand
+    if (!wait_for_it) return GNS_OK;
+    const gns_status st = finish_pending_draw(c);
+    if (st != GNS_OK) { c->pending = false; return st; }
+    return activate_cache(c);
 }
 
 }  // namespace gns

@@ -19,6 +19,10 @@ struct DeviceState {
     int32_t map_nodes[2];                 // entries of each of the two hash maps (what its next clear has to undo)
     int32_t hub_count;                    // entries of the batch's hub-row list (reset by the batch's last kernel)
     int32_t chunk_distinct;               // cache draw: first occurrences found in the current chunk
+    int32_t chunk_limit;                  //   how many of them enter the cache
+    int32_t chunk_final;                  //   1 if they complete it
+    int32_t draw_distinct;                //   nodes in the cache before the current chunk
+    int32_t draw_done_chunk;              //   index of the chunk that completed the cache, -1 while incomplete
     int32_t plan_chunks;                  // CACHE_ONLY sampler: aligned chunks in the current work list
     unsigned long long cut_draw;          // cache draw: stream index of the draw that completed the cache
     unsigned long long walk_total;        // random-walk probability: sum of the weights
@@ -116,6 +120,12 @@ struct gns_ctx {
     hipStream_t last_stream;         // where this context last enqueued readers of the cache block
     bool has_stream;
     int64_t refresh_count;           // root only
+    // root only: a draw enqueued by gns_sample_cache_async and not yet made current
+    bool pending;
+    int pending_gen;
+    hipEvent_t ready_event[2];       // recorded behind the draw that filled the copy
+    uint64_t cache_version;          // bumped when a copy becomes current
+    uint64_t seen_version;           // per context: the version its stream has been made to wait for
     gns_ctx* family[64];             // root only: the root itself and its live forks
     int family_count;
     int64_t cache_draws;
@@ -164,11 +174,16 @@ static inline T* cache_ptr(const gns_ctx* c, size_t off, int gen)
 // The generation the mini-batches enqueued now read.
 static inline int active_gen(const gns_ctx* c) { return c->root->cache_gen; }
 
-// Remembers where this context enqueues the kernels that read the cache block.
-static inline void note_cache_readers(gns_ctx* c, hipStream_t s)
+// Called before a context enqueues kernels that read the cache block on stream s: remembers the stream and,
+// the first time after another copy became current, makes the stream wait for the draw that filled it.
+static inline hipError_t before_cache_readers(gns_ctx* c, hipStream_t s)
 {
     c->last_stream = s;
     c->has_stream = true;
+    gns_ctx* root = c->root;
+    if (!c->uses_cache || !root->cache_valid || c->seen_version == root->cache_version) return hipSuccess;
+    c->seen_version = root->cache_version;
+    return hipStreamWaitEvent(s, root->ready_event[root->cache_gen], 0);
 }
 
 gns_status ctx_fail(gns_ctx* c, gns_status st, const char* what, hipError_t e = hipSuccess);
@@ -203,7 +218,11 @@ gns_status run_walk_probability(gns_ctx* c, const int32_t* train_nodes, int64_t 
 
 // gns_cache.hip
 hipError_t launch_count_nonzero_rows(gns_ctx* c, hipStream_t s, int32_t* d_out);
-gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, hipStream_t s);
+// wait_for_it: run the chunk loop with a read-back per chunk and synchronise (exact error reporting); otherwise
+// enqueue a fixed number of chunks (later ones stand down once the cache is complete) and return.
+gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, bool wait_for_it, hipStream_t s);
+gns_status activate_cache(gns_ctx* c);
+gns_status finish_pending_draw(gns_ctx* c);
 
 // gns_sampler.hip
 // prev_dst / prev_blk: the previous layer, whose relabel shares this layer's first launch (null for layer index 0)

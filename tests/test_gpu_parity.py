@@ -520,6 +520,56 @@ def test_cache_refresh_while_batches_are_in_flight():
         gns.close()
 
 
+def test_cache_prepared_ahead_and_activated_later():
+    """gns_sample_cache_async fills the copy of the cache structures that is not in use while batches of the
+    current cache run; gns_activate_cache switches over.  Nothing here synchronises between the draws, the
+    activations and the batches; every batch must match the oracle for the cache of its own period."""
+    ip, ix = _small(n=7000, avg=22, seed=29)
+    n = ip.numel() - 1
+    F = 16
+    feat = _feat(n, F, seed=4)
+    fanouts, policies, csize, bs = (5, 4), (CF, C), 450, 96
+    gns = GpuGns(ip, ix, feat, fanouts=fanouts, policies=policies, cache_size=csize, max_seeds=bs, flag_mode=1)
+    try:
+        work, draws = torch.cuda.Stream(), torch.cuda.Stream()
+        periods, per = 4, 3
+        nb = periods * per
+        bufs = [B.BlockBuffers(gns.graph, gns.config, gns.device) for _ in range(nb)]
+        xin = [torch.zeros((b.array[1].cap_src, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        seeds = [synth.uniform_seed_batch(n, bs, 800 + b).cuda() for b in range(nb)]
+        with pytest.raises(B.GnsError) as err:                     # nothing drawn yet
+            B.gns_activate_cache(gns.ctx)
+        assert err.value.status == B.GNS_ESTATE
+        torch.cuda.synchronize()
+        B.gns_sample_cache_async(gns.ctx, 66, 0, draws)
+        for b in range(nb):
+            if b % per == 0:
+                B.gns_activate_cache(gns.ctx)                      # the cache of period b // per, drawn one period ago
+                if b // per + 1 < periods:
+                    B.gns_sample_cache_async(gns.ctx, 66, b // per + 1, draws)
+            B.gns_sample_blocks_async(gns.ctx, 2000 + b, seeds[b], bufs[b].array, work)
+            B.gns_gather_features(gns.ctx, bufs[b].tensors[1]["src_nodes"], -1, xin[b], work)
+        torch.cuda.synchronize()
+        for b in range(nb):
+            cache = oracle.sample_cache(ip.numpy(), 66, b // per, csize)
+            ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), cache[1], csize, 2000 + b, seeds[b].cpu().numpy(),
+                                       list(fanouts), list(policies))
+            for j, r in enumerate(ref):
+                t = bufs[b].tensors[j]
+                assert np.array_equal(t["indptr"][:r.num_dst + 1].cpu().numpy(), r.indptr)
+                assert np.array_equal(t["indices"][:r.num_edges].cpu().numpy(), r.indices)
+                assert np.array_equal(t["src_nodes"][:r.num_src].cpu().numpy(), r.src_nodes)
+                gw = t["weights"][:r.num_edges].cpu().numpy().astype(np.float64)
+                assert np.all(np.abs(gw - r.weights) <= 1e-5 * np.abs(r.weights))
+            x_ref = oracle.gather(feat.numpy(), ref[1].src_nodes)
+            assert xin[b][:ref[1].num_src].cpu().numpy().tobytes() == x_ref.tobytes()
+        last = oracle.sample_cache(ip.numpy(), 66, periods - 1, csize)
+        nodes_ptr, size, _, num_draws = B.gns_cache_view(gns.ctx)   # reads the asynchronous draw's outcome back
+        assert np.array_equal(B.device_view_i32(nodes_ptr, size, gns.device).cpu().numpy(), last[0]) and num_draws == last[2]
+    finally:
+        gns.close()
+
+
 def test_host_far_ahead_of_the_device_across_cache_refreshes():
     """Many mini-batches and several cache draws enqueued without waiting for any of them, the draws on a
     stream of their own: a draw must not overwrite the copy of the cache structures that batches the device
