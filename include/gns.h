@@ -152,7 +152,10 @@ gns_status gns_block_capacity(const gns_graph* graph, const gns_config* config, 
  * gns_workspace_bytes bytes, 256-byte aligned, borrowed until gns_destroy.
  * Validates the arguments (GNS_EINVAL), e.g. cache_size must not exceed the
  * number of nodes with at least one neighbor when a cache policy is used.
- * Initialises the workspace on `hip_stream` and synchronises it. */
+ * Initialises the workspace on `hip_stream` and synchronises it.
+ * A mini-batch's launch sequence is captured into a HIP graph on first use and replayed afterwards;
+ * with the environment variable GNS_NO_GRAPH set when the context is created (forks inherit it) every
+ * kernel is launched on its own instead. */
 gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_config* config,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
