@@ -21,8 +21,13 @@
  *  - Every pointer is a DEVICE pointer unless its name starts with host_ or it
  *    is documented as a host pointer (struct pointers, out-parameters).
  *  - The caller owns every buffer, including the workspace; the library
- *    borrows them for the lifetime of the context and never frees them.  After
- *    gns_create the library performs no device allocation.
+ *    borrows them for the lifetime of the context and never frees them.  All
+ *    device memory the kernels touch is the caller's.  What the
+ *    library itself allocates is host-side or runtime state: gns_create and
+ *    gns_fork allocate a small pinned host mirror of the device counters, HIP
+ *    events and a capture stream; the first mini-batch with a new set of block
+ *    buffers instantiates a HIP graph of its launch sequence; gns_profile_begin
+ *    creates HIP events.  Everything is released by gns_destroy.
  *  - All device work is enqueued on the hipStream_t passed as `hip_stream`
  *    (NULL = the default stream).  Calls that must report counts to the host
  *    (gns_sample_cache, gns_sample_blocks) synchronise that stream before
@@ -185,9 +190,10 @@ gns_status gns_destroy(gns_ctx* ctx);
  * before the call (on this context or on forks, on other streams) may still be in flight:
  * they keep reading the cache they were enqueued with; mini-batches enqueued after the call
  * returns read the new one.  The draw after this one overwrites the copy those older
- * mini-batches read; it waits on the device for them (every draw records an event on the
- * stream each context last used, the next draw waits for it), so the host may run ahead freely
- * as long as each context keeps to one stream between two draws.
+ * mini-batches read; it waits on the device for them (every draw records an event on each
+ * stream each context enqueued mini-batches on since the previous draw, the next draw waits for
+ * them), so the host may run ahead freely.  A context may use up to 4 different streams between
+ * two draws; gns_sample_blocks(_async) and gns_gather_features return GNS_ESTATE for a fifth.
  * All calls on a context and its forks are made from one host thread at a time. */
 gns_status gns_sample_cache(gns_ctx* ctx, uint64_t seed, uint64_t epoch, void* hip_stream);
 
@@ -221,7 +227,9 @@ gns_status gns_cache_view(gns_ctx* ctx, const int32_t** cache_nodes, int64_t* ca
  * node whose prefix interval holds it, and Section 3.4 uses p_u = weight_u / total.
  * GNS_ECAPACITY if a row sum, a product or the total reaches 2^62 (lower scale_log2);
  * GNS_EINVAL for a node id outside [0, n) or an all-zero result.  Synchronises the stream.
- * Call it on the context made by gns_create; it invalidates the current cache. */
+ * Call it on the context made by gns_create; it invalidates the current cache: mini-batches
+ * already enqueued keep the cache they were enqueued with (the next draw fills the other copy of
+ * the cache structures), new ones need a new gns_sample_cache.  No cache draw may be in flight. */
 gns_status gns_cache_walk_probability(gns_ctx* ctx, const int32_t* train_nodes_dev, int64_t num_train,
                                       int32_t scale_log2, void* hip_stream);
 
@@ -250,7 +258,8 @@ gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_d
  * gns_sample_blocks_wait the blocks' host counts hold the placeholder
  * GNS_DEVICE_COUNTS(layer_index), which gns_aggregate understands (see there).
  * gns_sample_blocks_wait copies the counts to the host, synchronises the stream, fills
- * them in and reports GNS_EINVAL for bad seeds.  gns_sample_blocks is exactly async followed by wait.
+ * them in and reports GNS_EINVAL if any mini-batch enqueued on the context since the previous
+ * wait had a bad seed (not only the last one).  gns_sample_blocks is exactly async followed by wait.
  * Between the two calls no other call may use the context's block state except
  * gns_gather_features / gns_aggregate on the same stream. */
 #define GNS_DEVICE_COUNTS(layer_index) (-1 - (layer_index))

@@ -76,6 +76,8 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
         if (L.edges[i] >= (int64_t) 1 << 31) GNS_BAD("a layer's worst-case edge count exceeds 2^31");
     }
     L.row_tiles = (L.max_rows + kTile - 1) / kTile;
+    // the batch hash map addresses its slots with 32 bits at a load factor of at most 1/2
+    if (2 * (uint64_t) L.rows[cfg->num_layers] > (uint64_t) 1 << 31) GNS_BAD("worst-case frontier too large for the batch hash map (more than 2^30 nodes)");
     L.hash_cap = pow2_at_least(2 * (uint64_t) L.rows[cfg->num_layers]);
 
     L.draw_chunk = C;
@@ -207,16 +209,17 @@ static gns_status enqueue_batch(gns_ctx* c, uint64_t seed, const int32_t* seeds_
 
 static hipError_t events_create(gns_ctx* c)
 {
-    c->gen_event[0] = c->gen_event[1] = nullptr;
+    memset(c->gen_event, 0, sizeof(c->gen_event));
     c->ready_event[0] = c->ready_event[1] = nullptr;
     c->pending = false;
     c->cache_version = 0;
     c->seen_version = 0;
-    c->gen_event_used[0] = c->gen_event_used[1] = false;
-    c->has_stream = false;
-    c->last_stream = nullptr;
-    hipError_t e = hipEventCreateWithFlags(&c->gen_event[0], hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->gen_event[1], hipEventDisableTiming);
+    c->gen_event_used[0] = c->gen_event_used[1] = 0;
+    c->reader_stream_count = 0;
+    hipError_t e = hipSuccess;
+    for (int g = 0; g < 2; ++g)
+        for (int i = 0; i < kReaderStreams && e == hipSuccess; ++i)
+            e = hipEventCreateWithFlags(&c->gen_event[g][i], hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ready_event[0], hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ready_event[1], hipEventDisableTiming);
     return e;
@@ -226,7 +229,8 @@ static void events_destroy(gns_ctx* c)
 {
     for (int g = 0; g < 2; ++g)
     {
-        if (c->gen_event[g]) { (void) hipEventDestroy(c->gen_event[g]); c->gen_event[g] = nullptr; }
+        for (int i = 0; i < kReaderStreams; ++i)
+            if (c->gen_event[g][i]) { (void) hipEventDestroy(c->gen_event[g][i]); c->gen_event[g][i] = nullptr; }
         if (c->ready_event[g]) { (void) hipEventDestroy(c->ready_event[g]); c->ready_event[g] = nullptr; }
     }
 }
@@ -508,9 +512,10 @@ gns_status gns_fork(gns_ctx* parent, void* workspace, size_t workspace_bytes, vo
     memset(c->bg, 0, sizeof(c->bg));
     c->hash_parity = 0;
     c->batch_id = 0;
+    c->bad_reported = 0;
     c->cap_stream = nullptr;
     c->family_count = 0;
-    c->gen_event[0] = c->gen_event[1] = nullptr;
+    memset(c->gen_event, 0, sizeof(c->gen_event));
     c->ready_event[0] = c->ready_event[1] = nullptr;
     if (root->family_count >= (int) (sizeof(root->family) / sizeof(root->family[0]))) {
         delete c;
@@ -603,7 +608,13 @@ gns_status gns_cache_walk_probability(gns_ctx* ctx, const int32_t* train_nodes_d
         return ctx_fail(ctx, GNS_ESTATE, "the config does not ask for GNS_PROB_WALK");
     if (!train_nodes_dev || num_train < 1) return ctx_fail(ctx, GNS_EINVAL, "no training nodes");
     if (scale_log2 < 0 || scale_log2 > 40) return ctx_fail(ctx, GNS_EINVAL, "scale_log2 must be in [0, 40]");
-    ctx->cache_valid = false;
+    // Mini-batches still in flight keep reading the current copy of the cache structures: record where they
+    // end, as a draw does when it replaces a cache, so that the draw after next does not overwrite that copy
+    // under them; the next draw goes into the other copy.
+    if (ctx->cache_valid) {
+        const gns_status st = retire_cache(ctx);
+        if (st != GNS_OK) return st;
+    }
     return run_walk_probability(ctx, train_nodes_dev, num_train, scale_log2, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -657,7 +668,11 @@ gns_status gns_sample_blocks_async(gns_ctx* ctx, uint64_t seed, const int32_t* s
         }
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    if (before_cache_readers(c, s) != hipSuccess) return ctx_fail(c, GNS_EHIP, "wait for the cache draw");
+    {
+        const hipError_t er = before_cache_readers(c, s);
+        if (er == hipErrorInvalidValue) return ctx_fail(c, GNS_ESTATE, "a context may use at most 4 streams between two cache draws");
+        if (er != hipSuccess) return ctx_fail(c, GNS_EHIP, "wait for the cache draw", er);
+    }
     gns_status st = GNS_OK;
     if (c->prof_mask == 0 && c->cap_stream) st = launch_batch_graph(c, seed, seeds_dev, num_seeds, blocks, s);
     else                                     st = enqueue_batch(c, seed, seeds_dev, num_seeds, blocks, s);
@@ -686,7 +701,12 @@ gns_status gns_sample_blocks_wait(gns_ctx* ctx, gns_block* blocks, void* hip_str
         blocks[i].num_src = c->h_state->num_dst[i + 1];
         blocks[i].num_edges = c->h_state->num_edges[i];
     }
-    if (c->batch_id != 0 && c->h_state->bad_seed == c->batch_id) return ctx_fail(c, GNS_EINVAL, "seeds must be distinct node ids in [0, num_nodes)");
+    // bad_seed holds the id of the latest mini-batch that had a bad seed: anything newer than the last one
+    // reported means that a batch enqueued since the previous wait (not necessarily the last one) was bad
+    if (c->h_state->bad_seed != c->bad_reported) {
+        c->bad_reported = c->h_state->bad_seed;
+        return ctx_fail(c, GNS_EINVAL, "seeds must be distinct node ids in [0, num_nodes) (a mini-batch enqueued since the last wait had a bad seed)");
+    }
     return GNS_OK;
 }
 
@@ -705,8 +725,11 @@ gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t n
     if (ctx->graph.feat_dim <= 0) return ctx_fail(ctx, GNS_ESTATE, "the graph was created without features");
     if (num_nodes == 0) return GNS_OK;
     if (!nodes_dev || !out_dev) return ctx_fail(ctx, GNS_EINVAL, "null nodes or output");
-    if (before_cache_readers(ctx, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
-        return ctx_fail(ctx, GNS_EHIP, "wait for the cache draw");
+    {
+        const hipError_t er = before_cache_readers(ctx, static_cast<hipStream_t>(hip_stream));
+        if (er == hipErrorInvalidValue) return ctx_fail(ctx, GNS_ESTATE, "a context may use at most 4 streams between two cache draws");
+        if (er != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "wait for the cache draw", er);
+    }
     StageTimer t(ctx, GNS_STAGE_GATHER, static_cast<hipStream_t>(hip_stream));
     hipError_t e = launch_gather(ctx, nodes_dev, num_nodes, out_dev, active_gen(ctx), static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "gather launch", e);

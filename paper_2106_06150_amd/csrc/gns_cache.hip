@@ -331,10 +331,20 @@ static gns_status mark_last_readers(gns_ctx* c, int old_gen)
 {
     for (int i = 0; i < c->family_count; ++i) {
         gns_ctx* m = c->family[i];
-        if (!m->has_stream) continue;
-        GNS_HIP_TRY(hipEventRecord(m->gen_event[old_gen], m->last_stream), "event record");
-        m->gen_event_used[old_gen] = true;
+        for (int i = 0; i < m->reader_stream_count; ++i)
+            GNS_HIP_TRY(hipEventRecord(m->gen_event[old_gen][i], m->reader_streams[i]), "event record");
+        m->gen_event_used[old_gen] = m->reader_stream_count;
+        m->reader_stream_count = 0;          // streams used from now on read the next cache
     }
+    return GNS_OK;
+}
+
+// The current cache stops being usable without a successor (the cache probability is about to change).
+gns_status retire_cache(gns_ctx* c)
+{
+    const gns_status st = mark_last_readers(c, c->cache_gen);
+    if (st != GNS_OK) return st;
+    c->cache_valid = false;
     return GNS_OK;
 }
 
@@ -347,6 +357,7 @@ gns_status activate_cache(gns_ctx* c)
     }
     c->cache_gen = c->pending_gen;
     c->cache_valid = true;
+    c->had_cache = true;
     c->pending = false;
     c->cache_version += 1;
     return GNS_OK;
@@ -371,15 +382,15 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, bool wait
     // The draw fills the copy of the cache block the mini-batches are not reading.  Whatever was enqueued
     // while that copy was the current one ended with the events recorded when it stopped being current:
     // the device may not have reached all of it yet if the host runs far ahead, so the draw waits for them.
-    const int gen = c->cache_valid ? (c->cache_gen ^ 1) : 0;
+    const int gen = c->had_cache ? (c->cache_gen ^ 1) : 0;
     uint64_t* bitmap = cache_ptr<uint64_t>(c, L.cache_bitmap, gen);
     if (c->pending)                                  // a draw that was never made current: this one replaces it
         GNS_HIP_TRY(hipStreamWaitEvent(s, c->ready_event[c->pending_gen], 0), "wait for the replaced draw");
     for (int i = 0; i < c->family_count; ++i) {
         gns_ctx* m = c->family[i];
-        if (!m->gen_event_used[gen]) continue;
-        GNS_HIP_TRY(hipStreamWaitEvent(s, m->gen_event[gen], 0), "wait for the readers of the old cache");
-        m->gen_event_used[gen] = false;
+        for (int i = 0; i < m->gen_event_used[gen]; ++i)
+            GNS_HIP_TRY(hipStreamWaitEvent(s, m->gen_event[gen][i], 0), "wait for the readers of the old cache");
+        m->gen_event_used[gen] = 0;
     }
     hipLaunchKernelGGL(k_cache_draw_reset, dim3(1), dim3(kWave), 0, s, c->d_state);
     GNS_HIP_TRY(launch_fill_u64(reinterpret_cast<unsigned long long*>(bitmap), (size_t) L.words, 0ull, s), "clear cache bitmap");

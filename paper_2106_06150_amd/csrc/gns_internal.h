@@ -82,6 +82,9 @@ struct Layout {
 }  // namespace gns
 
 namespace gns {
+// Streams one context may enqueue mini-batches on between two cache draws (each gets an event the
+// draw after next waits for).
+constexpr int kReaderStreams = 4;
 // Opaque host-side storage for the first kernel's argument block (filled by fill_begin_args).
 struct BeginArgsHost {
     alignas(8) unsigned char bytes[96];
@@ -115,10 +118,11 @@ struct gns_ctx {
     // Who may still read the copy a draw is about to overwrite: work enqueued before the previous draw.
     // Every draw records an event on the stream each context of the family last used (all that was
     // enqueued there so far) and waits, on the device, for the events the previous draw recorded.
-    hipEvent_t gen_event[2];         // alternate from draw to draw
-    bool gen_event_used[2];
-    hipStream_t last_stream;         // where this context last enqueued readers of the cache block
-    bool has_stream;
+    hipEvent_t gen_event[2][gns::kReaderStreams];   // alternate from draw to draw; one per stream used
+    int gen_event_used[2];           // how many of them the draw that overwrites that copy has to wait for
+    hipStream_t reader_streams[gns::kReaderStreams];   // where this context enqueued readers of the cache block
+    int reader_stream_count;         //   since the last draw became current
+    bool had_cache;                  // root only: some draw has been made current (cache_gen is meaningful)
     int64_t refresh_count;           // root only
     // root only: a draw enqueued by gns_sample_cache_async and not yet made current
     bool pending;
@@ -143,6 +147,7 @@ struct gns_ctx {
     gns::BatchGraph bg[2][2];        // [hash-map parity][cache generation]
     int hash_parity;                 // which hash map the next mini-batch uses
     uint32_t batch_id;               // id of the last mini-batch enqueued on this context (from 1)
+    uint32_t bad_reported;           // DeviceState::bad_seed as of the last report to the caller
     // argument storage of the first kernel (pointed to by the node's parameter list)
     gns::BeginArgsHost ga_begin;
     int32_t ga_num_seeds;
@@ -178,8 +183,12 @@ static inline int active_gen(const gns_ctx* c) { return c->root->cache_gen; }
 // the first time after another copy became current, makes the stream wait for the draw that filled it.
 static inline hipError_t before_cache_readers(gns_ctx* c, hipStream_t s)
 {
-    c->last_stream = s;
-    c->has_stream = true;
+    int known = 0;
+    while (known < c->reader_stream_count && c->reader_streams[known] != s) ++known;
+    if (known == c->reader_stream_count) {
+        if (known == kReaderStreams) return hipErrorInvalidValue;     // reported as GNS_ESTATE
+        c->reader_streams[c->reader_stream_count++] = s;
+    }
     gns_ctx* root = c->root;
     if (!c->uses_cache || !root->cache_valid || c->seen_version == root->cache_version) return hipSuccess;
     c->seen_version = root->cache_version;
@@ -222,6 +231,7 @@ hipError_t launch_count_nonzero_rows(gns_ctx* c, hipStream_t s, int32_t* d_out);
 // enqueue a fixed number of chunks (later ones stand down once the cache is complete) and return.
 gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, bool wait_for_it, hipStream_t s);
 gns_status activate_cache(gns_ctx* c);
+gns_status retire_cache(gns_ctx* c);
 gns_status finish_pending_draw(gns_ctx* c);
 
 // gns_sampler.hip

@@ -469,6 +469,78 @@ def test_async_pipeline_on_forked_contexts():
         gns.close()
 
 
+def test_bad_seed_in_an_earlier_batch_is_still_reported():
+    """Three mini-batches enqueued before one wait, the first of them with a repeated seed: the wait reports
+    it although the last batch was fine; the next wait is clean again."""
+    ip, ix = _small(n=2000)
+    n = ip.numel() - 1
+    gns = GpuGns(ip, ix, None, fanouts=(4, 3), policies=(U, C), cache_size=150, max_seeds=48)
+    try:
+        B.gns_sample_cache(gns.ctx, 3, 0)
+        good = [synth.uniform_seed_batch(n, 48, 70 + i).cuda() for i in range(3)]
+        bad = good[0].clone()
+        bad[7] = bad[3]
+        for sd_, t in ((1, bad), (2, good[1]), (3, good[2])):
+            B.gns_sample_blocks_async(gns.ctx, sd_, t, gns.blocks.array)
+        with pytest.raises(B.GnsError) as e:
+            B.gns_sample_blocks_wait(gns.ctx, gns.blocks.array)
+        assert e.value.status == B.GNS_EINVAL
+        B.gns_sample_blocks_async(gns.ctx, 4, good[0], gns.blocks.array)
+        B.gns_sample_blocks_wait(gns.ctx, gns.blocks.array)
+        cache = oracle.sample_cache(ip.numpy(), 3, 0, 150)
+        ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), cache[1], 150, 4, good[0].cpu().numpy(), [4, 3], [U, C])
+        compare_blocks([gns.blocks.views(i) for i in range(2)], ref)
+    finally:
+        gns.close()
+
+
+def test_walk_probability_recomputed_while_batches_are_in_flight():
+    """gns_cache_walk_probability invalidates the cache; mini-batches enqueued before it (on another stream,
+    not yet waited for) keep the cache they were enqueued with, and the draw that follows fills the other
+    copy of the cache structures instead of the one they read."""
+    ip, ix = _small(n=6000, avg=18, seed=31)
+    n = ip.numel() - 1
+    F = 16
+    feat = _feat(n, F, seed=2)
+    fanouts, policies, csize, bs = (5, 4), (CF, C), 300, 80
+    train = torch.from_numpy(np.random.default_rng(9).permutation(n)[:400].astype(np.int32))
+    gns = GpuGns(ip, ix, feat, fanouts=fanouts, policies=policies, cache_size=csize, max_seeds=bs, flag_mode=1,
+                 cache_probability=B.GNS_PROB_WALK)
+    try:
+        work = torch.cuda.Stream()
+        nb = 6
+        bufs = [B.BlockBuffers(gns.graph, gns.config, gns.device) for _ in range(nb)]
+        xin = [torch.zeros((b.array[1].cap_src, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        seeds = [train[40 * b:40 * b + bs].contiguous().cuda() for b in range(nb)]
+        prefixes = []
+        for rnd, scale in enumerate((10, 20)):
+            w, pre, total, support = gns.walk_probability(train, scale)     # while round 0's batches may still run
+            w_ref, pre_ref = oracle.walk_weights(ip.numpy(), ix.numpy(), train.numpy(), list(fanouts), scale_log2=scale)
+            assert np.array_equal(pre, pre_ref)
+            prefixes.append(pre_ref)
+            B.gns_sample_cache(gns.ctx, 12, rnd)
+            for b in range(3 * rnd, 3 * rnd + 3):
+                B.gns_sample_blocks_async(gns.ctx, 300 + b, seeds[b], bufs[b].array, work)
+                B.gns_gather_features(gns.ctx, bufs[b].tensors[1]["src_nodes"], -1, xin[b], work)
+        torch.cuda.synchronize()
+        for b in range(nb):
+            pre_ref = prefixes[b // 3]
+            cache = oracle.sample_cache(pre_ref, 12, b // 3, csize)
+            ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), cache[1], csize, 300 + b, seeds[b].cpu().numpy(),
+                                       list(fanouts), list(policies), prob_prefix=pre_ref)
+            for j, r in enumerate(ref):
+                t = bufs[b].tensors[j]
+                assert np.array_equal(t["indptr"][:r.num_dst + 1].cpu().numpy(), r.indptr)
+                assert np.array_equal(t["indices"][:r.num_edges].cpu().numpy(), r.indices)
+                assert np.array_equal(t["src_nodes"][:r.num_src].cpu().numpy(), r.src_nodes)
+                gw = t["weights"][:r.num_edges].cpu().numpy().astype(np.float64)
+                assert np.all(np.abs(gw - r.weights) <= 1e-5 * np.abs(r.weights))
+            x_ref = oracle.gather(feat.numpy(), ref[1].src_nodes)
+            assert xin[b][:ref[1].num_src].cpu().numpy().tobytes() == x_ref.tobytes()
+    finally:
+        gns.close()
+
+
 def test_cache_refresh_while_batches_are_in_flight():
     """A cache draw fills the copy of the cache structures that is not in use: batches enqueued before it
     (here on two forks, not yet waited for) must come out with the old cache, batches enqueued after it
@@ -617,6 +689,12 @@ def test_config3_cache_first_per_cache_flags():
     _config_parity(3, batches=1, device_gen="cuda", flag_mode=1, upper=CF, check_features=False)
 
 
+def test_config3_per_cache_flags_with_features():
+    """The benchmark's default mode (one flag per CSR entry, built when the cache is drawn) on the
+    products-shaped graph, gather and aggregation included."""
+    _config_parity(3, batches=2, device_gen="cuda", flag_mode=1)
+
+
 def test_config2_walk_probability_at_scale():
     """The random-walk cache probability on the medium graph from a 10 % training split: weights and prefix
     bit for bit, then one mini-batch drawn with that cache."""
@@ -643,6 +721,12 @@ def test_config4_int64_offsets_and_host_features():
 
 def test_config5_giant_graph():
     _config_parity(5, batches=2, device_gen="cuda", flag_mode=0)
+
+
+def test_config5_giant_graph_per_cache_flags():
+    """The flag pass over all 1.6 G CSR entries with the cache bitmap in global memory, then mini-batches that
+    only read their rows' flag words: the mode the benchmark runs on this workload."""
+    _config_parity(5, batches=2, device_gen="cuda", flag_mode=1)
 
 
 @pytest.mark.parametrize("rows,f1,f2,hdim,relu,use_bias", [(1000, 128, 128, 256, True, True), (1, 4, 8, 12, False, False),
