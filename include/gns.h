@@ -22,7 +22,8 @@
  *    is documented as a host pointer (struct pointers, out-parameters).
  *  - The caller owns every buffer, including the workspace; the library
  *    borrows them for the lifetime of the context and never frees them.  All
- *    device memory the kernels touch is the caller's.  What the
+ *    device memory the kernels touch is the caller's (or, for
+ *    gns_sample_blocks_static, the library's fixed scratch array).  What the
  *    library itself allocates is host-side or runtime state: gns_create and
  *    gns_fork allocate a small pinned host mirror of the device counters, HIP
  *    events and a capture stream; the first mini-batch with a new set of block
@@ -266,6 +267,24 @@ gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_d
 gns_status gns_sample_blocks_async(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
                                    gns_block* blocks, void* hip_stream);
 gns_status gns_sample_blocks_wait(gns_ctx* ctx, gns_block* blocks, void* hip_stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): gns_sample_blocks with the per-batch scratch (device
+ * counters, frontier mark bitmap, batch hash map, row extents, sampler scratch, scan partials)
+ * in a fixed array of GNS_STATIC_SCRATCH_BYTES bytes that the library holds on every GPU it is
+ * loaded on, instead of in the context's workspace.  Same arguments, same results, same errors
+ * as gns_sample_blocks; ctx may be the context made by gns_create or any of its forks (the
+ * graph, config and current cache are theirs).  The call allocates nothing: no hipMalloc, no
+ * host allocation, no HIP graph (the kernels are launched one by one on hip_stream, which is
+ * synchronised before the call returns).  GNS_ECAPACITY if the per-batch scratch of this graph
+ * and config (what gns_fork_workspace_bytes reports) exceeds the array: nothing is launched.
+ * All calls on one GPU share that GPU's array, whatever their context: it is re-initialised at
+ * the start of every call, and calls that overlap on one GPU race.  gns_gather_features and
+ * gns_aggregate after it take the host counts the call filled in (the device-count
+ * placeholders refer to the context's own scratch, which this call does not use). */
+#define GNS_STATIC_SCRATCH_BYTES (128u << 20)
+gns_status gns_sample_blocks_static(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
+                                    gns_block* blocks, void* hip_stream);
 
 /* Section 2.2 steps 2-3.  out_dev[j, :] = feature row of nodes_dev[j]
  * (fp32[num_nodes x F] row-major, bit copies).  A cached node is read from the

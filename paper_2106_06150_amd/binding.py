@@ -79,6 +79,8 @@ def _load():
     lib.gns_sample_blocks.restype = ctypes.c_int
     lib.gns_sample_blocks_async.argtypes = [vp, u64, vp, i32, P(gns_block), vp]
     lib.gns_sample_blocks_async.restype = ctypes.c_int
+    lib.gns_sample_blocks_static.argtypes = [vp, u64, vp, i32, P(gns_block), vp]
+    lib.gns_sample_blocks_static.restype = ctypes.c_int
     lib.gns_sample_blocks_wait.argtypes = [vp, P(gns_block), vp]
     lib.gns_sample_blocks_wait.restype = ctypes.c_int
     lib.gns_gather_features.argtypes = [vp, vp, i32, vp, vp]
@@ -101,7 +103,9 @@ lib = _load()
 EXPORTED = ["gns_workspace_bytes", "gns_block_capacity", "gns_create", "gns_destroy", "gns_sample_cache",
             "gns_cache_view", "gns_sample_blocks", "gns_gather_features", "gns_aggregate", "gns_last_error",
             "gns_profile_begin", "gns_profile_collect", "gns_sample_blocks_async", "gns_sample_blocks_wait",
-            "gns_fork", "gns_fork_workspace_bytes", "gns_cache_walk_probability", "gns_cache_probability_view", "gns_sage_dense", "gns_sample_cache_async", "gns_activate_cache"]
+            "gns_fork", "gns_fork_workspace_bytes", "gns_cache_walk_probability", "gns_cache_probability_view", "gns_sage_dense", "gns_sample_cache_async", "gns_activate_cache",
+            "gns_sample_blocks_static"]
+GNS_STATIC_SCRATCH_BYTES = 128 << 20
 
 GNS_STAGE_SAMPLE, GNS_STAGE_FINISH, GNS_STAGE_GATHER, GNS_STAGE_AGGREGATE = 0, 8, 16, 17
 GNS_STAGE_DENSE = 21
@@ -245,6 +249,12 @@ def gns_sample_blocks_async(ctx, seed, seeds_dev, blocks, stream=None):
     assert seeds_dev.is_cuda and seeds_dev.dtype == torch.int32 and seeds_dev.is_contiguous()
     _check(lib.gns_sample_blocks_async(ctx, seed, seeds_dev.data_ptr(), seeds_dev.numel(), blocks,
                                        _stream_ptr(stream)), ctx)
+
+
+def gns_sample_blocks_static(ctx, seed, seeds_dev, blocks, stream=None):
+    assert seeds_dev.is_cuda and seeds_dev.dtype == torch.int32 and seeds_dev.is_contiguous()
+    _check(lib.gns_sample_blocks_static(ctx, seed, seeds_dev.data_ptr(), seeds_dev.numel(), blocks,
+                                        _stream_ptr(stream)), ctx)
 
 
 def gns_sample_blocks_wait(ctx, blocks, stream=None):

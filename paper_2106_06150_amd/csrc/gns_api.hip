@@ -179,8 +179,9 @@ gns_status ctx_fail(gns_ctx* c, gns_status st, const char* what, hipError_t e)
 using namespace gns;
 
 // Every launch of one mini-batch, in order, on stream s (also the body that is captured).
-static gns_status enqueue_batch(gns_ctx* c, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
-                                gns_block* blocks, hipStream_t s)
+namespace gns {
+gns_status enqueue_batch(gns_ctx* c, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
+                         gns_block* blocks, hipStream_t s)
 {
     const int nl = c->config.num_layers;
     hipError_t e = launch_batch_begin(c, seed, seeds_dev, num_seeds, c->batch_id + 1, s);
@@ -206,6 +207,27 @@ static gns_status enqueue_batch(gns_ctx* c, uint64_t seed, const int32_t* seeds_
     }
     return GNS_OK;
 }
+
+// Host-side checks of one mini-batch's arguments (no device work).
+gns_status check_batch_args(gns_ctx* c, const int32_t* seeds_dev, int32_t num_seeds, const gns_block* blocks)
+{
+    if (!seeds_dev || !blocks) return ctx_fail(c, GNS_EINVAL, "null seeds or blocks");
+    if (num_seeds < 1 || num_seeds > c->config.max_seeds) return ctx_fail(c, GNS_EINVAL, "num_seeds out of range");
+    if (c->uses_cache && !c->root->cache_valid) return ctx_fail(c, GNS_ESTATE, "gns_sample_cache must run before gns_sample_blocks");
+    const Layout& L = c->lay;
+    for (int i = 0; i < c->config.num_layers; ++i) {
+        const gns_block* b = &blocks[i];
+        if (!b->indptr || !b->indices || !b->src_nodes || !b->row_eligible || !b->weights)
+            return ctx_fail(c, GNS_EINVAL, "a block has a null buffer");
+        if (b->cap_dst < L.rows[i] || b->cap_src < L.rows[i + 1] || b->cap_edges < L.edges[i]) {
+            snprintf(c->err, sizeof(c->err), "block %d too small: need cap_dst %lld cap_src %lld cap_edges %lld", i,
+                     (long long) L.rows[i], (long long) L.rows[i + 1], (long long) L.edges[i]);
+            return GNS_ECAPACITY;
+        }
+    }
+    return GNS_OK;
+}
+}  // namespace gns
 
 static hipError_t events_create(gns_ctx* c)
 {
@@ -315,6 +337,70 @@ static gns_status launch_batch_graph(gns_ctx* c, uint64_t seed, const int32_t* s
     return GNS_OK;
 }
 
+namespace gns {
+// What a context's per-batch scratch must hold before its first mini-batch: zeroed device state, an empty
+// frontier mark bitmap, two empty hash maps.  Enqueue only.
+hipError_t init_batch_scratch(gns_ctx* c, hipStream_t s)
+{
+    const Layout& L = c->lay;
+    hipError_t e = launch_fill_u32(reinterpret_cast<uint32_t*>(c->d_state), (sizeof(DeviceState) + 64) / 4, 0u, s);
+    if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.mark_bitmap), (size_t) L.words, 0ull, s);
+    for (int par = 0; par < 2 && e == hipSuccess; ++par)
+        e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.hash_slots[par]), (size_t) L.hash_cap, ~0ull, s);
+    return e;
+}
+
+// A context that shares root's graph, config and cache and keeps its per-batch scratch at `workspace`
+// (not initialised here).  Joins root's family.
+gns_status make_child(gns_ctx* root, void* workspace, bool with_capture_stream, gns_ctx** out)
+{
+    *out = nullptr;
+    if (root->family_count >= (int) (sizeof(root->family) / sizeof(root->family[0])))
+        return ctx_fail(root, GNS_ECAPACITY, "too many live forks of one context");
+    gns_ctx* c = new (std::nothrow) gns_ctx;
+    if (!c) return ctx_fail(root, GNS_ENOMEM, "host allocation failed");
+    memcpy(c, root, sizeof(*c));
+    c->ws = static_cast<char*>(workspace);
+    c->shared_ws = root->ws;
+    c->root = root;
+    c->d_state = ws_ptr<DeviceState>(c, c->lay.state);
+    c->h_state = nullptr;
+    c->prof = nullptr;
+    c->prof_capacity = c->prof_count = 0;
+    c->prof_mask = 0;
+    c->err[0] = 0;
+    memset(c->bg, 0, sizeof(c->bg));
+    c->hash_parity = 0;
+    c->batch_id = 0;
+    c->bad_reported = 0;
+    c->cap_stream = nullptr;
+    c->family_count = 0;
+    c->static_child = nullptr;
+    memset(c->gen_event, 0, sizeof(c->gen_event));
+    c->ready_event[0] = c->ready_event[1] = nullptr;
+    hipError_t e = hipSuccess;
+    if (with_capture_stream) {
+        e = hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking);
+        if (e != hipSuccess) c->cap_stream = nullptr;
+    }
+    if (e == hipSuccess) {
+        e = hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(DeviceState), hipHostMallocDefault);
+        if (e != hipSuccess) c->h_state = nullptr;
+    }
+    if (e == hipSuccess) e = events_create(c);
+    if (e != hipSuccess) {
+        if (c->h_state) (void) hipHostFree(c->h_state);
+        if (c->cap_stream) (void) hipStreamDestroy(c->cap_stream);
+        events_destroy(c);
+        delete c;
+        return ctx_fail(root, GNS_EHIP, "child context", e);
+    }
+    root->family[root->family_count++] = c;
+    *out = c;
+    return GNS_OK;
+}
+}  // namespace gns
+
 extern "C" {
 
 size_t gns_workspace_bytes(const gns_graph* graph, const gns_config* config)
@@ -398,11 +484,8 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
     }
 
     // zero the state, the mark bitmap and the cache bitmap; validate the graph
-    e = launch_fill_u32(reinterpret_cast<uint32_t*>(c->d_state), (sizeof(DeviceState) + 64) / 4, 0u, s);
-    if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.mark_bitmap), (size_t) L.words, 0ull, s);
+    e = init_batch_scratch(c, s);
     if (e == hipSuccess) e = launch_fill_u64(cache_ptr<unsigned long long>(c, L.cache_bitmap, 0), (size_t) L.words, 0ull, s);
-    for (int par = 0; par < 2 && e == hipSuccess; ++par)
-        e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.hash_slots[par]), (size_t) L.hash_cap, ~0ull, s);
     if (e != hipSuccess) return bail(GNS_EHIP, "workspace init", e);
     int32_t* d_info = ws_ptr<int32_t>(c, L.sums_words);   // scratch, 4 ints
     e = launch_count_nonzero_rows(c, s, d_info);
@@ -417,6 +500,15 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
     c->nonzero_degree_nodes = info[0];
     if (c->uses_cache && config->cache_size > c->nonzero_degree_nodes)
         return bail(GNS_EINVAL, "cache_size exceeds the number of nodes that have a neighbor", hipSuccess);
+    // the hidden context gns_sample_blocks_static runs on (none if the per-batch scratch does not fit)
+    {
+        const gns_status st = static_scratch_setup(c);
+        if (st != GNS_OK) {
+            snprintf(g_create_err, sizeof(g_create_err), "%s", c->err);
+            (void) gns_destroy(c);
+            return st;
+        }
+    }
     *out_ctx = c;
     return GNS_OK;
 }
@@ -497,50 +589,16 @@ gns_status gns_fork(gns_ctx* parent, void* workspace, size_t workspace_bytes, vo
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return ctx_fail(parent, GNS_EINVAL, "workspace must be a 256-byte aligned device pointer");
     if (workspace_bytes < root->lay.shared_begin) return ctx_fail(parent, GNS_ECAPACITY, "fork workspace too small");
-    gns_ctx* c = new (std::nothrow) gns_ctx;
-    if (!c) return ctx_fail(parent, GNS_ENOMEM, "host allocation failed");
-    memcpy(c, root, sizeof(*c));
-    c->ws = static_cast<char*>(workspace);
-    c->shared_ws = root->ws;
-    c->root = root;
-    c->d_state = ws_ptr<DeviceState>(c, c->lay.state);
-    c->h_state = nullptr;
-    c->prof = nullptr;
-    c->prof_capacity = c->prof_count = 0;
-    c->prof_mask = 0;
-    c->err[0] = 0;
-    memset(c->bg, 0, sizeof(c->bg));
-    c->hash_parity = 0;
-    c->batch_id = 0;
-    c->bad_reported = 0;
-    c->cap_stream = nullptr;
-    c->family_count = 0;
-    memset(c->gen_event, 0, sizeof(c->gen_event));
-    c->ready_event[0] = c->ready_event[1] = nullptr;
-    if (root->family_count >= (int) (sizeof(root->family) / sizeof(root->family[0]))) {
-        delete c;
-        return ctx_fail(parent, GNS_ECAPACITY, "too many live forks of one context");
-    }
+    gns_ctx* c = nullptr;
+    const gns_status st = make_child(root, workspace, root->cap_stream != nullptr, &c);
+    if (st != GNS_OK) { snprintf(parent->err, sizeof(parent->err), "%s", root->err); return st; }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    if (root->cap_stream && hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking) != hipSuccess) {
-        delete c;
-        return ctx_fail(parent, GNS_EHIP, "hipStreamCreate");
-    }
-    hipError_t e = hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(DeviceState), hipHostMallocDefault);
-    if (e == hipSuccess) e = events_create(c);
-    if (e == hipSuccess) e = launch_fill_u32(reinterpret_cast<uint32_t*>(c->d_state), (sizeof(DeviceState) + 64) / 4, 0u, s);
-    if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, c->lay.mark_bitmap), (size_t) c->lay.words, 0ull, s);
-    for (int par = 0; par < 2 && e == hipSuccess; ++par)
-        e = launch_fill_u64(ws_ptr<unsigned long long>(c, c->lay.hash_slots[par]), (size_t) c->lay.hash_cap, ~0ull, s);
+    hipError_t e = init_batch_scratch(c, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
-        if (c->h_state) (void) hipHostFree(c->h_state);
-        if (c->cap_stream) (void) hipStreamDestroy(c->cap_stream);
-        events_destroy(c);
-        delete c;
+        (void) gns_destroy(c);
         return ctx_fail(parent, GNS_EHIP, "fork init", e);
     }
-    root->family[root->family_count++] = c;
     *out_child = c;
     return GNS_OK;
 }
@@ -548,6 +606,7 @@ gns_status gns_fork(gns_ctx* parent, void* workspace, size_t workspace_bytes, vo
 gns_status gns_destroy(gns_ctx* ctx)
 {
     if (!ctx) return GNS_OK;
+    if (ctx->static_child) { (void) gns_destroy(ctx->static_child); ctx->static_child = nullptr; }
     profile_release(ctx);
     for (int par = 0; par < 2; ++par)
         for (int gen = 0; gen < 2; ++gen) graph_release(ctx, par, gen);
@@ -652,20 +711,10 @@ gns_status gns_sample_blocks_async(gns_ctx* ctx, uint64_t seed, const int32_t* s
 {
     if (!ctx) return GNS_EINVAL;
     gns_ctx* c = ctx;
-    if (!seeds_dev || !blocks) return ctx_fail(c, GNS_EINVAL, "null seeds or blocks");
-    if (num_seeds < 1 || num_seeds > c->config.max_seeds) return ctx_fail(c, GNS_EINVAL, "num_seeds out of range");
-    if (c->uses_cache && !c->root->cache_valid) return ctx_fail(c, GNS_ESTATE, "gns_sample_cache must run before gns_sample_blocks");
-    const Layout& L = c->lay;
     const int nl = c->config.num_layers;
-    for (int i = 0; i < nl; ++i) {
-        gns_block* b = &blocks[i];
-        if (!b->indptr || !b->indices || !b->src_nodes || !b->row_eligible || !b->weights)
-            return ctx_fail(c, GNS_EINVAL, "a block has a null buffer");
-        if (b->cap_dst < L.rows[i] || b->cap_src < L.rows[i + 1] || b->cap_edges < L.edges[i]) {
-            snprintf(c->err, sizeof(c->err), "block %d too small: need cap_dst %lld cap_src %lld cap_edges %lld", i,
-                     (long long) L.rows[i], (long long) L.rows[i + 1], (long long) L.edges[i]);
-            return GNS_ECAPACITY;
-        }
+    {
+        const gns_status st = check_batch_args(c, seeds_dev, num_seeds, blocks);
+        if (st != GNS_OK) return st;
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     {

@@ -148,6 +148,7 @@ struct gns_ctx {
     int hash_parity;                 // which hash map the next mini-batch uses
     uint32_t batch_id;               // id of the last mini-batch enqueued on this context (from 1)
     uint32_t bad_reported;           // DeviceState::bad_seed as of the last report to the caller
+    gns_ctx* static_child;           // root only: the context of gns_sample_blocks_static (scratch in the library's array)
     // argument storage of the first kernel (pointed to by the node's parameter list)
     gns::BeginArgsHost ga_begin;
     int32_t ga_num_seeds;
@@ -196,6 +197,14 @@ static inline hipError_t before_cache_readers(gns_ctx* c, hipStream_t s)
 }
 
 gns_status ctx_fail(gns_ctx* c, gns_status st, const char* what, hipError_t e = hipSuccess);
+// gns_api.hip
+gns_status enqueue_batch(gns_ctx* c, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds, gns_block* blocks,
+                         hipStream_t s);
+gns_status check_batch_args(gns_ctx* c, const int32_t* seeds_dev, int32_t num_seeds, const gns_block* blocks);
+hipError_t init_batch_scratch(gns_ctx* c, hipStream_t s);
+gns_status make_child(gns_ctx* root, void* workspace, bool with_capture_stream, gns_ctx** out);
+// gns_static.hip
+gns_status static_scratch_setup(gns_ctx* root);
 bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char* err, size_t errlen);
 
 // Brackets a stage's launches with events when that stage is being timed.
