@@ -53,6 +53,7 @@ extern "C" {
 
 #define GNS_MAX_LAYERS 8
 #define GNS_MAX_FANOUT 64
+#define GNS_MAX_GROUP 8      /* mini-batches one gns_*_group call serves */
 
 typedef struct gns_ctx gns_ctx; /* opaque; one per (graph, config, device) */
 
@@ -159,7 +160,8 @@ gns_status gns_block_capacity(const gns_graph* graph, const gns_config* config, 
  * Validates the arguments (GNS_EINVAL), e.g. cache_size must not exceed the
  * number of nodes with at least one neighbor when a cache policy is used.
  * Initialises the workspace on `hip_stream` and synchronises it.
- * A mini-batch's launch sequence is captured into a HIP graph on first use and replayed afterwards;
+ * A mini-batch's launch sequence is captured into a HIP graph on first use (per set of block buffers)
+ * and replayed afterwards, whatever the cache generation;
  * with the environment variable GNS_NO_GRAPH set when the context is created (forks inherit it) every
  * kernel is launched on its own instead. */
 gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_config* config,
@@ -267,6 +269,29 @@ gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_d
 gns_status gns_sample_blocks_async(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
                                    gns_block* blocks, void* hip_stream);
 gns_status gns_sample_blocks_wait(gns_ctx* ctx, gns_block* blocks, void* hip_stream);
+
+/* Several independent mini-batches in one launch sequence.  Mini-batches are independent given the
+ * cache (the paper's sampling workers, Section 3.3), and on a GPU the many small dependent kernels
+ * of one batch are bound by launch latency, so every kernel of the sequence serves the whole group:
+ * batch b of the group runs on context ctxs[b] (count distinct contexts of one family: the context made
+ * by gns_create and forks of it, 1 <= count <= GNS_MAX_GROUP), with seed seeds[b], seed nodes
+ * seeds_dev[b][0 .. num_seeds[b]) and block buffers blocks[b] (an array of num_layers gns_block each).
+ * All arrays are host arrays of count entries.  Results are exactly those of count calls of
+ * gns_sample_blocks_async / gns_gather_features / gns_aggregate, one per context, and the same
+ * rules hold (placeholders for the counts until the wait, device-side counts with num_nodes[b] < 0
+ * or GNS_DEVICE_COUNTS).  Errors are reported on ctxs[0] (gns_last_error(ctxs[0])).
+ * The captured launch sequence is kept by ctxs[0] and reused while the group consists of the same
+ * contexts and block buffers. */
+gns_status gns_sample_blocks_group(gns_ctx* const* ctxs, int32_t count, const uint64_t* seeds,
+                                   const int32_t* const* seeds_dev, const int32_t* num_seeds,
+                                   gns_block* const* blocks, void* hip_stream);
+gns_status gns_sample_blocks_group_wait(gns_ctx* const* ctxs, int32_t count, gns_block* const* blocks,
+                                        void* hip_stream);
+gns_status gns_gather_features_group(gns_ctx* const* ctxs, int32_t count, const int32_t* const* nodes_dev,
+                                     const int32_t* num_nodes, float* const* out_dev, void* hip_stream);
+gns_status gns_aggregate_group(gns_ctx* const* ctxs, int32_t count, const gns_block* const* blocks,
+                               const float* const* x_src_dev, int32_t feat_dim, float* const* out_dev,
+                               void* hip_stream);
 
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc): gns_sample_blocks with the per-batch scratch (device

@@ -19,6 +19,7 @@ GNS_FLAGS_PER_BATCH, GNS_FLAGS_PER_CACHE = 0, 1
 GNS_PROB_DEGREE, GNS_PROB_WALK = 0, 1
 GNS_MAX_LAYERS = 8
 GNS_MAX_FANOUT = 64
+GNS_MAX_GROUP = 8
 
 STATUS_NAMES = ["GNS_OK", "GNS_EINVAL", "GNS_ECAPACITY", "GNS_ESTATE", "GNS_EHIP", "GNS_ENOMEM", "GNS_ENOTIMPL"]
 
@@ -79,6 +80,14 @@ def _load():
     lib.gns_sample_blocks.restype = ctypes.c_int
     lib.gns_sample_blocks_async.argtypes = [vp, u64, vp, i32, P(gns_block), vp]
     lib.gns_sample_blocks_async.restype = ctypes.c_int
+    lib.gns_sample_blocks_group.argtypes = [P(vp), i32, P(u64), P(vp), P(i32), P(P(gns_block)), vp]
+    lib.gns_sample_blocks_group.restype = ctypes.c_int
+    lib.gns_sample_blocks_group_wait.argtypes = [P(vp), i32, P(P(gns_block)), vp]
+    lib.gns_sample_blocks_group_wait.restype = ctypes.c_int
+    lib.gns_gather_features_group.argtypes = [P(vp), i32, P(vp), P(i32), P(vp), vp]
+    lib.gns_gather_features_group.restype = ctypes.c_int
+    lib.gns_aggregate_group.argtypes = [P(vp), i32, P(P(gns_block)), P(vp), i32, P(vp), vp]
+    lib.gns_aggregate_group.restype = ctypes.c_int
     lib.gns_sample_blocks_static.argtypes = [vp, u64, vp, i32, P(gns_block), vp]
     lib.gns_sample_blocks_static.restype = ctypes.c_int
     lib.gns_sample_blocks_wait.argtypes = [vp, P(gns_block), vp]
@@ -104,7 +113,8 @@ EXPORTED = ["gns_workspace_bytes", "gns_block_capacity", "gns_create", "gns_dest
             "gns_cache_view", "gns_sample_blocks", "gns_gather_features", "gns_aggregate", "gns_last_error",
             "gns_profile_begin", "gns_profile_collect", "gns_sample_blocks_async", "gns_sample_blocks_wait",
             "gns_fork", "gns_fork_workspace_bytes", "gns_cache_walk_probability", "gns_cache_probability_view", "gns_sage_dense", "gns_sample_cache_async", "gns_activate_cache",
-            "gns_sample_blocks_static"]
+            "gns_sample_blocks_static", "gns_sample_blocks_group", "gns_sample_blocks_group_wait",
+            "gns_gather_features_group", "gns_aggregate_group"]
 GNS_STATIC_SCRATCH_BYTES = 128 << 20
 
 GNS_STAGE_SAMPLE, GNS_STAGE_FINISH, GNS_STAGE_GATHER, GNS_STAGE_AGGREGATE = 0, 8, 16, 17
@@ -255,6 +265,59 @@ def gns_sample_blocks_static(ctx, seed, seeds_dev, blocks, stream=None):
     assert seeds_dev.is_cuda and seeds_dev.dtype == torch.int32 and seeds_dev.is_contiguous()
     _check(lib.gns_sample_blocks_static(ctx, seed, seeds_dev.data_ptr(), seeds_dev.numel(), blocks,
                                         _stream_ptr(stream)), ctx)
+
+
+class GroupCall:
+    """Argument arrays of the gns_*_group calls for a fixed set of contexts and block buffers (marshalling
+    only: built once, reused for every call; seeds and per-call pointers are filled in per call)."""
+
+    def __init__(self, ctxs, block_arrays):
+        n = len(ctxs)
+        assert 1 <= n <= GNS_MAX_GROUP and len(block_arrays) == n
+        self.n = n
+        self.lead = ctxs[0]
+        self.ctxs = (ctypes.c_void_p * n)(*[c.value if isinstance(c, ctypes.c_void_p) else c for c in ctxs])
+        self.blocks = (ctypes.POINTER(gns_block) * n)(*[ctypes.cast(b, ctypes.POINTER(gns_block)) for b in block_arrays])
+        self.seeds = (ctypes.c_uint64 * n)()
+        self.seeds_dev = (ctypes.c_void_p * n)()
+        self.num_seeds = (ctypes.c_int32 * n)()
+        self.nodes = (ctypes.c_void_p * n)()
+        self.num_nodes = (ctypes.c_int32 * n)()
+        self.out = (ctypes.c_void_p * n)()
+        self.agg_blocks = (ctypes.POINTER(gns_block) * n)()
+        self.x_src = (ctypes.c_void_p * n)()
+        self.agg_out = (ctypes.c_void_p * n)()
+        self._keep = (ctxs, block_arrays)
+
+    def sample(self, seeds, seeds_dev, stream=None):
+        """seeds: n integers; seeds_dev: n int32 device tensors.  Enqueue only (counts stay on the device)."""
+        for b in range(self.n):
+            t = seeds_dev[b]
+            assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()
+            self.seeds[b] = seeds[b]
+            self.seeds_dev[b] = t.data_ptr()
+            self.num_seeds[b] = t.numel()
+        _check(lib.gns_sample_blocks_group(self.ctxs, self.n, self.seeds, self.seeds_dev, self.num_seeds, self.blocks,
+                                           _stream_ptr(stream)), self.lead)
+
+    def wait(self, stream=None):
+        _check(lib.gns_sample_blocks_group_wait(self.ctxs, self.n, self.blocks, _stream_ptr(stream)), self.lead)
+
+    def gather(self, nodes_dev, num_nodes, out_dev, stream=None):
+        for b in range(self.n):
+            self.nodes[b] = nodes_dev[b].data_ptr()
+            self.num_nodes[b] = num_nodes[b]
+            self.out[b] = out_dev[b].data_ptr()
+        _check(lib.gns_gather_features_group(self.ctxs, self.n, self.nodes, self.num_nodes, self.out,
+                                             _stream_ptr(stream)), self.lead)
+
+    def aggregate(self, layer_index, x_src_dev, feat_dim, out_dev, stream=None):
+        for b in range(self.n):
+            self.agg_blocks[b] = ctypes.pointer(self.blocks[b][layer_index])
+            self.x_src[b] = x_src_dev[b].data_ptr()
+            self.agg_out[b] = out_dev[b].data_ptr()
+        _check(lib.gns_aggregate_group(self.ctxs, self.n, self.agg_blocks, self.x_src, feat_dim, self.agg_out,
+                                       _stream_ptr(stream)), self.lead)
 
 
 def gns_sample_blocks_wait(ctx, blocks, stream=None):

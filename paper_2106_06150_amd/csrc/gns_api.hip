@@ -5,7 +5,7 @@
 #include <string.h>
 #include <new>
 #include "gns_internal.h"
-#include "gns_device.hpp"
+#include "gns_kernels.hpp"
 
 namespace gns {
 
@@ -180,32 +180,47 @@ using namespace gns;
 
 // Every launch of one mini-batch, in order, on stream s (also the body that is captured).
 namespace gns {
-gns_status enqueue_batch(gns_ctx* c, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
-                         gns_block* blocks, hipStream_t s)
+// Every launch of one group of mini-batches, in order, on stream s (also the body that is captured).
+gns_status enqueue_batch(const Group& g, const BeginDyn& d, hipStream_t s)
 {
+    gns_ctx* c = g.ctx[0];
     const int nl = c->config.num_layers;
-    hipError_t e = launch_batch_begin(c, seed, seeds_dev, num_seeds, c->batch_id + 1, s);
+    hipError_t e = launch_batch_begin(g, d, s);
     if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "batch begin", e);
     // the batch's kernels read the seeds from the context's own copy (made by the first kernel), so
     // the captured launch sequence does not depend on where the caller keeps them
-    const int32_t* dst = ws_ptr<int32_t>(c, c->lay.seed_copy);
-    const int32_t* prev_dst = nullptr;
     for (int i = 0; i < nl; ++i) {
         {
             StageTimer t(c, GNS_STAGE_SAMPLE + i, s);
-            e = launch_sample_layer(c, i, dst, blocks[i].row_eligible, prev_dst, i ? &blocks[i - 1] : nullptr, s);
+            e = launch_sample_layer(g, i, s);
         }
         if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample layer", e);
         {
             StageTimer t(c, GNS_STAGE_FINISH + i, s);
-            e = launch_finish_layer(c, i, dst, &blocks[i], s);
-            if (e == hipSuccess && i == nl - 1) e = launch_relabel(c, i, dst, &blocks[i], s);
+            e = launch_finish_layer(g, i, s);
+            if (e == hipSuccess && i == nl - 1) e = launch_relabel(g, i, s);
         }
         if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "finish layer", e);
-        prev_dst = dst;
-        dst = blocks[i].src_nodes;
     }
     return GNS_OK;
+}
+
+// The first kernel's per-call arguments: seeds, Philox keys, batch ids, and for every batch which hash map
+// it uses and which copy of the cache structures it reads (the current one).
+void fill_begin_dyn(const Group& g, const uint64_t* seeds, const int32_t* const* seeds_dev, const int32_t* num_seeds,
+                    BeginDyn* out)
+{
+    memset(out, 0, sizeof(*out));
+    for (int b = 0; b < g.count; ++b) {
+        gns_ctx* c = g.ctx[b];
+        out->seeds[b] = seeds_dev[b];
+        out->num_seeds[b] = num_seeds[b];
+        out->key0[b] = (uint32_t) seeds[b];
+        out->key1[b] = (uint32_t) (seeds[b] >> 32);
+        out->batch_id[b] = c->batch_id + 1;
+        out->parity[b] = c->hash_parity;
+        out->cache_gen[b] = active_gen(c);
+    }
 }
 
 // Host-side checks of one mini-batch's arguments (no device work).
@@ -257,9 +272,8 @@ static void events_destroy(gns_ctx* c)
     }
 }
 
-static void graph_release(gns_ctx* c, int par, int gen)
+static void graph_release(BatchGraph& g)
 {
-    BatchGraph& g = c->bg[par][gen];
     if (g.exec) (void) hipGraphExecDestroy(g.exec);
     if (g.graph) (void) hipGraphDestroy(g.graph);
     g.exec = nullptr;
@@ -268,41 +282,52 @@ static void graph_release(gns_ctx* c, int par, int gen)
     g.valid = false;
 }
 
-// The batch's launch sequence does not depend on the data (grids are sized for the worst
-// case and counts stay on the device), so it is captured once per set of caller block buffers,
-// hash-map parity and cache generation, and replayed with hipGraphLaunch; only the first kernel's arguments (seeds
-// pointer, seed, seed count, batch id) change between replays.
-static gns_status launch_batch_graph(gns_ctx* c, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
-                                     gns_block* blocks, hipStream_t s)
+// A group's launch sequence does not depend on the data (grids are sized for the worst case; counts, the
+// hash-map parity and the cache generation stay on the device), so it is captured once per set of contexts
+// and caller block buffers and replayed with hipGraphLaunch; only the first kernel's arguments (seeds
+// pointers, seeds, seed counts, batch ids, parities, cache generation) change between replays.  The graphs
+// are kept by the group's first context.
+static gns_status launch_batch_graph(const Group& grp, const BeginDyn& dyn, hipStream_t s)
 {
+    gns_ctx* c = grp.ctx[0];
     const int nl = c->config.num_layers;
-    const int par = c->hash_parity, gen = active_gen(c);
-    BatchGraph& g = c->bg[par][gen];
-    bool same = g.valid;
-    for (int i = 0; same && i < nl; ++i) {
-        const gns_block& a = g.blocks[i];
-        const gns_block& b = blocks[i];
-        same = a.indptr == b.indptr && a.indices == b.indices && a.src_nodes == b.src_nodes &&
-               a.row_eligible == b.row_eligible && a.weights == b.weights;
+    BatchGraph* hit = nullptr;
+    BatchGraph* victim = &c->bg[0];
+    for (int k = 0; k < kGraphsPerContext; ++k) {
+        BatchGraph& g = c->bg[k];
+        if (!g.valid) { victim = &g; continue; }
+        bool same = g.count == grp.count;
+        for (int b = 0; same && b < grp.count; ++b) {
+            same = g.ctx[b] == grp.ctx[b];
+            for (int i = 0; same && i < nl; ++i) {
+                const gns_block& x = g.blocks[b][i];
+                const gns_block& y = grp.blocks[b][i];
+                same = x.indptr == y.indptr && x.indices == y.indices && x.src_nodes == y.src_nodes &&
+                       x.row_eligible == y.row_eligible && x.weights == y.weights;
+            }
+        }
+        if (same) { hit = &g; break; }
+        if (victim->valid && g.last_use < victim->last_use) victim = &g;
     }
     hipError_t e;
-    if (!same) {
-        graph_release(c, par, gen);
+    if (!hit) {
+        BatchGraph& g = *victim;
+        graph_release(g);
         e = hipStreamBeginCapture(c->cap_stream, hipStreamCaptureModeRelaxed);
         if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "begin capture", e);
-        const gns_status st = enqueue_batch(c, seed, seeds_dev, num_seeds, blocks, c->cap_stream);
+        const gns_status st = enqueue_batch(grp, dyn, c->cap_stream);
         e = hipStreamEndCapture(c->cap_stream, &g.graph);
-        if (st != GNS_OK) { graph_release(c, par, gen); return st; }
-        if (e != hipSuccess) { graph_release(c, par, gen); return ctx_fail(c, GNS_EHIP, "end capture", e); }
+        if (st != GNS_OK) { graph_release(g); return st; }
+        if (e != hipSuccess) { graph_release(g); return ctx_fail(c, GNS_EHIP, "end capture", e); }
         e = hipGraphInstantiate(&g.exec, g.graph, nullptr, nullptr, 0);
-        if (e != hipSuccess) { graph_release(c, par, gen); return ctx_fail(c, GNS_EHIP, "graph instantiate", e); }
+        if (e != hipSuccess) { graph_release(g); return ctx_fail(c, GNS_EHIP, "graph instantiate", e); }
         // find the first kernel's node
         size_t count = 0;
         e = hipGraphGetNodes(g.graph, nullptr, &count);
-        if (e != hipSuccess || count == 0 || count > 256) { graph_release(c, par, gen); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
+        if (e != hipSuccess || count == 0 || count > 256) { graph_release(g); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
         hipGraphNode_t nodes[256];
         e = hipGraphGetNodes(g.graph, nodes, &count);
-        if (e != hipSuccess) { graph_release(c, par, gen); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
+        if (e != hipSuccess) { graph_release(g); return ctx_fail(c, GNS_EHIP, "graph nodes", e); }
         for (size_t i = 0; i < count && !g.first; ++i) {
             hipGraphNodeType type;
             if (hipGraphNodeGetType(nodes[i], &type) != hipSuccess || type != hipGraphNodeTypeKernel) continue;
@@ -310,25 +335,31 @@ static gns_status launch_batch_graph(gns_ctx* c, uint64_t seed, const int32_t* s
             if (hipGraphKernelNodeGetParams(nodes[i], &kp) != hipSuccess) continue;
             if (kp.func == batch_first_kernel()) g.first = nodes[i];
         }
-        if (!g.first) { graph_release(c, par, gen); return ctx_fail(c, GNS_EHIP, "first kernel node not found in the captured graph"); }
-        for (int i = 0; i < nl; ++i) g.blocks[i] = blocks[i];
+        if (!g.first) { graph_release(g); return ctx_fail(c, GNS_EHIP, "first kernel node not found in the captured graph"); }
+        g.count = grp.count;
+        for (int b = 0; b < grp.count; ++b) {
+            g.ctx[b] = grp.ctx[b];
+            for (int i = 0; i < nl; ++i) g.blocks[b][i] = grp.blocks[b][i];
+        }
+        // the first kernel's fixed argument block: the same for every replay of this graph
+        static_assert(sizeof(LayerArgs) <= sizeof(g.args.fixed), "BeginArgsHost::fixed too small");
+        static_assert(sizeof(BeginDyn) <= sizeof(g.args.dyn), "BeginArgsHost::dyn too small");
+        LayerArgs* fixed = reinterpret_cast<LayerArgs*>(g.args.fixed);
+        fill_group_args(grp, fixed);
+        fill_finish_template(c, 0, &fixed->f);
         g.valid = true;
+        hit = &g;
     }
-    // new scalars for this batch
+    BatchGraph& g = *hit;
+    g.last_use = ++c->graph_clock;
+    // new scalars for this group of batches
     hipKernelNodeParams kp;
     e = hipGraphKernelNodeGetParams(g.first, &kp);
     if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "get first kernel params", e);
-    fill_begin_args(c, seeds_dev, &c->ga_begin);
-    c->ga_num_seeds = num_seeds;
-    c->ga_key0 = (uint32_t) seed;
-    c->ga_key1 = (uint32_t) (seed >> 32);
-    c->ga_batch_id = c->batch_id + 1;
-    c->ga_ptrs[0] = c->ga_begin.bytes;
-    c->ga_ptrs[1] = &c->ga_num_seeds;
-    c->ga_ptrs[2] = &c->ga_key0;
-    c->ga_ptrs[3] = &c->ga_key1;
-    c->ga_ptrs[4] = &c->ga_batch_id;
-    kp.kernelParams = c->ga_ptrs;
+    memcpy(g.args.dyn, &dyn, sizeof(dyn));
+    g.arg_ptrs[0] = g.args.fixed;
+    g.arg_ptrs[1] = g.args.dyn;
+    kp.kernelParams = g.arg_ptrs;
     kp.extra = nullptr;
     e = hipGraphExecKernelNodeSetParams(g.exec, g.first, &kp);
     if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "set first kernel params", e);
@@ -369,7 +400,8 @@ gns_status make_child(gns_ctx* root, void* workspace, bool with_capture_stream, 
     c->prof_capacity = c->prof_count = 0;
     c->prof_mask = 0;
     c->err[0] = 0;
-    memset(c->bg, 0, sizeof(c->bg));
+    c->bg = nullptr;
+    c->graph_clock = 0;
     c->hash_parity = 0;
     c->batch_id = 0;
     c->bad_reported = 0;
@@ -382,6 +414,8 @@ gns_status make_child(gns_ctx* root, void* workspace, bool with_capture_stream, 
     if (with_capture_stream) {
         e = hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking);
         if (e != hipSuccess) c->cap_stream = nullptr;
+        c->bg = static_cast<BatchGraph*>(calloc(kGraphsPerContext, sizeof(BatchGraph)));
+        if (e == hipSuccess && !c->bg) e = hipErrorOutOfMemory;
     }
     if (e == hipSuccess) {
         e = hipHostMalloc(reinterpret_cast<void**>(&c->h_state), sizeof(DeviceState), hipHostMallocDefault);
@@ -389,6 +423,7 @@ gns_status make_child(gns_ctx* root, void* workspace, bool with_capture_stream, 
     }
     if (e == hipSuccess) e = events_create(c);
     if (e != hipSuccess) {
+        free(c->bg);
         if (c->h_state) (void) hipHostFree(c->h_state);
         if (c->cap_stream) (void) hipStreamDestroy(c->cap_stream);
         events_destroy(c);
@@ -458,6 +493,7 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
         else snprintf(g_create_err, sizeof(g_create_err), "%s", what);
         if (c->h_state) (void) hipHostFree(c->h_state);
         if (c->cap_stream) (void) hipStreamDestroy(c->cap_stream);
+        free(c->bg);
         events_destroy(c);
         delete c;
         return st;
@@ -481,6 +517,8 @@ gns_status gns_create(gns_ctx** out_ctx, const gns_graph* graph, const gns_confi
     if (!getenv("GNS_NO_GRAPH")) {
         e = hipStreamCreateWithFlags(&c->cap_stream, hipStreamNonBlocking);
         if (e != hipSuccess) { c->cap_stream = nullptr; return bail(GNS_EHIP, "hipStreamCreate", e); }
+        c->bg = static_cast<BatchGraph*>(calloc(kGraphsPerContext, sizeof(BatchGraph)));
+        if (!c->bg) return bail(GNS_ENOMEM, "host allocation failed", hipSuccess);
     }
 
     // zero the state, the mark bitmap and the cache bitmap; validate the graph
@@ -608,8 +646,20 @@ gns_status gns_destroy(gns_ctx* ctx)
     if (!ctx) return GNS_OK;
     if (ctx->static_child) { (void) gns_destroy(ctx->static_child); ctx->static_child = nullptr; }
     profile_release(ctx);
-    for (int par = 0; par < 2; ++par)
-        for (int gen = 0; gen < 2; ++gen) graph_release(ctx, par, gen);
+    // captured launch sequences that name this context: its own, and those of groups it was a member of
+    gns_ctx* fam_root = ctx->root;
+    for (int i = 0; i < fam_root->family_count; ++i) {
+        gns_ctx* m = fam_root->family[i];
+        if (!m->bg) continue;
+        for (int k = 0; k < kGraphsPerContext; ++k) {
+            BatchGraph& g = m->bg[k];
+            bool names = m == ctx;
+            for (int b = 0; !names && b < g.count; ++b) names = g.ctx[b] == ctx;
+            if (names) graph_release(g);
+        }
+    }
+    free(ctx->bg);
+    ctx->bg = nullptr;
     if (ctx->cap_stream) (void) hipStreamDestroy(ctx->cap_stream);
     if (ctx->h_state) (void) hipHostFree(ctx->h_state);
     events_destroy(ctx);
@@ -706,57 +756,114 @@ gns_status gns_cache_view(gns_ctx* ctx, const int32_t** cache_nodes, int64_t* ca
     return GNS_OK;
 }
 
+// Checks a group: 1..GNS_MAX_GROUP distinct contexts of one family.  Errors are reported on ctxs[0].
+static gns_status check_group(gns_ctx* const* ctxs, int32_t count)
+{
+    if (!ctxs || count < 1 || !ctxs[0]) return GNS_EINVAL;
+    gns_ctx* lead = ctxs[0];
+    if (count > GNS_MAX_GROUP) return ctx_fail(lead, GNS_EINVAL, "a group holds at most GNS_MAX_GROUP mini-batches");
+    for (int b = 0; b < count; ++b) {
+        if (!ctxs[b]) return ctx_fail(lead, GNS_EINVAL, "null context in the group");
+        if (ctxs[b]->root != lead->root) return ctx_fail(lead, GNS_EINVAL, "the contexts of a group must be one context and its forks");
+        for (int q = 0; q < b; ++q)
+            if (ctxs[q] == ctxs[b]) return ctx_fail(lead, GNS_EINVAL, "a context appears twice in the group");
+    }
+    return GNS_OK;
+}
+
+static gns_status group_before_cache_readers(gns_ctx* const* ctxs, int32_t count, hipStream_t s)
+{
+    for (int b = 0; b < count; ++b) {
+        const hipError_t er = before_cache_readers(ctxs[b], s);
+        if (er == hipErrorInvalidValue) return ctx_fail(ctxs[0], GNS_ESTATE, "a context may use at most 4 streams between two cache draws");
+        if (er != hipSuccess) return ctx_fail(ctxs[0], GNS_EHIP, "wait for the cache draw", er);
+    }
+    return GNS_OK;
+}
+
+gns_status gns_sample_blocks_group(gns_ctx* const* ctxs, int32_t count, const uint64_t* seeds,
+                                   const int32_t* const* seeds_dev, const int32_t* num_seeds,
+                                   gns_block* const* blocks, void* hip_stream)
+{
+    gns_status st = check_group(ctxs, count);
+    if (st != GNS_OK) return st;
+    gns_ctx* lead = ctxs[0];
+    if (!seeds || !seeds_dev || !num_seeds || !blocks) return ctx_fail(lead, GNS_EINVAL, "null argument array");
+    Group g;
+    memset(&g, 0, sizeof(g));
+    g.count = count;
+    for (int b = 0; b < count; ++b) {
+        st = check_batch_args(ctxs[b], seeds_dev[b], num_seeds[b], blocks[b]);
+        if (st != GNS_OK) {
+            if (ctxs[b] != lead) snprintf(lead->err, sizeof(lead->err), "%s", ctxs[b]->err);
+            return st;
+        }
+        g.ctx[b] = ctxs[b];
+        g.blocks[b] = blocks[b];
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    st = group_before_cache_readers(ctxs, count, s);
+    if (st != GNS_OK) return st;
+    BeginDyn dyn;
+    fill_begin_dyn(g, seeds, seeds_dev, num_seeds, &dyn);
+    if (lead->prof_mask == 0 && lead->cap_stream) st = launch_batch_graph(g, dyn, s);
+    else                                           st = enqueue_batch(g, dyn, s);
+    if (st != GNS_OK) return st;
+    const int nl = lead->config.num_layers;
+    for (int b = 0; b < count; ++b) {
+        ctxs[b]->batch_id += 1;
+        ctxs[b]->hash_parity ^= 1;             // this batch has left the other map empty
+        for (int i = 0; i < nl; ++i) {
+            blocks[b][i].num_dst = GNS_DEVICE_COUNTS(i);
+            blocks[b][i].num_src = -1;
+            blocks[b][i].num_edges = -1;
+        }
+    }
+    return GNS_OK;
+}
+
+gns_status gns_sample_blocks_group_wait(gns_ctx* const* ctxs, int32_t count, gns_block* const* blocks, void* hip_stream)
+{
+    gns_status st = check_group(ctxs, count);
+    if (st != GNS_OK) return st;
+    gns_ctx* lead = ctxs[0];
+    if (!blocks) return ctx_fail(lead, GNS_EINVAL, "null blocks");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipSuccess;
+    for (int b = 0; b < count && e == hipSuccess; ++b)
+        e = hipMemcpyAsync(ctxs[b]->h_state, ctxs[b]->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return ctx_fail(lead, GNS_EHIP, "sample_blocks wait", e);
+    st = GNS_OK;
+    for (int b = 0; b < count; ++b) {
+        gns_ctx* c = ctxs[b];
+        if (!blocks[b]) return ctx_fail(lead, GNS_EINVAL, "null blocks");
+        for (int i = 0; i < c->config.num_layers; ++i) {
+            blocks[b][i].num_dst = c->h_state->num_dst[i];
+            blocks[b][i].num_src = c->h_state->num_dst[i + 1];
+            blocks[b][i].num_edges = c->h_state->num_edges[i];
+        }
+        // bad_seed holds the id of the latest mini-batch that had a bad seed: anything newer than the last one
+        // reported means that a batch enqueued since the previous wait (not necessarily the last one) was bad
+        if (c->h_state->bad_seed != c->bad_reported) {
+            c->bad_reported = c->h_state->bad_seed;
+            st = ctx_fail(lead, GNS_EINVAL, "seeds must be distinct node ids in [0, num_nodes) (a mini-batch enqueued since the last wait had a bad seed)");
+        }
+    }
+    return st;
+}
+
 gns_status gns_sample_blocks_async(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
                                    gns_block* blocks, void* hip_stream)
 {
     if (!ctx) return GNS_EINVAL;
-    gns_ctx* c = ctx;
-    const int nl = c->config.num_layers;
-    {
-        const gns_status st = check_batch_args(c, seeds_dev, num_seeds, blocks);
-        if (st != GNS_OK) return st;
-    }
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    {
-        const hipError_t er = before_cache_readers(c, s);
-        if (er == hipErrorInvalidValue) return ctx_fail(c, GNS_ESTATE, "a context may use at most 4 streams between two cache draws");
-        if (er != hipSuccess) return ctx_fail(c, GNS_EHIP, "wait for the cache draw", er);
-    }
-    gns_status st = GNS_OK;
-    if (c->prof_mask == 0 && c->cap_stream) st = launch_batch_graph(c, seed, seeds_dev, num_seeds, blocks, s);
-    else                                     st = enqueue_batch(c, seed, seeds_dev, num_seeds, blocks, s);
-    if (st != GNS_OK) return st;
-    c->batch_id += 1;
-    c->hash_parity ^= 1;             // this batch has left the other map empty
-    for (int i = 0; i < nl; ++i) {
-        blocks[i].num_dst = GNS_DEVICE_COUNTS(i);
-        blocks[i].num_src = -1;
-        blocks[i].num_edges = -1;
-    }
-    return GNS_OK;
+    return gns_sample_blocks_group(&ctx, 1, &seed, &seeds_dev, &num_seeds, &blocks, hip_stream);
 }
 
 gns_status gns_sample_blocks_wait(gns_ctx* ctx, gns_block* blocks, void* hip_stream)
 {
     if (!ctx) return GNS_EINVAL;
-    gns_ctx* c = ctx;
-    if (!blocks) return ctx_fail(c, GNS_EINVAL, "null blocks");
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s);
-    if (e == hipSuccess) e = hipStreamSynchronize(s);
-    if (e != hipSuccess) return ctx_fail(c, GNS_EHIP, "sample_blocks wait", e);
-    for (int i = 0; i < c->config.num_layers; ++i) {
-        blocks[i].num_dst = c->h_state->num_dst[i];
-        blocks[i].num_src = c->h_state->num_dst[i + 1];
-        blocks[i].num_edges = c->h_state->num_edges[i];
-    }
-    // bad_seed holds the id of the latest mini-batch that had a bad seed: anything newer than the last one
-    // reported means that a batch enqueued since the previous wait (not necessarily the last one) was bad
-    if (c->h_state->bad_seed != c->bad_reported) {
-        c->bad_reported = c->h_state->bad_seed;
-        return ctx_fail(c, GNS_EINVAL, "seeds must be distinct node ids in [0, num_nodes) (a mini-batch enqueued since the last wait had a bad seed)");
-    }
-    return GNS_OK;
+    return gns_sample_blocks_group_wait(&ctx, 1, &blocks, hip_stream);
 }
 
 gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds,
@@ -767,22 +874,67 @@ gns_status gns_sample_blocks(gns_ctx* ctx, uint64_t seed, const int32_t* seeds_d
     return gns_sample_blocks_wait(ctx, blocks, hip_stream);
 }
 
+gns_status gns_gather_features_group(gns_ctx* const* ctxs, int32_t count, const int32_t* const* nodes_dev,
+                                     const int32_t* num_nodes, float* const* out_dev, void* hip_stream)
+{
+    gns_status st = check_group(ctxs, count);
+    if (st != GNS_OK) return st;
+    gns_ctx* lead = ctxs[0];
+    if (lead->graph.feat_dim <= 0) return ctx_fail(lead, GNS_ESTATE, "the graph was created without features");
+    if (!nodes_dev || !num_nodes || !out_dev) return ctx_fail(lead, GNS_EINVAL, "null argument array");
+    bool any = false;
+    for (int b = 0; b < count; ++b) {
+        if (num_nodes[b] == 0) continue;
+        any = true;
+        if (!nodes_dev[b] || !out_dev[b]) return ctx_fail(lead, GNS_EINVAL, "null nodes or output");
+    }
+    if (!any) return GNS_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    st = group_before_cache_readers(ctxs, count, s);
+    if (st != GNS_OK) return st;
+    StageTimer t(lead, GNS_STAGE_GATHER, s);
+    hipError_t e = launch_gather(ctxs, count, nodes_dev, num_nodes, out_dev, active_gen(lead), s);
+    if (e != hipSuccess) return ctx_fail(lead, GNS_EHIP, "gather launch", e);
+    return GNS_OK;
+}
+
 gns_status gns_gather_features(gns_ctx* ctx, const int32_t* nodes_dev, int32_t num_nodes, float* out_dev,
                                void* hip_stream)
 {
     if (!ctx) return GNS_EINVAL;
-    if (ctx->graph.feat_dim <= 0) return ctx_fail(ctx, GNS_ESTATE, "the graph was created without features");
-    if (num_nodes == 0) return GNS_OK;
-    if (!nodes_dev || !out_dev) return ctx_fail(ctx, GNS_EINVAL, "null nodes or output");
-    {
-        const hipError_t er = before_cache_readers(ctx, static_cast<hipStream_t>(hip_stream));
-        if (er == hipErrorInvalidValue) return ctx_fail(ctx, GNS_ESTATE, "a context may use at most 4 streams between two cache draws");
-        if (er != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "wait for the cache draw", er);
+    return gns_gather_features_group(&ctx, 1, &nodes_dev, &num_nodes, &out_dev, hip_stream);
+}
+
+gns_status gns_aggregate_group(gns_ctx* const* ctxs, int32_t count, const gns_block* const* blocks,
+                               const float* const* x_src_dev, int32_t feat_dim, float* const* out_dev, void* hip_stream)
+{
+    gns_status st = check_group(ctxs, count);
+    if (st != GNS_OK) return st;
+    gns_ctx* lead = ctxs[0];
+    if (!blocks || !x_src_dev || !out_dev) return ctx_fail(lead, GNS_EINVAL, "null argument array");
+    if (feat_dim < 1) return ctx_fail(lead, GNS_EINVAL, "feat_dim must be >= 1");
+    for (int b = 0; b < count; ++b) {
+        const gns_block* block = blocks[b];
+        if (!block || !x_src_dev[b] || !out_dev[b]) return ctx_fail(lead, GNS_EINVAL, "null block, input or output");
+        if (block->num_dst < 0) {
+            if (-1 - block->num_dst >= lead->config.num_layers) return ctx_fail(lead, GNS_EINVAL, "bad device-count placeholder");
+        } else if (block->num_src < block->num_dst || block->num_edges < 0) {
+            return ctx_fail(lead, GNS_EINVAL, "block counts are inconsistent");
+        }
+        if (!block->indptr || !block->indices || !block->weights) return ctx_fail(lead, GNS_EINVAL, "block has a null buffer");
     }
-    StageTimer t(ctx, GNS_STAGE_GATHER, static_cast<hipStream_t>(hip_stream));
-    hipError_t e = launch_gather(ctx, nodes_dev, num_nodes, out_dev, active_gen(ctx), static_cast<hipStream_t>(hip_stream));
-    if (e != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "gather launch", e);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    StageTimer t(lead, GNS_STAGE_AGGREGATE, s);
+    hipError_t e = launch_aggregate(ctxs, count, blocks, x_src_dev, feat_dim, out_dev, s);
+    if (e != hipSuccess) return ctx_fail(lead, GNS_EHIP, "aggregate launch", e);
     return GNS_OK;
+}
+
+gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_src_dev, int32_t feat_dim,
+                         float* out_dev, void* hip_stream)
+{
+    if (!ctx) return GNS_EINVAL;
+    return gns_aggregate_group(&ctx, 1, &block, &x_src_dev, feat_dim, &out_dev, hip_stream);
 }
 
 gns_status gns_sage_dense(gns_ctx* ctx, const float* h_self_dev, int32_t f1, const float* h_neigh_dev, int32_t f2,
@@ -801,24 +953,6 @@ gns_status gns_sage_dense(gns_ctx* ctx, const float* h_self_dev, int32_t f1, con
     hipError_t e = launch_sage_dense(ctx, h_self_dev, f1, h_neigh_dev, f2, w_dev, bias_dev, hdim, relu, out_dev, num_rows,
                                      static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "dense launch", e);
-    return GNS_OK;
-}
-
-gns_status gns_aggregate(gns_ctx* ctx, const gns_block* block, const float* x_src_dev, int32_t feat_dim,
-                         float* out_dev, void* hip_stream)
-{
-    if (!ctx) return GNS_EINVAL;
-    if (!block || !x_src_dev || !out_dev) return ctx_fail(ctx, GNS_EINVAL, "null block, input or output");
-    if (feat_dim < 1) return ctx_fail(ctx, GNS_EINVAL, "feat_dim must be >= 1");
-    if (block->num_dst < 0) {
-        if (-1 - block->num_dst >= ctx->config.num_layers) return ctx_fail(ctx, GNS_EINVAL, "bad device-count placeholder");
-    } else if (block->num_src < block->num_dst || block->num_edges < 0) {
-        return ctx_fail(ctx, GNS_EINVAL, "block counts are inconsistent");
-    }
-    if (!block->indptr || !block->indices || !block->weights) return ctx_fail(ctx, GNS_EINVAL, "block has a null buffer");
-    StageTimer t(ctx, GNS_STAGE_AGGREGATE, static_cast<hipStream_t>(hip_stream));
-    hipError_t e = launch_aggregate(ctx, block, x_src_dev, feat_dim, out_dev, static_cast<hipStream_t>(hip_stream));
-    if (e != hipSuccess) return ctx_fail(ctx, GNS_EHIP, "aggregate launch", e);
     return GNS_OK;
 }
 

@@ -483,7 +483,10 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, bool wait
         GNS_HIP_TRY(launch_flag_all_entries(c, gen, s), "flag all entries");
     if (c->graph.feat_dim > 0) {
         // fill the device table of cached feature rows (slot order) straight from the full store
-        GNS_HIP_TRY(launch_gather(c, x.cache_nodes, (int32_t) C, cache_ptr<float>(c, L.cache_feat, gen), -1, s), "cache feature fill");
+        const int32_t* fill_nodes = x.cache_nodes;
+        const int32_t fill_count = (int32_t) C;
+        float* fill_out = cache_ptr<float>(c, L.cache_feat, gen);
+        GNS_HIP_TRY(launch_gather(&c, 1, &fill_nodes, &fill_count, &fill_out, -1, s), "cache feature fill");
     }
     GNS_HIP_TRY(hipEventRecord(c->ready_event[gen], s), "event record");
     c->pending = true;

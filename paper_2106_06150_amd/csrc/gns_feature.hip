@@ -5,6 +5,7 @@
 // lanes owns one row and moves it with 128-bit accesses.
 #include "gns_internal.h"
 #include "gns_device.hpp"
+#include <string.h>
 
 namespace gns {
 
@@ -18,13 +19,19 @@ __device__ __forceinline__ void store_streaming(float4* p, const float4& v)
     __builtin_nontemporal_store(v.w, &p->w);
 }
 
-struct GatherArgs {
+// One launch serves a group of mini-batches: blockIdx.y picks the batch.
+struct GatherBatch {
     const int32_t* nodes;
-    int32_t num_nodes;
     const int32_t* num_nodes_dev;   // if not null the count is read here (num_nodes is then the worst case)
+    float* out;
+    int32_t num_nodes;
+    int32_t pad;
+};
+
+struct GatherArgs {
+    GatherBatch b[GNS_MAX_GROUP];
     int64_t n;
     int32_t feat_dim;
-    float* out;
     int32_t use_cache;
     const uint64_t* cache_bitmap;
     const int32_t* cache_prefix;
@@ -41,9 +48,10 @@ __global__ void __launch_bounds__(kBlock) k_gather(GatherArgs a)
     const int64_t group = (int64_t) blockIdx.x * groups_per_block + threadIdx.x / kLanes;
     const int64_t num_groups = (int64_t) gridDim.x * groups_per_block;
     const int64_t F = a.feat_dim;
-    const int64_t count = a.num_nodes_dev ? (int64_t) *a.num_nodes_dev : (int64_t) a.num_nodes;
+    const GatherBatch q = a.b[blockIdx.y];
+    const int64_t count = q.num_nodes_dev ? (int64_t) *q.num_nodes_dev : (int64_t) q.num_nodes;
     for (int64_t row = group; row < count; row += num_groups) {
-        const int32_t u = a.nodes[row];
+        const int32_t u = q.nodes[row];
         const bool valid = u >= 0 && (int64_t) u < a.n;
         const float* src = nullptr;
         if (valid) {
@@ -52,7 +60,7 @@ __global__ void __launch_bounds__(kBlock) k_gather(GatherArgs a)
             else
                 src = a.store + (int64_t) u * F;
         }
-        float* dst = a.out + row * F;
+        float* dst = q.out + row * F;
         if (kVec) {
             const float4* s4 = reinterpret_cast<const float4*>(src);
             float4* d4 = reinterpret_cast<float4*>(dst);
@@ -72,33 +80,43 @@ static inline int lanes_for(int64_t units)
 }
 
 template <bool kVec>
-static void gather_dispatch(int lanes, unsigned blocks, hipStream_t s, const GatherArgs& a)
+static void gather_dispatch(int lanes, dim3 blocks, hipStream_t s, const GatherArgs& a)
 {
     switch (lanes) {
-        case 4:  hipLaunchKernelGGL((k_gather<4, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
-        case 8:  hipLaunchKernelGGL((k_gather<8, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
-        case 16: hipLaunchKernelGGL((k_gather<16, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
-        case 32: hipLaunchKernelGGL((k_gather<32, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
-        default: hipLaunchKernelGGL((k_gather<64, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
+        case 4:  hipLaunchKernelGGL((k_gather<4, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        case 8:  hipLaunchKernelGGL((k_gather<8, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        case 16: hipLaunchKernelGGL((k_gather<16, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        case 32: hipLaunchKernelGGL((k_gather<32, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        default: hipLaunchKernelGGL((k_gather<64, kVec>), blocks, dim3(kBlock), 0, s, a); break;
     }
 }
 
-hipError_t launch_gather(gns_ctx* c, const int32_t* nodes, int32_t num_nodes, float* out, int use_cache_gen,
-                         hipStream_t s)
+// count mini-batches (contexts ctxs[0..count) of one family) in one launch.  num_nodes[b] < 0: the input
+// nodes of the last batch sampled on ctxs[b], counted on the device.
+hipError_t launch_gather(gns_ctx* const* ctxs, int count, const int32_t* const* nodes, const int32_t* num_nodes,
+                         float* const* out, int use_cache_gen, hipStream_t s)
 {
-    if (num_nodes == 0) return hipSuccess;
+    gns_ctx* c = ctxs[0];
     const Layout& L = c->lay;
     GatherArgs a;
-    a.nodes = nodes;
-    a.num_nodes_dev = nullptr;
-    if (num_nodes < 0) {            // input nodes of the last sampled batch, counted on the device
-        a.num_nodes_dev = &c->d_state->num_dst[c->config.num_layers];
-        num_nodes = (int32_t) L.rows[c->config.num_layers];
+    memset(&a, 0, sizeof(a));
+    int64_t most = 0;
+    bool aligned = true;
+    for (int b = 0; b < count; ++b) {
+        GatherBatch& q = a.b[b];
+        q.nodes = nodes[b];
+        q.out = out[b];
+        q.num_nodes = num_nodes[b];
+        if (num_nodes[b] < 0) {
+            q.num_nodes_dev = &ctxs[b]->d_state->num_dst[c->config.num_layers];
+            q.num_nodes = (int32_t) L.rows[c->config.num_layers];
+        }
+        if (q.num_nodes > most) most = q.num_nodes;
+        aligned = aligned && (reinterpret_cast<uintptr_t>(out[b]) & 15u) == 0;
     }
-    a.num_nodes = num_nodes;
+    if (most == 0) return hipSuccess;
     a.n = c->graph.num_nodes;
     a.feat_dim = c->graph.feat_dim;
-    a.out = out;
     const int gen = use_cache_gen < 0 ? 0 : use_cache_gen;
     a.use_cache = (use_cache_gen >= 0 && c->uses_cache && c->root->cache_valid) ? 1 : 0;
     a.cache_bitmap = cache_ptr<uint64_t>(c, L.cache_bitmap, gen);
@@ -106,35 +124,47 @@ hipError_t launch_gather(gns_ctx* c, const int32_t* nodes, int32_t num_nodes, fl
     a.cache_feat = cache_ptr<float>(c, L.cache_feat, gen);
     a.store = c->graph.feat_dev ? c->graph.feat_dev : c->graph.feat_host_pinned;
     const int64_t F = a.feat_dim;
-    const bool vec = (F % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.store) & 15u) == 0) &&
-                     ((reinterpret_cast<uintptr_t>(out) & 15u) == 0);
+    const bool vec = (F % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.store) & 15u) == 0) && aligned;
     const int lanes = lanes_for(vec ? F / 4 : F);
     const int64_t groups_per_block = kBlock / lanes;
-    int64_t blocks = (num_nodes + groups_per_block - 1) / groups_per_block;
+    int64_t blocks = (most + groups_per_block - 1) / groups_per_block;
     const int64_t cap = (int64_t) c->num_cus * 16;
     if (blocks > cap) blocks = cap;
-    if (vec) gather_dispatch<true>(lanes, (unsigned) blocks, s, a);
-    else     gather_dispatch<false>(lanes, (unsigned) blocks, s, a);
+    const dim3 grid((unsigned) blocks, (unsigned) count);
+    if (vec) gather_dispatch<true>(lanes, grid, s, a);
+    else     gather_dispatch<false>(lanes, grid, s, a);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
-struct AggArgs {
+struct AggBatch {
     const int32_t* indptr;
     const int32_t* indices;
     const float* weights;
     const float* x_src;
     float* out;
-    int32_t num_dst;
     const int32_t* num_dst_dev;     // if not null the row count is read here
-    int32_t num_src;                // rows of x_src; an edge whose index lies outside is skipped
     const int32_t* num_src_dev;
+    int32_t num_dst;
+    int32_t num_src;                // rows of x_src; an edge whose index lies outside is skipped
+};
+
+struct AggGroup {
+    AggBatch b[GNS_MAX_GROUP];
+    int32_t feat_dim;
+};
+
+// the view of one batch the kernel body works on
+struct AggArgs : AggBatch {
     int32_t feat_dim;
 };
 
 template <int kLanes, bool kVec>
-__global__ void __launch_bounds__(kBlock) k_aggregate(AggArgs a)
+__global__ void __launch_bounds__(kBlock) k_aggregate(AggGroup g)
 {
+    AggArgs a;
+    static_cast<AggBatch&>(a) = g.b[blockIdx.y];
+    a.feat_dim = g.feat_dim;
     const int lane = (int) (threadIdx.x % kLanes);
     const int64_t groups_per_block = kBlock / kLanes;
     const int64_t group = (int64_t) blockIdx.x * groups_per_block + threadIdx.x / kLanes;
@@ -263,49 +293,58 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggArgs a)
 }
 
 template <bool kVec>
-static void aggregate_dispatch(int lanes, unsigned blocks, hipStream_t s, const AggArgs& a)
+static void aggregate_dispatch(int lanes, dim3 blocks, hipStream_t s, const AggGroup& a)
 {
     switch (lanes) {
-        case 4:  hipLaunchKernelGGL((k_aggregate<4, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
-        case 8:  hipLaunchKernelGGL((k_aggregate<8, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
-        case 16: hipLaunchKernelGGL((k_aggregate<16, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
-        case 32: hipLaunchKernelGGL((k_aggregate<32, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
-        default: hipLaunchKernelGGL((k_aggregate<64, kVec>), dim3(blocks), dim3(kBlock), 0, s, a); break;
+        case 4:  hipLaunchKernelGGL((k_aggregate<4, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        case 8:  hipLaunchKernelGGL((k_aggregate<8, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        case 16: hipLaunchKernelGGL((k_aggregate<16, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        case 32: hipLaunchKernelGGL((k_aggregate<32, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        default: hipLaunchKernelGGL((k_aggregate<64, kVec>), blocks, dim3(kBlock), 0, s, a); break;
     }
 }
 
-hipError_t launch_aggregate(gns_ctx* c, const gns_block* blk, const float* x_src, int32_t feat_dim, float* out,
-                            hipStream_t s)
+hipError_t launch_aggregate(gns_ctx* const* ctxs, int count, const gns_block* const* blks, const float* const* x_src,
+                            int32_t feat_dim, float* const* out, hipStream_t s)
 {
-    if (blk->num_dst == 0 || feat_dim == 0) return hipSuccess;
-    AggArgs a;
-    int32_t rows = blk->num_dst;
-    a.num_dst_dev = nullptr;
-    a.num_src_dev = nullptr;
-    a.num_src = blk->num_src;
-    if (rows < 0) {                 // GNS_DEVICE_COUNTS(layer): rows counted on the device
-        const int layer = -1 - rows;
-        a.num_dst_dev = &c->d_state->num_dst[layer];
-        a.num_src_dev = &c->d_state->num_dst[layer + 1];
-        rows = (int32_t) c->lay.rows[layer];
+    gns_ctx* c = ctxs[0];
+    if (feat_dim == 0) return hipSuccess;
+    AggGroup a;
+    memset(&a, 0, sizeof(a));
+    int64_t most = 0;
+    bool aligned = true;
+    for (int b = 0; b < count; ++b) {
+        const gns_block* blk = blks[b];
+        AggBatch& q = a.b[b];
+        int32_t rows = blk->num_dst;
+        q.num_src = blk->num_src;
+        if (rows < 0) {                 // GNS_DEVICE_COUNTS(layer): rows counted on the device
+            const int layer = -1 - rows;
+            q.num_dst_dev = &ctxs[b]->d_state->num_dst[layer];
+            q.num_src_dev = &ctxs[b]->d_state->num_dst[layer + 1];
+            rows = (int32_t) c->lay.rows[layer];
+        }
+        q.indptr = blk->indptr;
+        q.indices = blk->indices;
+        q.weights = blk->weights;
+        q.x_src = x_src[b];
+        q.out = out[b];
+        q.num_dst = rows;
+        if (rows > most) most = rows;
+        aligned = aligned && ((reinterpret_cast<uintptr_t>(x_src[b]) | reinterpret_cast<uintptr_t>(out[b])) & 15u) == 0;
     }
-    a.indptr = blk->indptr;
-    a.indices = blk->indices;
-    a.weights = blk->weights;
-    a.x_src = x_src;
-    a.out = out;
-    a.num_dst = rows;
+    if (most == 0) return hipSuccess;
     a.feat_dim = feat_dim;
     const int64_t F = feat_dim;
-    const bool vec = (F % 4 == 0) && ((reinterpret_cast<uintptr_t>(x_src) & 15u) == 0) &&
-                     ((reinterpret_cast<uintptr_t>(out) & 15u) == 0);
+    const bool vec = (F % 4 == 0) && aligned;
     const int lanes = lanes_for(vec ? F / 4 : F);
     const int64_t groups_per_block = kBlock / lanes;
-    int64_t blocks = (rows + groups_per_block - 1) / groups_per_block;
+    int64_t blocks = (most + groups_per_block - 1) / groups_per_block;
     const int64_t cap = (int64_t) c->num_cus * 16;
     if (blocks > cap) blocks = cap;
-    if (vec) aggregate_dispatch<true>(lanes, (unsigned) blocks, s, a);
-    else     aggregate_dispatch<false>(lanes, (unsigned) blocks, s, a);
+    const dim3 grid((unsigned) blocks, (unsigned) count);
+    if (vec) aggregate_dispatch<true>(lanes, grid, s, a);
+    else     aggregate_dispatch<false>(lanes, grid, s, a);
     return hipGetLastError();
 }
 

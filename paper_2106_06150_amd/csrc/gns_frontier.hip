@@ -19,6 +19,7 @@
 //            next batch will use)
 // Sorted order comes from walking the bitmap, so the result does not depend on
 // the order in which threads ran.
+#include <string.h>
 #include "gns_kernels.hpp"
 
 namespace gns {
@@ -60,93 +61,111 @@ hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s)
 }
 
 // ---------------------------------------------------------------------------
-// First kernel of a mini-batch: publishes the batch's scalars (number of seeds, Philox key) in
-// the device state, copies the seeds into the context and inserts them, with their local ids, into
-// this batch's hash map.  The
+// First kernel of a mini-batch: publishes the batch's scalars (number of seeds, Philox key, which hash map
+// it uses, which copy of the cache structures it reads) in the device state, copies the seeds into the
+// context and inserts them, with their local ids, into this batch's hash map.  The
 // map is already empty: the context keeps two, and every batch empties the other one for its
 // successor (see k_relabel_last).  A bad seed is reported by stamping the batch id, so no flag
 // needs resetting while other blocks may be setting it.
-struct BeginArgs {
-    unsigned long long* slots;
-    DeviceState* st;
-    const int32_t* seeds;
-    int64_t num_nodes;
-    uint32_t hmask, hshift;
-    RowExtent* row_ext;
-    const void* g_indptr;
-    int g_i64;
-    int32_t* hub_rows;
-    int32_t* seed_copy;
-    uint32_t* slot_list;
-};
-
-__global__ void __launch_bounds__(kBlock) k_batch_begin(BeginArgs a, int32_t num_seeds, uint32_t key0, uint32_t key1,
-                                                        uint32_t batch_id)
+__global__ void __launch_bounds__(kBlock) k_batch_begin(LayerArgs g, BeginDyn d)
 {
+    const int b = (int) blockIdx.y;
+    char* ws = g.b[b].ws;
+    DeviceState* st = at<DeviceState>(ws, g.off.state);
+    const int parity = d.parity[b];
+    const int32_t num_seeds = d.num_seeds[b];
+    const int32_t* seeds = d.seeds[b];
+    const uint32_t batch_id = d.batch_id[b];
+    unsigned long long* slots = at<unsigned long long>(ws, g.off.hash_slots[parity]);
+    uint32_t* slot_list = at<uint32_t>(ws, g.off.slot_list[parity]);
+    RowExtent* row_ext = at<RowExtent>(ws, g.off.row_ext);
+    int32_t* hub_rows = g.off.uses_cache ? at<int32_t>(ws, g.off.hub_rows) : nullptr;
+    int32_t* seed_copy = at<int32_t>(ws, g.off.seed_copy);
     const int64_t t = (int64_t) blockIdx.x * blockDim.x + threadIdx.x;
     if (t == 0) {
-        a.st->num_dst[0] = num_seeds;
-        for (int l = 0; l < GNS_MAX_LAYERS; ++l) { a.st->num_edges[l] = 0; a.st->num_dst[l + 1] = 0; }
-        a.st->key0 = key0;
-        a.st->key1 = key1;
+        st->num_dst[0] = num_seeds;
+        for (int l = 0; l < GNS_MAX_LAYERS; ++l) { st->num_edges[l] = 0; st->num_dst[l + 1] = 0; }
+        st->key0 = d.key0[b];
+        st->key1 = d.key1[b];
+        st->hash_parity = parity;
+        st->cache_gen = d.cache_gen[b];
     }
     for (int64_t q = t; q < num_seeds; q += (int64_t) gridDim.x * blockDim.x) {
-        const int32_t u = a.seeds[q];
-        const bool in_range = u >= 0 && (int64_t) u < a.num_nodes;
+        const int32_t u = seeds[q];
+        const bool in_range = u >= 0 && (int64_t) u < g.f.num_nodes;
         RowExtent ext = {0, 0};
         if (in_range) {
-            ext.start = load_off_rt(a.g_indptr, a.g_i64, u);
-            ext.end = load_off_rt(a.g_indptr, a.g_i64, (int64_t) u + 1);
+            ext.start = load_off_rt(g.f.g_indptr, g.f.g_i64, u);
+            ext.end = load_off_rt(g.f.g_indptr, g.f.g_i64, (int64_t) u + 1);
         }
-        a.seed_copy[q] = u;
-        a.row_ext[q] = ext;
-        append_hub_rows(a.st, a.hub_rows, is_hub_extent(ext.start, ext.end), (int32_t) q);
-        const int64_t slot = in_range ? hash_insert(a.slots, a.hmask, a.hshift, (uint32_t) u, (uint32_t) q) : -1;
-        a.slot_list[q] = slot >= 0 ? (uint32_t) slot : 0xFFFFFFFFu;
-        if (slot < 0) a.st->bad_seed = batch_id;
+        seed_copy[q] = u;
+        row_ext[q] = ext;
+        append_hub_rows(st, hub_rows, is_hub_extent(ext.start, ext.end), (int32_t) q);
+        const int64_t slot = in_range ? hash_insert(slots, g.f.hmask, g.f.hshift, (uint32_t) u, (uint32_t) q) : -1;
+        slot_list[q] = slot >= 0 ? (uint32_t) slot : 0xFFFFFFFFu;
+        if (slot < 0) st->bad_seed = batch_id;
     }
 }
 
 const void* batch_first_kernel() { return reinterpret_cast<const void*>(&k_batch_begin); }
 
-static inline unsigned long long* batch_hash(gns_ctx* c) { return ws_ptr<unsigned long long>(c, c->lay.hash_slots[c->hash_parity]); }
-
-void fill_begin_args(gns_ctx* c, const int32_t* seeds, BeginArgsHost* out)
+void fill_group_args(const Group& g, LayerArgs* out)
 {
+    gns_ctx* c = g.ctx[0];
     const Layout& L = c->lay;
-    BeginArgs* a = reinterpret_cast<BeginArgs*>(out->bytes);
-    static_assert(sizeof(BeginArgs) <= sizeof(out->bytes), "BeginArgsHost too small");
-    a->slots = batch_hash(c);
-    a->st = c->d_state;
-    a->seeds = seeds;
-    a->num_nodes = c->graph.num_nodes;
-    a->hmask = L.hash_cap - 1;
-    a->hshift = 32u - (uint32_t) __builtin_ctz(L.hash_cap);
-    a->row_ext = ws_ptr<RowExtent>(c, L.row_ext);
-    a->g_indptr = c->graph.indptr;
-    a->g_i64 = c->graph.indptr_is_i64;
-    a->hub_rows = c->uses_cache ? ws_ptr<int32_t>(c, L.hub_rows) : nullptr;
-    a->seed_copy = ws_ptr<int32_t>(c, L.seed_copy);
-    a->slot_list = ws_ptr<uint32_t>(c, L.slot_list[c->hash_parity]);
+    memset(out, 0, sizeof(*out));
+    WsOffsets& o = out->off;
+    o.state = L.state; o.mark = L.mark_bitmap; o.seed_copy = L.seed_copy; o.row_ext = L.row_ext; o.hub_rows = L.hub_rows;
+    for (int p = 0; p < 2; ++p) {
+        o.slot_list[p] = L.slot_list[p]; o.hash_slots[p] = L.hash_slots[p];
+        o.s_nbr[p] = L.s_nbr[p]; o.s_w[p] = L.s_w[p]; o.s_cnt[p] = L.s_cnt[p];
+    }
+    o.plan_cnt = L.plan_cnt; o.plan_g0 = L.plan_g0; o.plan_desc = L.plan_desc;
+    o.sums_rows = L.sums_rows; o.sums_marks = L.sums_marks; o.sums_plan = L.sums_plan;
+    o.cache_block_bytes = L.cache_block_bytes;
+    o.uses_cache = c->uses_cache ? 1 : 0;
+    for (int b = 0; b < kMaxGroup; ++b) out->b[b].ws = g.ctx[b < g.count ? b : 0]->ws;
 }
 
-hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, uint32_t batch_id,
-                              hipStream_t s)
+static inline BlockPtrs block_ptrs(const gns_block& k)
 {
-    BeginArgsHost h;
-    fill_begin_args(c, seeds, &h);
-    const BeginArgs a = *reinterpret_cast<const BeginArgs*>(h.bytes);
+    BlockPtrs p;
+    p.indptr = k.indptr; p.indices = k.indices; p.src_nodes = k.src_nodes; p.row_eligible = k.row_eligible; p.weights = k.weights;
+    return p;
+}
+
+void set_group_layer(const Group& g, int layer_index, LayerArgs* out)
+{
+    for (int b = 0; b < g.count; ++b) {
+        gns_ctx* c = g.ctx[b];
+        BatchSlot& q = out->b[b];
+        const int32_t* seed_copy = ws_ptr<int32_t>(c, c->lay.seed_copy);
+        const gns_block* blk = g.blocks[b];
+        q.dst = layer_index == 0 ? seed_copy : blk[layer_index - 1].src_nodes;
+        q.prev_dst = layer_index <= 1 ? seed_copy : blk[layer_index - 2].src_nodes;
+        q.cur = block_ptrs(blk[layer_index]);
+        q.prev = block_ptrs(blk[layer_index > 0 ? layer_index - 1 : 0]);
+    }
+}
+
+// Enqueues the first kernel of a group of mini-batches.
+hipError_t launch_batch_begin(const Group& g, const BeginDyn& d, hipStream_t s)
+{
+    gns_ctx* c = g.ctx[0];
+    LayerArgs a;
+    fill_group_args(g, &a);
+    fill_finish_template(c, 0, &a.f);
     // the grid is sized for the largest batch: the same launch serves every replay
     const unsigned grid = (unsigned) ((c->config.max_seeds + kBlock - 1) / kBlock);
-    hipLaunchKernelGGL(k_batch_begin, dim3(grid), dim3(kBlock), 0, s, a, num_seeds, (uint32_t) seed,
-                       (uint32_t) (seed >> 32), batch_id);
+    hipLaunchKernelGGL(k_batch_begin, dim3(grid, (unsigned) g.count), dim3(kBlock), 0, s, a, d);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(kBlock) k_finish_phase1(FinishArgs a)
+__global__ void __launch_bounds__(kBlock) k_finish_phase1(LayerArgs g)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
+    const FinishArgs a = bind_finish(g, (int) blockIdx.y, true);
     const int32_t R = a.st->num_dst[a.layer_index];
     if ((int32_t) blockIdx.x < a.row_tiles_max) {
         const int64_t base = (int64_t) blockIdx.x * kTile;
@@ -180,9 +199,10 @@ __device__ __forceinline__ int32_t block_sum_array(const int32_t* vals, int32_t 
 
 // Phase 3 needs each tile's offset = the sum of the earlier tiles' sums.  Every block adds
 // those up itself (at most a few thousand values), which saves a single-block scan kernel.
-__global__ void __launch_bounds__(kBlock) k_finish_phase3(FinishArgs a)
+__global__ void __launch_bounds__(kBlock) k_finish_phase3(LayerArgs g)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
+    const FinishArgs a = bind_finish(g, (int) blockIdx.y, true);
     __shared__ int32_t s_off[kMarkTileMax + 1];
     __shared__ uint64_t s_word[kMarkTileMax];
     const int32_t R = a.st->num_dst[a.layer_index];
@@ -270,39 +290,23 @@ __global__ void __launch_bounds__(kBlock) k_finish_phase3(FinishArgs a)
     }
 }
 
-void fill_finish_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, const gns_block* blk, FinishArgs* out)
+void fill_finish_template(gns_ctx* c, int layer_index, FinishArgs* out)
 {
     const Layout& L = c->lay;
     FinishArgs& a = *out;
-    const int par = layer_index & 1;                 // sampler scratch is double-buffered by layer parity
-    a.st = c->d_state;
+    memset(&a, 0, sizeof(a));
     a.layer_index = layer_index;
     a.fanout = c->config.fanout[layer_index];
-    a.dst_nodes = dst_nodes;
-    a.s_nbr = ws_ptr<int32_t>(c, L.s_nbr[par]);
-    a.s_w = ws_ptr<float>(c, L.s_w[par]);
-    a.s_cnt = ws_ptr<int32_t>(c, L.s_cnt[par]);
-    a.mark = ws_ptr<uint64_t>(c, L.mark_bitmap);
     a.words = L.words;
-    a.slots = batch_hash(c);
     a.hmask = L.hash_cap - 1;
     a.hshift = 32u - (uint32_t) __builtin_ctz(L.hash_cap);
-    a.sums_rows = ws_ptr<int32_t>(c, L.sums_rows);
-    a.sums_marks = ws_ptr<int32_t>(c, L.sums_marks);
     a.row_tiles_max = (int32_t) ((L.rows[layer_index] + kTile - 1) / kTile);
     a.mark_tiles = (int32_t) L.mark_tiles;
     a.mark_tile_words = L.mark_tile_words;
-    a.indptr = blk->indptr;
-    a.indices = blk->indices;
-    a.weights = blk->weights;
-    a.src_nodes = blk->src_nodes;
     a.max_slots = L.rows[layer_index] * (int64_t) a.fanout;
-    a.row_ext = ws_ptr<RowExtent>(c, L.row_ext);
     a.g_indptr = c->graph.indptr;
     a.g_i64 = c->graph.indptr_is_i64;
-    a.hub_rows = c->uses_cache ? ws_ptr<int32_t>(c, L.hub_rows) : nullptr;
-    a.slot_list = ws_ptr<uint32_t>(c, L.slot_list[c->hash_parity]);
-    a.parity = c->hash_parity;
+    a.num_nodes = c->graph.num_nodes;
 }
 
 int relabel_grid(const gns_ctx* c, int layer_index)
@@ -315,13 +319,16 @@ int relabel_grid(const gns_ctx* c, int layer_index)
 }
 
 // Phases 1 and 3 of a layer (the relabel rides with the next layer's first kernel).
-hipError_t launch_finish_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s)
+hipError_t launch_finish_layer(const Group& g, int layer_index, hipStream_t s)
 {
-    FinishArgs a;
-    fill_finish_args(c, layer_index, dst_nodes, blk, &a);
-    const unsigned grid = (unsigned) (a.row_tiles_max + a.mark_tiles);
-    hipLaunchKernelGGL(k_finish_phase1, dim3(grid), dim3(kBlock), 0, s, a);
-    hipLaunchKernelGGL(k_finish_phase3, dim3(grid), dim3(kBlock), 0, s, a);
+    gns_ctx* c = g.ctx[0];
+    LayerArgs a;
+    fill_group_args(g, &a);
+    set_group_layer(g, layer_index, &a);
+    fill_finish_template(c, layer_index, &a.f);
+    const dim3 grid((unsigned) (a.f.row_tiles_max + a.f.mark_tiles), (unsigned) g.count);
+    hipLaunchKernelGGL(k_finish_phase1, grid, dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL(k_finish_phase3, grid, dim3(kBlock), 0, s, a);
     return hipGetLastError();
 }
 
@@ -329,15 +336,15 @@ hipError_t launch_finish_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
 // other hash map empty for the next mini-batch (nothing in this batch touches that map).  The map was
 // filled by the batch before this one; every insertion recorded its slot, so emptying it means
 // resetting exactly those slots -- a few hundred KB instead of the whole table.
-__global__ void __launch_bounds__(kBlock) k_relabel_last(FinishArgs a, unsigned long long* other_slots,
-                                                         const uint32_t* other_slot_list, int total_layers)
+__global__ void __launch_bounds__(kBlock) k_relabel_last(LayerArgs g, int total_layers)
 {
+    const FinishArgs a = bind_finish(g, (int) blockIdx.y, true);
     relabel_body(a, blockIdx.x, gridDim.x);
     const int32_t stale = a.st->map_nodes[a.parity ^ 1];
     const size_t stride = (size_t) gridDim.x * kBlock;
     for (size_t i = (size_t) blockIdx.x * kBlock + threadIdx.x; i < (size_t) stale; i += stride) {
-        const uint32_t slot = other_slot_list[i];
-        if (slot != 0xFFFFFFFFu) other_slots[slot] = kEmptySlot;
+        const uint32_t slot = a.other_slot_list[i];
+        if (slot != 0xFFFFFFFFu) a.other_slots[slot] = kEmptySlot;
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         a.st->hub_count = 0;                                     // the next batch starts a new hub list
@@ -345,14 +352,15 @@ __global__ void __launch_bounds__(kBlock) k_relabel_last(FinishArgs a, unsigned 
     }
 }
 
-hipError_t launch_relabel(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s)
+hipError_t launch_relabel(const Group& g, int layer_index, hipStream_t s)
 {
-    FinishArgs a;
-    fill_finish_args(c, layer_index, dst_nodes, blk, &a);
-    const int other = c->hash_parity ^ 1;
-    hipLaunchKernelGGL(k_relabel_last, dim3((unsigned) relabel_grid(c, layer_index)), dim3(kBlock), 0, s, a,
-                       ws_ptr<unsigned long long>(c, c->lay.hash_slots[other]),
-                       ws_ptr<uint32_t>(c, c->lay.slot_list[other]), (int) c->config.num_layers);
+    gns_ctx* c = g.ctx[0];
+    LayerArgs a;
+    fill_group_args(g, &a);
+    set_group_layer(g, layer_index, &a);
+    fill_finish_template(c, layer_index, &a.f);
+    hipLaunchKernelGGL(k_relabel_last, dim3((unsigned) relabel_grid(c, layer_index), (unsigned) g.count), dim3(kBlock), 0, s, a,
+                       (int) c->config.num_layers);
     return hipGetLastError();
 }
 

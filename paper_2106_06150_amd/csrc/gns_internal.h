@@ -24,6 +24,8 @@ struct DeviceState {
     int32_t draw_distinct;                //   nodes in the cache before the current chunk
     int32_t draw_done_chunk;              //   index of the chunk that completed the cache, -1 while incomplete
     int32_t plan_chunks;                  // CACHE_ONLY sampler: aligned chunks in the current work list
+    int32_t hash_parity;                  // which of the two hash maps the current batch uses (set by its first kernel)
+    int32_t cache_gen;                    // which copy of the cache structures it reads (set by its first kernel)
     unsigned long long cut_draw;          // cache draw: stream index of the draw that completed the cache
     unsigned long long walk_total;        // random-walk probability: sum of the weights
     int32_t walk_support;                 //   number of nodes with a non-zero weight
@@ -85,18 +87,28 @@ namespace gns {
 // Streams one context may enqueue mini-batches on between two cache draws (each gets an event the
 // draw after next waits for).
 constexpr int kReaderStreams = 4;
-// Opaque host-side storage for the first kernel's argument block (filled by fill_begin_args).
+struct Group;       // gns_kernels.hpp: the mini-batches one launch sequence serves
+struct BeginDyn;    //   the first kernel's per-replay arguments
+// Opaque host-side storage for the first kernel's two argument blocks (LayerArgs, BeginDyn).
 struct BeginArgsHost {
-    alignas(8) unsigned char bytes[96];
+    alignas(8) unsigned char fixed[2560];
+    alignas(8) unsigned char dyn[512];
 };
-// One captured launch sequence (there is one per hash-map parity).
+// One captured launch sequence of a group of mini-batches, kept by the group's first context.
 struct BatchGraph {
     hipGraph_t graph;
     hipGraphExec_t exec;
     hipGraphNode_t first;            // the k_batch_begin node
     bool valid;
-    gns_block blocks[GNS_MAX_LAYERS];   // capture key: the caller's block buffers
+    uint64_t last_use;
+    // capture key: the contexts of the group and the caller's block buffers
+    int count;
+    gns_ctx* ctx[GNS_MAX_GROUP];
+    gns_block blocks[GNS_MAX_GROUP][GNS_MAX_LAYERS];
+    BeginArgsHost args;              // the first kernel's arguments (the node's parameter list points here)
+    void* arg_ptrs[2];
 };
+constexpr int kGraphsPerContext = 2;
 struct ProfileRecord {
     int32_t stage;
     hipEvent_t start, stop;
@@ -144,16 +156,12 @@ struct gns_ctx {
     // The launch sequence of one mini-batch, captured once per (seeds pointer, block buffers) and
     // replayed; only the first kernel's arguments (seed, number of seeds) change between replays.
     hipStream_t cap_stream;          // used for capture only, never for execution
-    gns::BatchGraph bg[2][2];        // [hash-map parity][cache generation]
+    gns::BatchGraph* bg;             // [kGraphsPerContext] captured launch sequences (least recently used is replaced)
+    uint64_t graph_clock;
     int hash_parity;                 // which hash map the next mini-batch uses
     uint32_t batch_id;               // id of the last mini-batch enqueued on this context (from 1)
     uint32_t bad_reported;           // DeviceState::bad_seed as of the last report to the caller
     gns_ctx* static_child;           // root only: the context of gns_sample_blocks_static (scratch in the library's array)
-    // argument storage of the first kernel (pointed to by the node's parameter list)
-    gns::BeginArgsHost ga_begin;
-    int32_t ga_num_seeds;
-    uint32_t ga_key0, ga_key1, ga_batch_id;
-    void* ga_ptrs[5];
     // optional stage timing (benchmarks only)
     uint32_t prof_mask;
     int32_t prof_capacity;
@@ -198,8 +206,9 @@ static inline hipError_t before_cache_readers(gns_ctx* c, hipStream_t s)
 
 gns_status ctx_fail(gns_ctx* c, gns_status st, const char* what, hipError_t e = hipSuccess);
 // gns_api.hip
-gns_status enqueue_batch(gns_ctx* c, uint64_t seed, const int32_t* seeds_dev, int32_t num_seeds, gns_block* blocks,
-                         hipStream_t s);
+gns_status enqueue_batch(const Group& g, const BeginDyn& d, hipStream_t s);
+void fill_begin_dyn(const Group& g, const uint64_t* seeds, const int32_t* const* seeds_dev, const int32_t* num_seeds,
+                    BeginDyn* out);
 gns_status check_batch_args(gns_ctx* c, const int32_t* seeds_dev, int32_t num_seeds, const gns_block* blocks);
 hipError_t init_batch_scratch(gns_ctx* c, hipStream_t s);
 gns_status make_child(gns_ctx* root, void* workspace, bool with_capture_stream, gns_ctx** out);
@@ -244,26 +253,23 @@ gns_status retire_cache(gns_ctx* c);
 gns_status finish_pending_draw(gns_ctx* c);
 
 // gns_sampler.hip
-// prev_dst / prev_blk: the previous layer, whose relabel shares this layer's first launch (null for layer index 0)
-hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, int32_t* row_eligible,
-                               const int32_t* prev_dst, const gns_block* prev_blk, hipStream_t s);
+// the previous layer's relabel shares this layer's first launch
+hipError_t launch_sample_layer(const Group& g, int layer_index, hipStream_t s);
 hipError_t launch_flag_all_entries(gns_ctx* c, int cache_gen, hipStream_t s);
 
 // gns_frontier.hip
-hipError_t launch_batch_begin(gns_ctx* c, uint64_t seed, const int32_t* seeds, int32_t num_seeds, uint32_t batch_id,
-                              hipStream_t s);
+hipError_t launch_batch_begin(const Group& g, const BeginDyn& d, hipStream_t s);
 const void* batch_first_kernel();
-void fill_begin_args(gns_ctx* c, const int32_t* seeds, BeginArgsHost* out);
-hipError_t launch_relabel(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s);
-hipError_t launch_finish_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, gns_block* blk, hipStream_t s);
+hipError_t launch_relabel(const Group& g, int layer_index, hipStream_t s);
+hipError_t launch_finish_layer(const Group& g, int layer_index, hipStream_t s);
 hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 
 // gns_feature.hip
 // use_cache_gen < 0: every row comes from the full store (used while a cache's own table is being filled)
-hipError_t launch_gather(gns_ctx* c, const int32_t* nodes, int32_t num_nodes, float* out, int use_cache_gen,
-                         hipStream_t s);
-hipError_t launch_aggregate(gns_ctx* c, const gns_block* blk, const float* x_src, int32_t feat_dim, float* out,
-                            hipStream_t s);
+hipError_t launch_gather(gns_ctx* const* ctxs, int count, const int32_t* const* nodes, const int32_t* num_nodes,
+                         float* const* out, int use_cache_gen, hipStream_t s);
+hipError_t launch_aggregate(gns_ctx* const* ctxs, int count, const gns_block* const* blks, const float* const* x_src,
+                            int32_t feat_dim, float* const* out, hipStream_t s);
 
 }  // namespace gns

@@ -19,46 +19,10 @@
 // i < s_cnt[r], row_eligible[r]; every emitted id that has no local id yet
 // (it is not a dst node of this layer) also sets its bit in the node-indexed
 // mark bitmap that the frontier stage turns into the src list.
+#include <string.h>
 #include "gns_kernels.hpp"
 
 namespace gns {
-
-struct SampleArgs {
-    DeviceState* st;
-    int layer_index;
-    uint32_t layer_number;     // the paper's l = L - layer_index
-    int fanout;
-    int wmode;
-    int policy;                // GNS_CACHE_ONLY or GNS_CACHE_FIRST for the select kernel
-    int64_t num_nodes;
-    const void* indptr;
-    const int32_t* indices;
-    const int32_t* dst_nodes;
-    const RowExtent* row_ext;  // CSR extent of every dst row's node (written when the node joined the batch)
-    const float* node_inv_pc;  // 1 / p^C_u for the nodes of the cache
-    const int32_t* hub_rows;   // rows of the batch whose CSR segment spans more than kHubChunks chunks
-    const uint64_t* cache_bitmap;
-    const int32_t* cache_prefix;
-    int64_t cache_size;
-    int32_t* s_nbr;
-    float* s_w;
-    int32_t* s_cnt;
-    int32_t* row_eligible;
-    uint64_t* mark;
-    const unsigned long long* slots;   // batch hash map node -> local id (holds this layer's dst nodes)
-    uint32_t hmask, hshift;
-    // CACHE_ONLY: per-batch plan and the CSR-aligned membership flags
-    int64_t num_entries;
-    int32_t* plan_cnt;         // [rows] aligned 64-entry chunks touched by each dst row
-    int32_t* plan_g0;          // [rows] id of the first of them
-    int32_t* plan_sums;        // [row tiles + 1]
-    int32_t* plan_desc;        // [chunks] ids of the aligned chunks to flag
-    uint64_t* flags;           // [ceil(nnz / 64)] bit e & 63 of word e >> 6: entry e points into the cache
-    int64_t bitmap_words;
-    const uint64_t* coarse_bitmap;   // one bit per 2^coarse_shift ids (flag kernel, mode 2)
-    int64_t coarse_words;
-    int coarse_shift;
-};
 
 // Floyd's subset draw inside a group of G consecutive lanes (G a power of two
 // <= 64).  Lane s < k ends up with one chosen rank of {0..m-1} in *val and that
@@ -111,12 +75,16 @@ __device__ __forceinline__ int32_t mark_if_new(const SampleArgs& a, uint32_t u)
 // ---------------------------------------------------------------------------
 // UNIFORM: G lanes per row, rows assigned round-robin to groups.
 template <int G>
-__global__ void __launch_bounds__(kBlock) k_sample_uniform(SampleArgs a, FinishArgs prev, int relabel_blocks)
+__global__ void __launch_bounds__(kBlock) k_sample_uniform(LayerArgs g, int relabel_blocks)
 {
     // the last relabel_blocks blocks finish the previous layer's block instead (see relabel_body); they are
     // dispatched after this layer's rows, whose dependent loads set the length of the launch
     const int64_t nblocks = (int64_t) gridDim.x - relabel_blocks;
-    if ((int64_t) blockIdx.x >= nblocks) { relabel_body(prev, (int64_t) blockIdx.x - nblocks, relabel_blocks); return; }
+    if ((int64_t) blockIdx.x >= nblocks) {
+        relabel_body(bind_finish(g, (int) blockIdx.y, false), (int64_t) blockIdx.x - nblocks, relabel_blocks);
+        return;
+    }
+    const SampleArgs a = bind_sample(g, (int) blockIdx.y);
     const int64_t block = (int64_t) blockIdx.x;
     const int32_t R = a.st->num_dst[a.layer_index];
     const int k = a.fanout;
@@ -182,11 +150,15 @@ __device__ __forceinline__ int32_t chunks_touched(int64_t start, int64_t end)
 // Plan tiles are kPlanTile rows (one row per thread): many small blocks keep the expansion parallel.
 constexpr int kPlanTile = kBlock;
 
-__global__ void __launch_bounds__(kBlock) k_plan_count(SampleArgs a, FinishArgs prev, int relabel_blocks)
+__global__ void __launch_bounds__(kBlock) k_plan_count(LayerArgs g, int relabel_blocks)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
     const int64_t ntiles = (int64_t) gridDim.x - relabel_blocks;
-    if ((int64_t) blockIdx.x >= ntiles) { relabel_body(prev, (int64_t) blockIdx.x - ntiles, relabel_blocks); return; }
+    if ((int64_t) blockIdx.x >= ntiles) {
+        relabel_body(bind_finish(g, (int) blockIdx.y, false), (int64_t) blockIdx.x - ntiles, relabel_blocks);
+        return;
+    }
+    const SampleArgs a = bind_sample(g, (int) blockIdx.y);
     const int64_t tile = (int64_t) blockIdx.x;
     const int32_t R = a.st->num_dst[a.layer_index];
     const int64_t r = tile * kPlanTile + threadIdx.x;
@@ -203,9 +175,10 @@ __global__ void __launch_bounds__(kBlock) k_plan_count(SampleArgs a, FinishArgs 
     if (threadIdx.x == 0) a.plan_sums[tile] = sum;
 }
 
-__global__ void __launch_bounds__(kBlock) k_plan_expand(SampleArgs a)
+__global__ void __launch_bounds__(kBlock) k_plan_expand(LayerArgs g)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
+    const SampleArgs a = bind_sample(g, (int) blockIdx.y);
     __shared__ int32_t s_off[kPlanTile + 1];
     __shared__ int32_t s_g0[kPlanTile];
     const int32_t R = a.st->num_dst[a.layer_index];
@@ -287,31 +260,10 @@ __device__ __forceinline__ void flag_chunk_set(const SampleArgs& a, const uint32
 
 // kMode 1 / 2: the cache bitmap / its coarse companion is first copied into dynamic LDS (rounded up to
 // 16 bytes).  Every wave takes an equal, contiguous share of the work list.
+// One work list: every wave takes an equal, contiguous share of its Q chunks.
 template <int kMode>
-__global__ void k_flag_chunks(SampleArgs a, int use_plan, int64_t all_chunks)
+__device__ __forceinline__ void flag_work_list(const SampleArgs& a, const uint32_t* lds32, int64_t Q, int use_plan)
 {
-    extern __shared__ uint4 lds_bitmap16[];
-    if (kMode != 0) {
-        const uint4* src = reinterpret_cast<const uint4*>(kMode == 1 ? a.cache_bitmap : a.coarse_bitmap);
-        const int64_t n16 = ((kMode == 1 ? a.bitmap_words : a.coarse_words) + 1) / 2;
-        constexpr int kFill = 4;
-        for (int64_t base = 0; base < n16; base += (int64_t) blockDim.x * kFill) {
-            uint4 v[kFill];
-#pragma unroll
-            for (int i = 0; i < kFill; ++i) {
-                const int64_t q = base + (int64_t) i * blockDim.x + threadIdx.x;
-                v[i] = src[q < n16 ? q : n16 - 1];
-            }
-#pragma unroll
-            for (int i = 0; i < kFill; ++i) {
-                const int64_t q = base + (int64_t) i * blockDim.x + threadIdx.x;
-                if (q < n16) lds_bitmap16[q] = v[i];
-            }
-        }
-        __syncthreads();
-    }
-    const uint32_t* lds32 = reinterpret_cast<const uint32_t*>(lds_bitmap16);
-    const int64_t Q = use_plan ? (int64_t) a.st->plan_chunks : all_chunks;
     if (Q <= 0 || a.num_entries <= 0) return;
     const int waves_per_block = (int) (blockDim.x >> 6);
     const int64_t wave_global = (int64_t) blockIdx.x * waves_per_block +
@@ -336,6 +288,42 @@ __global__ void k_flag_chunks(SampleArgs a, int use_plan, int64_t all_chunks)
             else         flag_chunk_set<kMode, false>(a, lds32, my_chunk, sub, lane, &lo, &hi);
         }
         if (lane < here) a.flags[my_chunk] = ((uint64_t) hi << 32) | lo;
+    }
+}
+
+// kMode 1 / 2: the cache bitmap / its coarse companion is first copied into dynamic LDS (rounded up to
+// 16 bytes).  count > 0: the work lists of the group's `count` mini-batches, one after the other (they read
+// the same cache, so the bitmap is staged once); count == 0: every aligned chunk of the CSR entry array,
+// with the template's own cache pointers (the pass a cache draw runs over the whole graph).
+template <int kMode>
+__global__ void k_flag_chunks(LayerArgs g, int count, int64_t all_chunks)
+{
+    extern __shared__ uint4 lds_bitmap16[];
+    SampleArgs a = count > 0 ? bind_sample(g, 0) : g.s;
+    if (kMode != 0) {
+        const uint4* src = reinterpret_cast<const uint4*>(kMode == 1 ? a.cache_bitmap : a.coarse_bitmap);
+        const int64_t n16 = ((kMode == 1 ? a.bitmap_words : a.coarse_words) + 1) / 2;
+        constexpr int kFill = 4;
+        for (int64_t base = 0; base < n16; base += (int64_t) blockDim.x * kFill) {
+            uint4 v[kFill];
+#pragma unroll
+            for (int i = 0; i < kFill; ++i) {
+                const int64_t q = base + (int64_t) i * blockDim.x + threadIdx.x;
+                v[i] = src[q < n16 ? q : n16 - 1];
+            }
+#pragma unroll
+            for (int i = 0; i < kFill; ++i) {
+                const int64_t q = base + (int64_t) i * blockDim.x + threadIdx.x;
+                if (q < n16) lds_bitmap16[q] = v[i];
+            }
+        }
+        __syncthreads();
+    }
+    const uint32_t* lds32 = reinterpret_cast<const uint32_t*>(lds_bitmap16);
+    if (count == 0) { flag_work_list<kMode>(a, lds32, all_chunks, 0); return; }
+    for (int b = 0; b < count; ++b) {
+        if (b > 0) a = bind_sample(g, b);
+        flag_work_list<kMode>(a, lds32, (int64_t) a.st->plan_chunks, 1);
     }
 }
 
@@ -526,10 +514,14 @@ __device__ __forceinline__ void select_row(const SampleArgs& a, int64_t row, boo
 // and hub_blocks further blocks give each of them a whole wave (64 * kHubWords words per step).
 // Block order: hub blocks, row blocks, relabel blocks of the previous layer.
 template <int G>
-__global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs prev, int relabel_blocks, int hub_blocks)
+__global__ void __launch_bounds__(kBlock) k_select_rows(LayerArgs g, int relabel_blocks, int hub_blocks)
 {
     const int64_t own_blocks = (int64_t) gridDim.x - relabel_blocks;
-    if ((int64_t) blockIdx.x >= own_blocks) { relabel_body(prev, (int64_t) blockIdx.x - own_blocks, relabel_blocks); return; }
+    if ((int64_t) blockIdx.x >= own_blocks) {
+        relabel_body(bind_finish(g, (int) blockIdx.y, false), (int64_t) blockIdx.x - own_blocks, relabel_blocks);
+        return;
+    }
+    const SampleArgs a = bind_sample(g, (int) blockIdx.y);
     const int wave_in_block = __builtin_amdgcn_readfirstlane((int) (threadIdx.x >> 6));
     if ((int) blockIdx.x < hub_blocks) {
         const int32_t H = a.st->hub_count;
@@ -567,36 +559,13 @@ __global__ void __launch_bounds__(kBlock) k_select_rows(SampleArgs a, FinishArgs
     }
 }
 
-static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, int32_t* row_eligible,
-                             int cache_gen, SampleArgs* out);
-
-static void launch_flag_kernel(gns_ctx* c, const SampleArgs& a, int use_plan, int64_t all_chunks, hipStream_t s)
-{
-    const size_t lds_bytes = (size_t) ((c->lay.words + 1) / 2) * 16;
-    const size_t coarse_bytes = (size_t) ((c->lay.coarse_words + 1) / 2) * 16;
-    if (lds_bytes <= c->lds_bitmap_limit)
-        hipLaunchKernelGGL((k_flag_chunks<1>), dim3((unsigned) c->num_cus), dim3(1024), lds_bytes, s, a, use_plan, all_chunks);
-    else if (c->lay.coarse_shift > 0 && coarse_bytes <= c->lds_bitmap_limit)
-        hipLaunchKernelGGL((k_flag_chunks<2>), dim3((unsigned) c->num_cus), dim3(1024), coarse_bytes, s, a, use_plan, all_chunks);
-    else
-        hipLaunchKernelGGL((k_flag_chunks<0>), dim3((unsigned) c->num_cus * 8), dim3(kBlock), 0, s, a, use_plan, all_chunks);
-}
-
-// GNS_FLAGS_PER_CACHE: one pass over every aligned chunk of the CSR entry array.
-hipError_t launch_flag_all_entries(gns_ctx* c, int cache_gen, hipStream_t s)
-{
-    SampleArgs a;
-    fill_sample_args(c, 0, nullptr, nullptr, cache_gen, &a);
-    launch_flag_kernel(c, a, 0, (c->graph.num_entries + 63) / 64, s);
-    return hipGetLastError();
-}
-
-static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nodes, int32_t* row_eligible,
-                             int cache_gen, SampleArgs* out)
+// The cache pointers of the template are those of generation `cache_gen`; kernels that serve mini-batches
+// shift them to the generation each batch reads.
+static void fill_sample_template_gen(gns_ctx* c, int layer_index, int cache_gen, SampleArgs* out)
 {
     const Layout& L = c->lay;
     SampleArgs& a = *out;
-    a.st = c->d_state;
+    memset(&a, 0, sizeof(a));
     a.layer_index = layer_index;
     a.layer_number = (uint32_t) (c->config.num_layers - layer_index);
     a.fanout = c->config.fanout[layer_index];
@@ -605,28 +574,14 @@ static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nod
     a.num_nodes = c->graph.num_nodes;
     a.indptr = c->graph.indptr;
     a.indices = c->graph.indices;
-    a.dst_nodes = dst_nodes;
-    a.row_ext = ws_ptr<RowExtent>(c, L.row_ext);
-    a.hub_rows = ws_ptr<int32_t>(c, L.hub_rows);
     const int gen = cache_gen;
     a.node_inv_pc = c->uses_cache ? cache_ptr<float>(c, L.node_pc, gen) : nullptr;
     a.cache_bitmap = cache_ptr<uint64_t>(c, L.cache_bitmap, gen);
     a.cache_prefix = cache_ptr<int32_t>(c, L.cache_prefix, gen);
     a.cache_size = c->config.cache_size;
-    const int par = layer_index & 1;     // double-buffered: the previous layer's relabel may still read the other half
-    a.s_nbr = ws_ptr<int32_t>(c, L.s_nbr[par]);
-    a.s_w = ws_ptr<float>(c, L.s_w[par]);
-    a.s_cnt = ws_ptr<int32_t>(c, L.s_cnt[par]);
-    a.row_eligible = row_eligible;
-    a.mark = ws_ptr<uint64_t>(c, L.mark_bitmap);
-    a.slots = ws_ptr<unsigned long long>(c, L.hash_slots[c->hash_parity]);
     a.hmask = L.hash_cap - 1;
     a.hshift = 32u - (uint32_t) __builtin_ctz(L.hash_cap);
     a.num_entries = c->graph.num_entries;
-    a.plan_cnt = ws_ptr<int32_t>(c, L.plan_cnt);
-    a.plan_g0 = ws_ptr<int32_t>(c, L.plan_g0);
-    a.plan_sums = ws_ptr<int32_t>(c, L.sums_plan);
-    a.plan_desc = ws_ptr<int32_t>(c, L.plan_desc);
     a.flags = c->uses_cache ? cache_ptr<uint64_t>(c, L.edge_flags, gen) : nullptr;
     a.bitmap_words = L.words;
     a.coarse_bitmap = L.coarse_shift ? cache_ptr<uint64_t>(c, L.coarse_bitmap, gen) : nullptr;
@@ -634,24 +589,54 @@ static void fill_sample_args(gns_ctx* c, int layer_index, const int32_t* dst_nod
     a.coarse_shift = L.coarse_shift;
 }
 
-hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_nodes, int32_t* row_eligible,
-                               const int32_t* prev_dst, const gns_block* prev_blk, hipStream_t s)
+void fill_sample_template(gns_ctx* c, int layer_index, SampleArgs* out)
 {
-    const Layout& L = c->lay;
-    SampleArgs a;
-    fill_sample_args(c, layer_index, dst_nodes, row_eligible, active_gen(c), &a);
+    fill_sample_template_gen(c, layer_index, 0, out);
+}
 
-    // The previous layer's relabel rides in front of this layer's first kernel: both only need
-    // that layer's phase 3, and they touch disjoint memory (sampler scratch alternates by layer).
-    FinishArgs prev = {};
+static void launch_flag_kernel(gns_ctx* c, const LayerArgs& a, int count, int64_t all_chunks, hipStream_t s)
+{
+    const size_t lds_bytes = (size_t) ((c->lay.words + 1) / 2) * 16;
+    const size_t coarse_bytes = (size_t) ((c->lay.coarse_words + 1) / 2) * 16;
+    if (lds_bytes <= c->lds_bitmap_limit)
+        hipLaunchKernelGGL((k_flag_chunks<1>), dim3((unsigned) c->num_cus), dim3(1024), lds_bytes, s, a, count, all_chunks);
+    else if (c->lay.coarse_shift > 0 && coarse_bytes <= c->lds_bitmap_limit)
+        hipLaunchKernelGGL((k_flag_chunks<2>), dim3((unsigned) c->num_cus), dim3(1024), coarse_bytes, s, a, count, all_chunks);
+    else
+        hipLaunchKernelGGL((k_flag_chunks<0>), dim3((unsigned) c->num_cus * 8), dim3(kBlock), 0, s, a, count, all_chunks);
+}
+
+// GNS_FLAGS_PER_CACHE: one pass over every aligned chunk of the CSR entry array, for the copy of the cache
+// structures a draw is filling.
+hipError_t launch_flag_all_entries(gns_ctx* c, int cache_gen, hipStream_t s)
+{
+    LayerArgs a;
+    memset(&a, 0, sizeof(a));
+    fill_sample_template_gen(c, 0, cache_gen, &a.s);
+    launch_flag_kernel(c, a, 0, (c->graph.num_entries + 63) / 64, s);
+    return hipGetLastError();
+}
+
+// One layer's sampler launches for a group of mini-batches.  The previous layer's relabel rides in front
+// of this layer's first kernel: both only need that layer's phase 3, and they touch disjoint memory
+// (sampler scratch alternates by layer).
+hipError_t launch_sample_layer(const Group& g, int layer_index, hipStream_t s)
+{
+    gns_ctx* c = g.ctx[0];
+    const Layout& L = c->lay;
+    LayerArgs a;
+    fill_group_args(g, &a);
+    set_group_layer(g, layer_index, &a);
+    fill_sample_template(c, layer_index, &a.s);
     int rl = 0;
-    if (prev_blk) {
-        fill_finish_args(c, layer_index - 1, prev_dst, prev_blk, &prev);
+    if (layer_index > 0) {
+        fill_finish_template(c, layer_index - 1, &a.f);
         rl = relabel_grid(c, layer_index - 1);
     }
+    const unsigned gy = (unsigned) g.count;
 
     const int64_t rows_max = L.rows[layer_index];
-    const int G = (a.fanout <= 8) ? 8 : (a.fanout <= 16) ? 16 : 64;
+    const int G = (a.s.fanout <= 8) ? 8 : (a.s.fanout <= 16) ? 16 : 64;
     const int64_t rows_per_block = kBlock / G;
     int64_t row_blocks = (rows_max + rows_per_block - 1) / rows_per_block;
     // One step of rows per wave where that fits: rows differ a lot in cost, and with more blocks
@@ -661,15 +646,15 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
     if (row_blocks < 1) row_blocks = 1;
     const dim3 tb(kBlock);
 
-#define GNS_LAUNCH_BY_G(KERNEL, RL, ...)                                                              \
-    do {                                                                                              \
-        if (G == 8)       hipLaunchKernelGGL((KERNEL<8>), rb, tb, 0, s, a, prev, (RL), ##__VA_ARGS__);  \
-        else if (G == 16) hipLaunchKernelGGL((KERNEL<16>), rb, tb, 0, s, a, prev, (RL), ##__VA_ARGS__); \
-        else              hipLaunchKernelGGL((KERNEL<64>), rb, tb, 0, s, a, prev, (RL), ##__VA_ARGS__); \
+#define GNS_LAUNCH_BY_G(KERNEL, RL, ...)                                                         \
+    do {                                                                                         \
+        if (G == 8)       hipLaunchKernelGGL((KERNEL<8>), rb, tb, 0, s, a, (RL), ##__VA_ARGS__);  \
+        else if (G == 16) hipLaunchKernelGGL((KERNEL<16>), rb, tb, 0, s, a, (RL), ##__VA_ARGS__); \
+        else              hipLaunchKernelGGL((KERNEL<64>), rb, tb, 0, s, a, (RL), ##__VA_ARGS__); \
     } while (0)
 
     if (c->config.policy[layer_index] == GNS_UNIFORM) {
-        const dim3 rb((unsigned) (row_blocks + rl));
+        const dim3 rb((unsigned) (row_blocks + rl), gy);
         GNS_LAUNCH_BY_G(k_sample_uniform, rl);
         return hipGetLastError();
     }
@@ -679,18 +664,18 @@ hipError_t launch_sample_layer(gns_ctx* c, int layer_index, const int32_t* dst_n
         {
             StageTimer t(c, GNS_STAGE_PLAN, s);
             const unsigned plan_blocks = (unsigned) ((rows_max + kPlanTile - 1) / kPlanTile);
-            hipLaunchKernelGGL(k_plan_count, dim3(plan_blocks + (unsigned) rl), tb, 0, s, a, prev, rl);
-            hipLaunchKernelGGL(k_plan_expand, dim3(plan_blocks), tb, 0, s, a);
+            hipLaunchKernelGGL(k_plan_count, dim3(plan_blocks + (unsigned) rl, gy), tb, 0, s, a, rl);
+            hipLaunchKernelGGL(k_plan_expand, dim3(plan_blocks, gy), tb, 0, s, a);
         }
         rl = 0;                          // done with the plan kernel
         StageTimer t(c, GNS_STAGE_FLAG, s);
-        launch_flag_kernel(c, a, 1, 0, s);
+        launch_flag_kernel(c, a, g.count, 0, s);
     }
     StageTimer t(c, GNS_STAGE_SELECT, s);
     // hub rows get dedicated waves (the count lives on the device; the waves stride over the list)
     const int hub_blocks = (G < 64) ? (int) (rows_max / (kBlock / kWave) < (int64_t) c->num_cus * 2
                                                  ? rows_max / (kBlock / kWave) + 1 : (int64_t) c->num_cus * 2) : 0;
-    const dim3 rb((unsigned) (row_blocks + rl + hub_blocks));
+    const dim3 rb((unsigned) (row_blocks + rl + hub_blocks), gy);
     GNS_LAUNCH_BY_G(k_select_rows, rl, hub_blocks);
 #undef GNS_LAUNCH_BY_G
     return hipGetLastError();

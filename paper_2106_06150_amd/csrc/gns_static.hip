@@ -6,7 +6,8 @@
 // array's device address where they are otherwise handed the workspace.
 #include <stdio.h>
 #include "gns_internal.h"
-#include "gns_device.hpp"
+#include <string.h>
+#include "gns_kernels.hpp"
 
 namespace gns {
 
@@ -78,7 +79,16 @@ extern "C" gns_status gns_sample_blocks_static(gns_ctx* ctx, uint64_t seed, cons
         const hipError_t e = init_batch_scratch(c, s);
         if (e != hipSuccess) st = ctx_fail(c, GNS_EHIP, "static scratch init", e);
     }
-    if (st == GNS_OK) st = enqueue_batch(c, seed, seeds_dev, num_seeds, blocks, s);
+    if (st == GNS_OK) {
+        Group g;
+        memset(&g, 0, sizeof(g));
+        g.count = 1;
+        g.ctx[0] = c;
+        g.blocks[0] = blocks;
+        BeginDyn dyn;
+        fill_begin_dyn(g, &seed, &seeds_dev, &num_seeds, &dyn);
+        st = enqueue_batch(g, dyn, s);
+    }
     if (st == GNS_OK) {
         c->batch_id = 1;
         hipError_t e = hipMemcpyAsync(c->h_state, c->d_state, sizeof(DeviceState), hipMemcpyDeviceToHost, s);

@@ -758,3 +758,185 @@ def test_sage_dense_update_step(rows, f1, f2, hdim, relu, use_bias):
                              w.cuda()[1:].contiguous(), None, relu, out, rows)
     finally:
         gns.close()
+
+
+def _group_setup(gns, count):
+    """count contexts (the created one and forks) with their own block buffers, feature buffers and a GroupCall."""
+    ctxs, keep = [gns.ctx], []
+    for _ in range(count - 1):
+        ws = torch.empty(B.gns_fork_workspace_bytes(gns.ctx), dtype=torch.uint8, device=gns.device)
+        keep.append(ws)
+        ctxs.append(B.gns_fork(gns.ctx, ws))
+    bufs = [gns.blocks] + [B.BlockBuffers(gns.graph, gns.config, gns.device) for _ in range(count - 1)]
+    call = B.GroupCall(ctxs, [b.array for b in bufs])
+    return ctxs, keep, bufs, call
+
+
+def _check_group_batch(gns, buf, ref, feat, xin, hout, F):
+    from gpu_harness import compare_aggregate, aggregate_scale
+    L = len(ref)
+    compare_blocks([buf.views(j) for j in range(L)], ref)
+    if feat is None:
+        return
+    last = L - 1
+    x_ref = oracle.gather(feat.numpy(), ref[last].src_nodes)
+    assert xin[:ref[last].num_src].cpu().numpy().tobytes() == x_ref.tobytes()
+    o_ref = oracle.aggregate(ref[last].indptr, ref[last].indices, ref[last].weights, x_ref)
+    compare_aggregate(hout[:ref[last].num_dst].cpu().numpy(), o_ref, aggregate_scale(ref[last], x_ref))
+
+
+@pytest.mark.parametrize("flag_mode", [0, 1])
+@pytest.mark.parametrize("count,fanouts,policies", [(8, (6, 4, 3), (U, U, C)), (3, (5, 7), (CF, CF)), (1, (4, 4), (U, C)),
+                                                    (5, (20, 3), (U, C))])
+def test_group_of_mini_batches_in_one_launch_sequence(count, fanouts, policies, flag_mode):
+    """gns_*_group: `count` mini-batches of different sizes per launch sequence, several rounds (both hash-map
+    parities, graph replays), a cache refresh in the middle; every batch against the oracle."""
+    ip, ix = _small(n=5000, avg=16, seed=37)
+    n = ip.numel() - 1
+    F = 24
+    feat = _feat(n, F, seed=8)
+    csize, bs = 300, 90
+    gns = GpuGns(ip, ix, feat, fanouts=fanouts, policies=policies, cache_size=csize, max_seeds=bs, flag_mode=flag_mode)
+    ctxs, keep, bufs, call = _group_setup(gns, count)
+    try:
+        L = len(fanouts)
+        last = L - 1
+        st = torch.cuda.Stream()
+        xin = [torch.zeros((b.array[last].cap_src, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        hout = [torch.zeros((b.array[last].cap_dst, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        for rnd in range(5):
+            epoch = rnd // 2
+            if rnd % 2 == 0:
+                B.gns_sample_cache(gns.ctx, 44, epoch, st)
+            cache = oracle.sample_cache(ip.numpy(), 44, epoch, csize)
+            seeds = [synth.uniform_seed_batch(n, bs - 11 * ((b + rnd) % 7), 100 * rnd + b).cuda() for b in range(count)]
+            bseeds = [7000 + 10 * rnd + b for b in range(count)]
+            call.sample(bseeds, seeds, st)
+            call.gather([b.tensors[last]["src_nodes"] for b in bufs], [-1] * count, xin, st)
+            call.aggregate(last, xin, F, hout, st)
+            call.wait(st)
+            torch.cuda.synchronize()
+            for b in range(count):
+                ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), cache[1], csize, bseeds[b], seeds[b].cpu().numpy(),
+                                           list(fanouts), list(policies))
+                _check_group_batch(gns, bufs[b], ref, feat, xin[b], hout[b], F)
+        # a context of the group used on its own in between, then the group again (parities now differ)
+        solo = synth.uniform_seed_batch(n, 33, 999).cuda()
+        B.gns_sample_blocks(ctxs[-1], 31337, solo, bufs[-1].array, st)
+        ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), cache[1], csize, 31337, solo.cpu().numpy(), list(fanouts),
+                                   list(policies))
+        compare_blocks([bufs[-1].views(j) for j in range(L)], ref)
+        seeds = [synth.uniform_seed_batch(n, bs, 5000 + b).cuda() for b in range(count)]
+        call.sample(list(range(count)), seeds, st)
+        call.wait(st)
+        for b in range(count):
+            ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), cache[1], csize, b, seeds[b].cpu().numpy(), list(fanouts),
+                                       list(policies))
+            compare_blocks([bufs[b].views(j) for j in range(L)], ref)
+        # a bad seed in one batch of a group is reported by the group's wait
+        bad = seeds[count // 2].clone()
+        bad[1] = bad[0]
+        seeds2 = list(seeds)
+        seeds2[count // 2] = bad
+        call.sample(list(range(count)), seeds2, st)
+        with pytest.raises(B.GnsError) as e:
+            call.wait(st)
+        assert e.value.status == B.GNS_EINVAL
+    finally:
+        for f in ctxs[1:]:
+            B.gns_destroy(f)
+        gns.close()
+
+
+def test_group_argument_checks():
+    ip, ix = _small(n=800)
+    n = ip.numel() - 1
+    gns = GpuGns(ip, ix, None, fanouts=(3, 2), policies=(U, U), cache_size=0, max_seeds=16)
+    other = GpuGns(ip, ix, None, fanouts=(3, 2), policies=(U, U), cache_size=0, max_seeds=16)
+    try:
+        seeds = synth.uniform_seed_batch(n, 16, 1).cuda()
+        twice = B.GroupCall([gns.ctx, gns.ctx], [gns.blocks.array, other.blocks.array])
+        with pytest.raises(B.GnsError) as e:
+            twice.sample([1, 2], [seeds, seeds])
+        assert e.value.status == B.GNS_EINVAL
+        strangers = B.GroupCall([gns.ctx, other.ctx], [gns.blocks.array, other.blocks.array])
+        with pytest.raises(B.GnsError) as e:
+            strangers.sample([1, 2], [seeds, seeds])
+        assert e.value.status == B.GNS_EINVAL
+    finally:
+        other.close()
+        gns.close()
+
+
+def test_config2_pipeline_as_the_benchmark_drives_it():
+    """The medium workload driven the way bench.py times it: groups of mini-batches on two streams, device-side
+    counts, graph replays, no host synchronisation between batches, a cache refresh in the middle; every
+    batch compared with the oracle afterwards (blocks, gathered rows, aggregate)."""
+    _release_cached_memory()
+    cfg_id = 2
+    c = synth.CONFIGS[cfg_id]
+    sd = synth.config_seeds(cfg_id)
+    g = synth.make_config_graph(cfg_id)
+    n, F = c["n"], c["feat"]
+    feat = synth.node_features(n, F, sd["feat"])
+    fanouts, policies = list(c["fanouts"]), [U, U, C]
+    csize = int(n * c["cache_frac"])
+    gns = GpuGns(g.indptr, g.indices, feat, fanouts=fanouts, policies=policies, cache_size=csize, max_seeds=c["batch"],
+                 flag_mode=1)
+    G, S = 4, 2                                       # batches per group, groups in flight
+    ctxs, keep, bufs, _ = _group_setup(gns, G * S)
+    try:
+        calls = [B.GroupCall(ctxs[s * G:(s + 1) * G], [b.array for b in bufs[s * G:(s + 1) * G]]) for s in range(S)]
+        streams = [torch.cuda.Stream() for _ in range(S)]
+        last = len(fanouts) - 1
+        rounds, refresh_at = 3, 2 * G                # 3 rounds of S groups of G batches; a refresh after 8 batches
+        nb = rounds * S * G
+        seeds = [synth.uniform_seed_batch(n, c["batch"], sd["batch"] + b).cuda() for b in range(nb)]
+        # results are copied out of the reused buffers on the batch's own stream right behind the batch
+        snap = {}
+        xin = [torch.zeros((bufs[i].array[last].cap_src, F), dtype=torch.float32, device=gns.device) for i in range(G * S)]
+        hout = [torch.zeros((bufs[i].array[last].cap_dst, F), dtype=torch.float32, device=gns.device) for i in range(G * S)]
+        torch.cuda.synchronize()
+        b0 = 0
+        for rnd in range(rounds):
+            for s in range(S):
+                ids = list(range(b0, b0 + G))
+                if b0 % refresh_at == 0:
+                    B.gns_sample_cache(gns.ctx, sd["cache"], b0 // refresh_at, streams[0])
+                sl = slice(s * G, (s + 1) * G)
+                with torch.cuda.stream(streams[s]):
+                    calls[s].sample([sd["batch"] + b for b in ids], [seeds[b] for b in ids], streams[s])
+                    calls[s].gather([bf.tensors[last]["src_nodes"] for bf in bufs[sl]], [-1] * G, xin[sl], streams[s])
+                    calls[s].aggregate(last, xin[sl], F, hout[sl], streams[s])
+                    for k, b in enumerate(ids):
+                        i = s * G + k
+                        snap[b] = ([{name: t.clone() for name, t in bufs[i].tensors[j].items()} for j in range(last + 1)],
+                                   xin[i].clone(), hout[i].clone())
+                b0 += G
+        torch.cuda.synchronize()
+        ip, ix = g.indptr.numpy(), g.indices.numpy()
+        from gpu_harness import compare_aggregate, aggregate_scale
+        caches = {}
+        for b in (0, 1, G, 2 * G, 2 * G + 1, nb - 1):          # first group, across the refresh, the last batch
+            epoch = b // refresh_at
+            if epoch not in caches:
+                caches[epoch] = oracle.sample_cache(ip, sd["cache"], epoch, csize)
+            ref = oracle.sample_blocks(ip, ix, caches[epoch][1], csize, sd["batch"] + b, seeds[b].cpu().numpy(), fanouts, policies)
+            tens, x, h = snap[b]
+            for j, r in enumerate(ref):
+                t = tens[j]
+                assert np.array_equal(t["indptr"][:r.num_dst + 1].cpu().numpy(), r.indptr), (b, j)
+                assert np.array_equal(t["indices"][:r.num_edges].cpu().numpy(), r.indices), (b, j)
+                assert np.array_equal(t["src_nodes"][:r.num_src].cpu().numpy(), r.src_nodes), (b, j)
+                assert np.array_equal(t["row_eligible"][:r.num_dst].cpu().numpy(), r.row_eligible), (b, j)
+                gw = t["weights"][:r.num_edges].cpu().numpy().astype(np.float64)
+                assert np.all(np.abs(gw - r.weights) <= 1e-5 * np.abs(r.weights)), (b, j)
+            x_ref = oracle.gather(feat.numpy(), ref[last].src_nodes)
+            assert x[:ref[last].num_src].cpu().numpy().tobytes() == x_ref.tobytes(), b
+            o_ref = oracle.aggregate(ref[last].indptr, ref[last].indices, ref[last].weights, x_ref)
+            compare_aggregate(h[:ref[last].num_dst].cpu().numpy(), o_ref, aggregate_scale(ref[last], x_ref))
+    finally:
+        for f in ctxs[1:]:
+            B.gns_destroy(f)
+        gns.close()
+        _release_cached_memory()

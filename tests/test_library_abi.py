@@ -25,7 +25,7 @@ def declared_functions():
 
 def test_header_functions_are_exported():
     names = declared_functions()
-    assert len(names) == 22, names
+    assert len(names) == 26, names
     lib = ctypes.CDLL(LIB)
     for name in names:
         assert hasattr(lib, name), name
