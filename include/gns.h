@@ -53,7 +53,7 @@ extern "C" {
 
 #define GNS_MAX_LAYERS 8
 #define GNS_MAX_FANOUT 64
-#define GNS_MAX_GROUP 8      /* mini-batches one gns_*_group call serves */
+#define GNS_MAX_GROUP 16     /* mini-batches one gns_*_group call serves */
 
 typedef struct gns_ctx gns_ctx; /* opaque; one per (graph, config, device) */
 

@@ -19,7 +19,7 @@ GNS_FLAGS_PER_BATCH, GNS_FLAGS_PER_CACHE = 0, 1
 GNS_PROB_DEGREE, GNS_PROB_WALK = 0, 1
 GNS_MAX_LAYERS = 8
 GNS_MAX_FANOUT = 64
-GNS_MAX_GROUP = 8
+GNS_MAX_GROUP = 16
 
 STATUS_NAMES = ["GNS_OK", "GNS_EINVAL", "GNS_ECAPACITY", "GNS_ESTATE", "GNS_EHIP", "GNS_ENOMEM", "GNS_ENOTIMPL"]
 

@@ -59,7 +59,11 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     L.words = (n + 63) / 64;
     L.word_tiles = (L.words + kTile - 1) / kTile;
     L.mark_tile_words = kMarkTileMin;
-    while (L.mark_tile_words < kMarkTileMax && L.words / L.mark_tile_words > 2048) L.mark_tile_words *= 2;
+    while (L.mark_tile_words < kMarkTileMax && L.words / L.mark_tile_words > 256) L.mark_tile_words *= 2;
+    if (const char* e = getenv("GNS_MARK_TILE_WORDS")) {           // testing aid: a power of two in [64, kMarkTileMax]
+        const int t = atoi(e);
+        if (t >= kMarkTileMin && t <= kMarkTileMax && (t & (t - 1)) == 0) L.mark_tile_words = t;
+    }
     L.mark_tiles = (L.words + L.mark_tile_words - 1) / L.mark_tile_words;
 
     // worst-case frontier growth: rows[i+1] = min(rows[i] * (1 + k_i), n)
@@ -91,6 +95,14 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     // per-batch scratch (every forked context has its own copy of these sections)
     L.state = take(sizeof(DeviceState) + 64);
     L.mark_bitmap = take((size_t) L.words * 8);
+    // A graph with millions of nodes gets a summary of the mark bitmap (one bit per word), so that the union
+    // step reads the words that carry marks instead of walking n / 8 bytes per layer.
+    {
+        int64_t min_words = 65536;
+        if (const char* e = getenv("GNS_MARK_SUMMARY_MIN_WORDS")) min_words = atoll(e);
+        L.summary_words = L.words >= min_words ? (L.words + 63) / 64 : 0;
+        L.mark_summary = take((size_t) (L.summary_words > 0 ? L.summary_words : 1) * 8);
+    }
     L.seed_copy = take((size_t) cfg->max_seeds * 4);
     L.row_ext = take((size_t) L.rows[cfg->num_layers] * 16);
     L.hub_rows = take((size_t) L.rows[cfg->num_layers] * 4);
@@ -132,6 +144,11 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
             L.walk_tiles_nz = take((tiles + 1) * 4);
         }
     }
+    if (uses_cache && cfg->flag_mode == GNS_FLAGS_PER_CACHE) {
+        if (g->num_entries >= (int64_t) 1 << 32) GNS_BAD("GNS_FLAGS_PER_CACHE counts cached entries in 32 bits: num_entries must be < 2^32");
+        L.chunk_tiles = (g->num_entries / 64 + 1 + kTile - 1) / kTile;
+        L.sums_chunks = take((size_t) (L.chunk_tiles + 1) * 4);
+    }
     // The cache block: everything a cache draw writes and the mini-batches read.  There are two copies
     // (generations): a draw fills the one that is not in use, so it can run while batches that were
     // enqueued before it still read the other.
@@ -158,6 +175,10 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     if (uses_cache) {
         L.edge_flags = take((size_t) (g->num_entries / 64 + 1) * 8);
         L.node_pc = take((size_t) n * 4);
+        if (cfg->flag_mode == GNS_FLAGS_PER_CACHE) {
+            L.srec = take((size_t) (g->num_entries / 64 + 2) * 16);
+            L.s_nodes = take((size_t) g->num_entries * 4);
+        }
     }
     L.cache_block_bytes = off - L.cache_block_begin;
     if (uses_cache) off += L.cache_block_bytes;            // the second generation
@@ -376,6 +397,8 @@ hipError_t init_batch_scratch(gns_ctx* c, hipStream_t s)
     const Layout& L = c->lay;
     hipError_t e = launch_fill_u32(reinterpret_cast<uint32_t*>(c->d_state), (sizeof(DeviceState) + 64) / 4, 0u, s);
     if (e == hipSuccess) e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.mark_bitmap), (size_t) L.words, 0ull, s);
+    if (e == hipSuccess && L.summary_words > 0)
+        e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.mark_summary), (size_t) L.summary_words, 0ull, s);
     for (int par = 0; par < 2 && e == hipSuccess; ++par)
         e = launch_fill_u64(ws_ptr<unsigned long long>(c, L.hash_slots[par]), (size_t) L.hash_cap, ~0ull, s);
     return e;

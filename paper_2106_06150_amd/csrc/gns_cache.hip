@@ -479,8 +479,10 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, bool wait
                            cache_ptr<uint64_t>(c, L.coarse_bitmap, gen), (int64_t) L.coarse_words);
         GNS_HIP_TRY(hipGetLastError(), "coarse bitmap launch");
     }
-    if (c->config.flag_mode == GNS_FLAGS_PER_CACHE)
+    if (c->config.flag_mode == GNS_FLAGS_PER_CACHE) {
         GNS_HIP_TRY(launch_flag_all_entries(c, gen, s), "flag all entries");
+        GNS_HIP_TRY(launch_build_induced(c, gen, s), "induced subgraph");
+    }
     if (c->graph.feat_dim > 0) {
         // fill the device table of cached feature rows (slot order) straight from the full store
         const int32_t* fill_nodes = x.cache_nodes;

@@ -6,6 +6,7 @@
 #include "gns_internal.h"
 #include "gns_device.hpp"
 #include <string.h>
+#include <stdlib.h>
 
 namespace gns {
 
@@ -152,6 +153,12 @@ struct AggBatch {
 struct AggGroup {
     AggBatch b[GNS_MAX_GROUP];
     int32_t feat_dim;
+    // Column slices: the chip's 8 XCDs have an L2 each and workgroups go to them round robin, so block
+    // x of a launch runs on XCD x % 8.  With `slices` > 1 a block works on float4 columns
+    // [slice * kLanes, (slice + 1) * kLanes) of its rows only, slice = (x % 8) % slices: each XCD's L2 then
+    // holds one slice of the few thousand hot source rows instead of all of them.
+    int32_t slices;
+    int32_t fold;       // XCDs that share a slice (8 / slices when that divides, else 1: surplus XCDs' blocks stand down)
 };
 
 // the view of one batch the kernel body works on
@@ -167,20 +174,30 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggGroup g)
     a.feat_dim = g.feat_dim;
     const int lane = (int) (threadIdx.x % kLanes);
     const int64_t groups_per_block = kBlock / kLanes;
-    const int64_t group = (int64_t) blockIdx.x * groups_per_block + threadIdx.x / kLanes;
-    const int64_t num_groups = (int64_t) gridDim.x * groups_per_block;
+    int64_t group = (int64_t) blockIdx.x * groups_per_block + threadIdx.x / kLanes;
+    int64_t num_groups = (int64_t) gridDim.x * groups_per_block;
     const int64_t F = a.feat_dim;
+    int col0 = 0;                   // first float4 column of this block's slice
+    if (g.slices > 1) {
+        const int xcd = (int) (blockIdx.x & 7u);
+        const int slice = g.fold > 1 ? xcd % g.slices : xcd;
+        if (slice >= g.slices) return;
+        const int64_t row_block = g.fold > 1 ? (int64_t) (blockIdx.x >> 3) * g.fold + xcd / g.slices : (int64_t) (blockIdx.x >> 3);
+        group = row_block * groups_per_block + threadIdx.x / kLanes;
+        num_groups = (int64_t) (gridDim.x >> 3) * g.fold * groups_per_block;
+        col0 = slice * kLanes;
+    }
     const int64_t count = a.num_dst_dev ? (int64_t) *a.num_dst_dev : (int64_t) a.num_dst;
     const uint32_t num_src = (uint32_t) (a.num_src_dev ? *a.num_src_dev : a.num_src);
     constexpr int kEdges = 8;       // edges whose rows are in flight together
-    if (kVec && F <= 4 * kLanes) {
+    if (kVec && (g.slices > 1 || F <= 4 * kLanes)) {
         // One float4 per lane covers a row.  The three dependent reads of a row (its offsets, its
         // edges, its sources' rows) are staggered over three consecutive rows of the group, so every
         // trip of the loop issues all three kinds of load before it waits for any of them:
         //   row i: source rows -> fma;  row i+1: indices and weights;  row i+2: offsets.
-        const float4* x4 = reinterpret_cast<const float4*>(a.x_src);
         const int64_t F4 = F >> 2;
-        const bool has = lane < (int) F4;
+        const float4* x4 = reinterpret_cast<const float4*>(a.x_src) + col0;
+        const bool has = col0 + lane < (int) F4;
         int32_t b0 = 0, e0 = 0, b1 = 0, e1 = 0, b2 = 0, e2 = 0;          // offsets of rows i, i+1, i+2
         uint32_t j1[kEdges];                                              // first kEdges edges of row i+1
         float w1[kEdges];
@@ -240,7 +257,7 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggGroup g)
                 const float n_v = (float) (e0 - b0);
                 acc.x /= n_v; acc.y /= n_v; acc.z /= n_v; acc.w /= n_v;
             }
-            if (has) store_streaming(reinterpret_cast<float4*>(a.out + row * F) + lane, acc);
+            if (has) store_streaming(reinterpret_cast<float4*>(a.out + row * F) + col0 + lane, acc);
             b0 = b1; e0 = e1; b1 = b2; e1 = e2; b2 = b3; e2 = e3;
         }
         return;
@@ -337,11 +354,29 @@ hipError_t launch_aggregate(gns_ctx* const* ctxs, int count, const gns_block* co
     a.feat_dim = feat_dim;
     const int64_t F = feat_dim;
     const bool vec = (F % 4 == 0) && aligned;
-    const int lanes = lanes_for(vec ? F / 4 : F);
+    int lanes = lanes_for(vec ? F / 4 : F);
+    a.slices = 1;
+    a.fold = 1;
+    if (vec && F / 4 >= 16 && getenv("GNS_AGG_SLICES")) {
+        // at least 8 lanes (128 bytes, one cache line) of a row per slice, at most 8 slices
+        lanes = 8;
+        if (const char* e = getenv("GNS_AGG_SLICE_LANES")) lanes = atoi(e) >= 4 ? atoi(e) : 8;
+        while (lanes * 8 < F / 4) lanes <<= 1;
+        a.slices = (int32_t) ((F / 4 + lanes - 1) / lanes);
+        a.fold = (8 % a.slices == 0) ? 8 / a.slices : 1;
+    }
     const int64_t groups_per_block = kBlock / lanes;
     int64_t blocks = (most + groups_per_block - 1) / groups_per_block;
     const int64_t cap = (int64_t) c->num_cus * 16;
-    if (blocks > cap) blocks = cap;
+    if (a.slices > 1) {
+        // row blocks per (8 / fold) ... every group of 8 consecutive blocks covers `fold` row blocks in all slices
+        int64_t row_blocks = (blocks + a.fold - 1) / a.fold;
+        if (row_blocks * 8 > cap * 2) row_blocks = cap * 2 / 8;
+        if (row_blocks < 1) row_blocks = 1;
+        blocks = row_blocks * 8;
+    } else if (blocks > cap) {
+        blocks = cap;
+    }
     const dim3 grid((unsigned) blocks, (unsigned) count);
     if (vec) aggregate_dispatch<true>(lanes, grid, s, a);
     else     aggregate_dispatch<false>(lanes, grid, s, a);

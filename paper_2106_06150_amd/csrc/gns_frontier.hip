@@ -115,6 +115,8 @@ void fill_group_args(const Group& g, LayerArgs* out)
     const Layout& L = c->lay;
     memset(out, 0, sizeof(*out));
     WsOffsets& o = out->off;
+    o.mark_summary = L.mark_summary;
+    o.has_summary = L.summary_words > 0 ? 1 : 0;
     o.state = L.state; o.mark = L.mark_bitmap; o.seed_copy = L.seed_copy; o.row_ext = L.row_ext; o.hub_rows = L.hub_rows;
     for (int p = 0; p < 2; ++p) {
         o.slot_list[p] = L.slot_list[p]; o.hash_slots[p] = L.hash_slots[p];
@@ -161,7 +163,26 @@ hipError_t launch_batch_begin(const Group& g, const BeginDyn& d, hipStream_t s)
     return hipGetLastError();
 }
 
+// Words first .. first + per - 1 of a tile that starts at word `base` (per <= kPerMax consecutive words of one
+// thread; they never straddle a summary word because per divides 64 and first is a multiple of per).  With a
+// summary only the words it reports as marked are read; the reads are issued together, behind one read of
+// the summary word.
+template <int kPerMax>
+__device__ __forceinline__ void load_marks(const FinishArgs& a, int64_t base, int first, int per, int T, uint64_t* word)
+{
+    uint64_t has = ~0ull;
+    const int64_t w0 = base + first;
+    if (a.mark_summary && first < T && w0 < a.words) has = a.mark_summary[w0 >> 6] >> (w0 & 63);
+#pragma unroll
+    for (int i = 0; i < kPerMax; ++i) {
+        const int64_t w = w0 + i;
+        const bool live = i < per && first + i < T && w < a.words && ((has >> i) & 1ull);
+        word[i] = live ? a.mark[w] : 0ull;
+    }
+}
+
 // ---------------------------------------------------------------------------
+template <int kPerMax>
 __global__ void __launch_bounds__(kBlock) k_finish_phase1(LayerArgs g)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
@@ -181,9 +202,13 @@ __global__ void __launch_bounds__(kBlock) k_finish_phase1(LayerArgs g)
     } else {
         const int32_t tile = (int32_t) blockIdx.x - a.row_tiles_max;
         const int64_t base = (int64_t) tile * a.mark_tile_words;
+        const int T = a.mark_tile_words;
+        const int per = T > kBlock ? T / kBlock : 1;
+        uint64_t word[kPerMax];
+        load_marks<kPerMax>(a, base, (int) threadIdx.x * per, per, T, word);
         int32_t sum = 0;
-        for (int i = (int) threadIdx.x; i < a.mark_tile_words; i += kBlock)
-            if (base + i < a.words) sum += __popcll(a.mark[base + i]);
+#pragma unroll
+        for (int i = 0; i < kPerMax; ++i) sum += __popcll(word[i]);
         sum = block_sum(sum, smem);
         if (threadIdx.x == 0) a.sums_marks[tile] = sum;
     }
@@ -199,12 +224,15 @@ __device__ __forceinline__ int32_t block_sum_array(const int32_t* vals, int32_t 
 
 // Phase 3 needs each tile's offset = the sum of the earlier tiles' sums.  Every block adds
 // those up itself (at most a few thousand values), which saves a single-block scan kernel.
+template <int kPerMax>
 __global__ void __launch_bounds__(kBlock) k_finish_phase3(LayerArgs g)
 {
     __shared__ int32_t smem[kBlock / kWave + 1];
     const FinishArgs a = bind_finish(g, (int) blockIdx.y, true);
-    __shared__ int32_t s_off[kMarkTileMax + 1];
-    __shared__ uint64_t s_word[kMarkTileMax];
+    // the tile's marked words, kMarkCap at a time: the word, its index in the tile, the number of marks before it
+    __shared__ uint64_t s_word[kMarkCap];
+    __shared__ int32_t s_widx[kMarkCap];
+    __shared__ int32_t s_off[kMarkCap];
     const int32_t R = a.st->num_dst[a.layer_index];
     const int32_t row_tiles = (R + kTile - 1) / kTile;
     if ((int32_t) blockIdx.x < a.row_tiles_max) {
@@ -244,48 +272,64 @@ __global__ void __launch_bounds__(kBlock) k_finish_phase3(LayerArgs g)
         if (here == 0) return;
         // thread t owns words t*per .. t*per+per-1 of the tile (per = 1 for tiles of up to kBlock words);
         // exclusive offsets of the tile's words into LDS
-        constexpr int kPerMax = kMarkTileMax / kBlock;
         const int per = T > kBlock ? T / kBlock : 1;
         const int first = (int) threadIdx.x * per;
         uint64_t word[kPerMax];
-        int32_t cnt = 0;
+        load_marks<kPerMax>(a, base, first, per, T, word);
+        int32_t cnt = 0, nz = 0;
 #pragma unroll
         for (int i = 0; i < kPerMax; ++i) {
-            const int64_t w = base + first + i;
-            word[i] = (i < per && first + i < T && w < a.words) ? a.mark[w] : 0ull;
             cnt += __popcll(word[i]);
+            nz += word[i] ? 1 : 0;
+            if (word[i]) a.mark[base + first + i] = 0ull;            // ready for the next layer
         }
-        int32_t total;
-        int32_t off = block_exclusive_scan(cnt, smem, &total);
-#pragma unroll
-        for (int i = 0; i < kPerMax; ++i) {
-            if (i < per && first + i < T) {
-                s_off[first + i] = off;
-                s_word[first + i] = word[i];
-                off += __popcll(word[i]);
-                if (word[i]) a.mark[base + first + i] = 0ull;        // ready for the next layer
-            }
-        }
-        if (threadIdx.x == 0) s_off[T] = total;
+        int32_t total, total_nz;
+        const int32_t off = block_exclusive_scan(cnt, smem, &total);        // marks before this thread's words
+        const int32_t widx = block_exclusive_scan(nz, smem, &total_nz);     // marked words before them
         __syncthreads();
-        // one thread per new node: locate its word (last word whose offset is <= j), then its bit
-        for (int32_t j = (int32_t) threadIdx.x; j < total; j += kBlock) {
-            int32_t lo = 0, hi = T;                                  // answer in [lo, hi)
-            while (hi - lo > 1) {
-                const int32_t mid = (lo + hi) >> 1;
-                if (s_off[mid] <= j) lo = mid; else hi = mid;
+        // every thread has read its summary words: clear them (a tile is a whole number of summary words)
+        if (a.mark_summary)
+            for (int i = (int) threadIdx.x; i < T / 64; i += kBlock)
+                if (base / 64 + i < (a.words + 63) / 64) a.mark_summary[base / 64 + i] = 0ull;
+        // The marked words go through LDS in order, kMarkCap at a time (most tiles need one pass).
+        for (int32_t p0 = 0; p0 < total_nz; p0 += kMarkCap) {
+            int32_t my = widx, my_off = off;
+#pragma unroll
+            for (int i = 0; i < kPerMax; ++i) {
+                if (word[i]) {
+                    if (my >= p0 && my < p0 + kMarkCap) {
+                        s_word[my - p0] = word[i];
+                        s_widx[my - p0] = first + i;
+                        s_off[my - p0] = my_off;
+                    }
+                    ++my;
+                    my_off += __popcll(word[i]);
+                }
             }
-            const int bit = select_bit64(s_word[lo], j - s_off[lo]);
-            const uint32_t node = (uint32_t) ((base + lo) * 64 + bit);
-            const int32_t pos = R + before + j;
-            RowExtent ext;
-            ext.start = load_off_rt(a.g_indptr, a.g_i64, node);
-            ext.end = load_off_rt(a.g_indptr, a.g_i64, (int64_t) node + 1);
-            a.src_nodes[pos] = (int32_t) node;
-            a.row_ext[pos] = ext;
-            append_hub_rows(a.st, a.hub_rows, is_hub_extent(ext.start, ext.end), pos);
-            const int64_t slot = hash_insert(a.slots, a.hmask, a.hshift, node, (uint32_t) pos);
-            a.slot_list[pos] = slot >= 0 ? (uint32_t) slot : 0xFFFFFFFFu;
+            __syncthreads();
+            const int32_t in_pass = total_nz - p0 < kMarkCap ? total_nz - p0 : kMarkCap;
+            const int32_t node_lo = s_off[0];
+            const int32_t node_hi = s_off[in_pass - 1] + __popcll(s_word[in_pass - 1]);
+            // one thread per new node: locate its word (last word whose offset is <= j), then its bit
+            for (int32_t j = node_lo + (int32_t) threadIdx.x; j < node_hi; j += kBlock) {
+                int32_t lo = 0, hi = in_pass;                            // answer in [lo, hi)
+                while (hi - lo > 1) {
+                    const int32_t mid = (lo + hi) >> 1;
+                    if (s_off[mid] <= j) lo = mid; else hi = mid;
+                }
+                const int bit = select_bit64(s_word[lo], j - s_off[lo]);
+                const uint32_t node = (uint32_t) ((base + s_widx[lo]) * 64 + bit);
+                const int32_t pos = R + before + j;
+                RowExtent ext;
+                ext.start = load_off_rt(a.g_indptr, a.g_i64, node);
+                ext.end = load_off_rt(a.g_indptr, a.g_i64, (int64_t) node + 1);
+                a.src_nodes[pos] = (int32_t) node;
+                a.row_ext[pos] = ext;
+                append_hub_rows(a.st, a.hub_rows, is_hub_extent(ext.start, ext.end), pos);
+                const int64_t slot = hash_insert(a.slots, a.hmask, a.hshift, node, (uint32_t) pos);
+                a.slot_list[pos] = slot >= 0 ? (uint32_t) slot : 0xFFFFFFFFu;
+            }
+            __syncthreads();
         }
     }
 }
@@ -327,8 +371,18 @@ hipError_t launch_finish_layer(const Group& g, int layer_index, hipStream_t s)
     set_group_layer(g, layer_index, &a);
     fill_finish_template(c, layer_index, &a.f);
     const dim3 grid((unsigned) (a.f.row_tiles_max + a.f.mark_tiles), (unsigned) g.count);
-    hipLaunchKernelGGL(k_finish_phase1, grid, dim3(kBlock), 0, s, a);
-    hipLaunchKernelGGL(k_finish_phase3, grid, dim3(kBlock), 0, s, a);
+    // words of a tile per thread: the kernels' loops over them are unrolled for 1, 4 or 32
+    const int per = a.f.mark_tile_words / kBlock;
+    if (per <= 1) {
+        hipLaunchKernelGGL(k_finish_phase1<1>, grid, dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL(k_finish_phase3<1>, grid, dim3(kBlock), 0, s, a);
+    } else if (per <= 4) {
+        hipLaunchKernelGGL(k_finish_phase1<4>, grid, dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL(k_finish_phase3<4>, grid, dim3(kBlock), 0, s, a);
+    } else {
+        hipLaunchKernelGGL((k_finish_phase1<kMarkTileMax / kBlock>), grid, dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL((k_finish_phase3<kMarkTileMax / kBlock>), grid, dim3(kBlock), 0, s, a);
+    }
     return hipGetLastError();
 }
 

@@ -48,6 +48,8 @@ struct Layout {
     size_t draw_keys, draw_vals, draw_node, draw_slot;
     // frontier structures
     size_t mark_bitmap;
+    size_t mark_summary;      // one bit per word of the mark bitmap: "this word has a mark" (large graphs only)
+    int64_t summary_words;    // 0: no summary
     size_t seed_copy;         // [max_seeds] the batch's seeds, copied by its first kernel
     size_t hub_rows;          // [max nodes of a batch] rows whose CSR segment spans more than kHubChunks chunks
     size_t row_ext;           // [max nodes of a batch] CSR extent of every node of the batch's list (append-only)
@@ -57,6 +59,11 @@ struct Layout {
     size_t s_nbr[2], s_w[2], s_cnt[2];     // double-buffered by layer parity
     // CACHE_ONLY sampler: per-row chunk counts, chunk work list, CSR-aligned membership flags
     size_t plan_cnt, plan_g0, plan_desc, edge_flags;
+    // GNS_FLAGS_PER_CACHE: the induced subgraph S of Section 3.3 in compact form.  s_nodes lists, in CSR order,
+    // the entries that point into the cache; srec[g] = {flags of chunk g, number of such entries before chunk g},
+    // so a row's cached neighbors are s_nodes[P(start) .. P(end)) with P(e) = off[e >> 6] + popcount(flags below e).
+    size_t srec, s_nodes, sums_chunks;
+    int64_t chunk_tiles;
     int64_t max_chunks;
     // scan partials
     size_t sums_rows, sums_words, sums_marks, sums_plan;
@@ -91,8 +98,8 @@ struct Group;       // gns_kernels.hpp: the mini-batches one launch sequence ser
 struct BeginDyn;    //   the first kernel's per-replay arguments
 // Opaque host-side storage for the first kernel's two argument blocks (LayerArgs, BeginDyn).
 struct BeginArgsHost {
-    alignas(8) unsigned char fixed[2560];
-    alignas(8) unsigned char dyn[512];
+    alignas(8) unsigned char fixed[3072];
+    alignas(8) unsigned char dyn[768];
 };
 // One captured launch sequence of a group of mini-batches, kept by the group's first context.
 struct BatchGraph {
@@ -221,9 +228,9 @@ struct StageTimer {
     gns_ctx* c;
     hipStream_t s;
     int32_t slot;
-    StageTimer(gns_ctx* ctx, int32_t stage, hipStream_t stream) : c(ctx), s(stream), slot(-1)
+    StageTimer(gns_ctx* ctx, int32_t stage, hipStream_t stream, bool enabled = true) : c(ctx), s(stream), slot(-1)
     {
-        if (!(c->prof_mask & (1u << stage)) || c->prof_count >= c->prof_capacity) return;
+        if (!enabled || !(c->prof_mask & (1u << stage)) || c->prof_count >= c->prof_capacity) return;
         slot = c->prof_count++;
         c->prof[slot].stage = stage;
         (void) hipEventRecord(c->prof[slot].start, s);
@@ -251,6 +258,9 @@ gns_status run_sample_cache(gns_ctx* c, uint64_t seed, uint64_t epoch, bool wait
 gns_status activate_cache(gns_ctx* c);
 gns_status retire_cache(gns_ctx* c);
 gns_status finish_pending_draw(gns_ctx* c);
+
+// gns_induced.hip
+hipError_t launch_build_induced(gns_ctx* c, int cache_gen, hipStream_t s);
 
 // gns_sampler.hip
 // the previous layer's relabel shares this layer's first launch

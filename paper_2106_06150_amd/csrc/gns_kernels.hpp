@@ -14,6 +14,13 @@ namespace gns {
 
 constexpr int kMaxGroup = GNS_MAX_GROUP;
 
+// One record per aligned 64-entry chunk of the CSR entry array (GNS_FLAGS_PER_CACHE).
+struct alignas(16) ChunkRec {
+    uint64_t flags;            // bit e & 63: entry e points into the cache
+    uint32_t before;           // number of such entries in all earlier chunks
+    uint32_t pad;
+};
+
 struct SampleArgs {
     DeviceState* st;
     int layer_index;
@@ -36,6 +43,7 @@ struct SampleArgs {
     int32_t* s_cnt;
     int32_t* row_eligible;
     uint64_t* mark;
+    uint64_t* mark_summary;    // one bit per word of mark, or null (small graphs)
     const unsigned long long* slots;   // batch hash map node -> local id (holds this layer's dst nodes)
     uint32_t hmask, hshift;
     // CACHE_ONLY: per-batch plan and the CSR-aligned membership flags
@@ -49,6 +57,8 @@ struct SampleArgs {
     const uint64_t* coarse_bitmap;   // one bit per 2^coarse_shift ids (flag kernel, mode 2)
     int64_t coarse_words;
     int coarse_shift;
+    const ChunkRec* srec;      // induced subgraph (GNS_FLAGS_PER_CACHE): chunk records and the cached entries' node ids
+    const int32_t* s_nodes;
 };
 
 struct FinishArgs {
@@ -60,6 +70,7 @@ struct FinishArgs {
     const float* s_w;              // [R x fanout]
     const int32_t* s_cnt;          // [R]
     uint64_t* mark;                // [words]
+    uint64_t* mark_summary;        // [ceil(words / 64)] or null: bit w & 63 of word w >> 6 says mark[w] != 0
     int64_t words;
     unsigned long long* slots;
     uint32_t hmask, hshift;
@@ -86,14 +97,14 @@ struct FinishArgs {
 
 // Byte offsets of the sections of a context's per-batch scratch (the same for every context of a family).
 struct WsOffsets {
-    uint64_t state, mark, seed_copy, row_ext, hub_rows;
+    uint64_t state, mark, mark_summary, seed_copy, row_ext, hub_rows;
     uint64_t slot_list[2], hash_slots[2];
     uint64_t s_nbr[2], s_w[2], s_cnt[2];
     uint64_t plan_cnt, plan_g0, plan_desc;
     uint64_t sums_rows, sums_marks, sums_plan;
     uint64_t cache_block_bytes;    // distance between the two copies of what a cache draw writes
     int32_t uses_cache;
-    int32_t pad;
+    int32_t has_summary;
 };
 
 struct BlockPtrs {
@@ -156,6 +167,7 @@ __device__ __forceinline__ SampleArgs bind_sample(const LayerArgs& g, int b)
     a.s_cnt = at<int32_t>(ws, g.off.s_cnt[par]);
     a.row_eligible = q.cur.row_eligible;
     a.mark = at<uint64_t>(ws, g.off.mark);
+    a.mark_summary = g.off.has_summary ? at<uint64_t>(ws, g.off.mark_summary) : nullptr;
     a.slots = at<unsigned long long>(ws, g.off.hash_slots[parity]);
     a.plan_cnt = at<int32_t>(ws, g.off.plan_cnt);
     a.plan_g0 = at<int32_t>(ws, g.off.plan_g0);
@@ -168,6 +180,10 @@ __device__ __forceinline__ SampleArgs bind_sample(const LayerArgs& g, int b)
         a.flags = reinterpret_cast<uint64_t*>(reinterpret_cast<char*>(g.s.flags) + gen_shift);
         if (g.s.coarse_bitmap)
             a.coarse_bitmap = reinterpret_cast<const uint64_t*>(reinterpret_cast<const char*>(g.s.coarse_bitmap) + gen_shift);
+        if (g.s.srec) {
+            a.srec = reinterpret_cast<const ChunkRec*>(reinterpret_cast<const char*>(g.s.srec) + gen_shift);
+            a.s_nodes = reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(g.s.s_nodes) + gen_shift);
+        }
     }
     return a;
 }
@@ -188,6 +204,7 @@ __device__ __forceinline__ FinishArgs bind_finish(const LayerArgs& g, int b, boo
     a.s_w = at<float>(ws, g.off.s_w[par]);
     a.s_cnt = at<int32_t>(ws, g.off.s_cnt[par]);
     a.mark = at<uint64_t>(ws, g.off.mark);
+    a.mark_summary = g.off.has_summary ? at<uint64_t>(ws, g.off.mark_summary) : nullptr;
     a.slots = at<unsigned long long>(ws, g.off.hash_slots[parity]);
     a.sums_rows = at<int32_t>(ws, g.off.sums_rows);
     a.sums_marks = at<int32_t>(ws, g.off.sums_marks);

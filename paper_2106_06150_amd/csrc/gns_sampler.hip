@@ -20,6 +20,7 @@
 // (it is not a dst node of this layer) also sets its bit in the node-indexed
 // mark bitmap that the frontier stage turns into the src list.
 #include <string.h>
+#include <stdlib.h>
 #include "gns_kernels.hpp"
 
 namespace gns {
@@ -64,11 +65,21 @@ __device__ __forceinline__ void floyd_in_group(uint32_t m, int k, int k_loop, ui
 // A sampled id becomes a new src node unless it already owns a local id.  Returns what the relabel
 // step should find in the scratch slot: the node's local id as -(id + 1) if it has one (no second
 // lookup then), else the global id (>= 0), whose local id is assigned by the union step.
+// Sets node u's bit in the frontier mark bitmap.  (Looking at the bit first, to spare popular nodes'
+// words thousands of atomics per batch, measured slower: the extra dependent read costs more than the
+// atomics it saves.)
+__device__ __forceinline__ void mark_node(const SampleArgs& a, uint32_t u)
+{
+    atomicOr(reinterpret_cast<unsigned long long*>(&a.mark[u >> 6]), 1ull << (u & 63u));
+    if (a.mark_summary)
+        atomicOr(reinterpret_cast<unsigned long long*>(&a.mark_summary[u >> 12]), 1ull << ((u >> 6) & 63u));
+}
+
 __device__ __forceinline__ int32_t mark_if_new(const SampleArgs& a, uint32_t u)
 {
     const int32_t local = hash_lookup(a.slots, a.hmask, a.hshift, u);
     if (local >= 0) return -1 - local;
-    atomicOr(reinterpret_cast<unsigned long long*>(&a.mark[u >> 6]), 1ull << (u & 63u));
+    mark_node(a, u);
     return (int32_t) u;
 }
 
@@ -123,6 +134,124 @@ __global__ void __launch_bounds__(kBlock) k_sample_uniform(LayerArgs g, int rela
             a.s_cnt[row] = cnt;
             a.row_eligible[row] = (int32_t) m;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// One dst row per lane (fan-outs up to 16).  The list a row draws from is either its CSR segment (UNIFORM)
+// or, with the induced subgraph S of GNS_FLAGS_PER_CACHE, its cached neighbors s_nodes[P(start) .. P(end))
+// (CACHE_ONLY): in both cases a contiguous list of m ids of which min(k, m) ranks are chosen, so a lane
+// needs the row's extent, the k drawn entries and nothing else of the row.  Every lane runs Floyd's draw
+// for its own row with the loops over the k slots unrolled (the chosen ranks stay in registers); the
+// loads of all k entries, their weights and their hash slots are issued together.  A wave handles 64
+// rows at once and consecutive lanes read consecutive rows' extents and ids.
+__device__ __forceinline__ uint64_t bits_below(int64_t e)
+{
+    return (1ull << (e & 63)) - 1ull;
+}
+
+template <int KMAX, bool kInduced>
+__global__ void __launch_bounds__(kBlock) k_sample_lane(LayerArgs g, int relabel_blocks)
+{
+    const int64_t nblocks = (int64_t) gridDim.x - relabel_blocks;
+    if ((int64_t) blockIdx.x >= nblocks) {
+        relabel_body(bind_finish(g, (int) blockIdx.y, false), (int64_t) blockIdx.x - nblocks, relabel_blocks);
+        return;
+    }
+    const SampleArgs a = bind_sample(g, (int) blockIdx.y);
+    const int32_t R = a.st->num_dst[a.layer_index];
+    const int k = a.fanout;                         // <= KMAX
+    const uint32_t key0 = a.st->key0, key1 = a.st->key1;
+    const int32_t* list = kInduced ? a.s_nodes : a.indices;
+    for (int64_t row = (int64_t) blockIdx.x * kBlock + threadIdx.x; row < R; row += nblocks * kBlock) {
+        const RowExtent ext = a.row_ext[row];
+        const uint32_t v = (uint32_t) a.dst_nodes[row];
+        int64_t base = ext.start;
+        uint32_t m = (uint32_t) (ext.end - ext.start);
+        if (kInduced) {
+            m = 0;
+            if (ext.end > ext.start) {
+                const ChunkRec rs = a.srec[ext.start >> 6];
+                const ChunkRec re = a.srec[ext.end >> 6];
+                const uint32_t p0 = rs.before + (uint32_t) __popcll(rs.flags & bits_below(ext.start));
+                const uint32_t p1 = re.before + (uint32_t) __popcll(re.flags & bits_below(ext.end));
+                base = (int64_t) p0;
+                m = p1 - p0;
+            }
+        }
+        const int cnt = m > (uint32_t) k ? k : (int) m;
+        uint32_t chosen[KMAX];
+#pragma unroll
+        for (int s = 0; s < KMAX; ++s) chosen[s] = s < cnt ? (uint32_t) s : 0xFFFFFFFFu;     // m <= k: take all
+        if (m > (uint32_t) k) {
+            // slot s of (layer, node) is word s & 3 of the Philox block with counter word s >> 2
+            uint32_t word[KMAX];
+#pragma unroll
+            for (int c = 0; c < KMAX / 4; ++c) {
+                if (4 * c < k) {
+                    const Philox4 r = philox4x32_10(v, (uint32_t) c, a.layer_number, kTagNeighbor, key0, key1);
+                    word[4 * c] = r.w[0]; word[4 * c + 1] = r.w[1]; word[4 * c + 2] = r.w[2]; word[4 * c + 3] = r.w[3];
+                } else {
+                    word[4 * c] = word[4 * c + 1] = word[4 * c + 2] = word[4 * c + 3] = 0u;
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < KMAX; ++s) {
+                if (s < k) {
+                    const uint32_t j = m - (uint32_t) k + (uint32_t) s;
+                    const uint32_t t = __umulhi(word[s], j + 1u);
+                    bool dup = false;
+#pragma unroll
+                    for (int q = 0; q < s; ++q) dup = dup || chosen[q] == t;
+                    chosen[s] = dup ? j : t;
+                }
+            }
+        }
+        // entries of the chosen ranks, all in flight together
+        uint32_t u[KMAX];
+#pragma unroll
+        for (int s = 0; s < KMAX; ++s) u[s] = s < cnt ? (uint32_t) list[base + (int64_t) chosen[s]] : 0u;
+        float wgt[KMAX];
+        unsigned long long first[KMAX];
+#pragma unroll
+        for (int s = 0; s < KMAX; ++s) {
+            wgt[s] = 1.0f;
+            first[s] = kEmptySlot;
+            if (s < cnt) {
+                if (kInduced) wgt[s] = a.node_inv_pc[u[s]];
+                first[s] = a.slots[hash_start(u[s], a.hshift)];
+            }
+        }
+        // Section 3.4: coefficient p^C_u * k / min(k, N_C(v)), weight = 1 / coefficient (fp32 from the table on)
+        const float scale = !kInduced ? 1.0f
+                          : (a.wmode == GNS_W_UNBIASED) ? ((float) m / (float) (cnt > 0 ? cnt : 1))
+                                                        : ((float) cnt / (float) k);
+#pragma unroll
+        for (int s = 0; s < KMAX; ++s) {
+            if (s < cnt) {
+                int pos = 0;
+#pragma unroll
+                for (int q = 0; q < KMAX; ++q) pos += chosen[q] < chosen[s] ? 1 : 0;
+                // local id if the node has one already (first probe in hand), else mark it as a new src node
+                int32_t out;
+                const unsigned long long f = first[s];
+                if ((uint32_t) f == u[s] && f != kEmptySlot) {
+                    out = -1 - (int32_t) (f >> 32);
+                } else {
+                    const int32_t local = f == kEmptySlot ? -1 : hash_lookup(a.slots, a.hmask, a.hshift, u[s]);
+                    if (local >= 0) {
+                        out = -1 - local;
+                    } else {
+                        mark_node(a, u[s]);
+                        out = (int32_t) u[s];
+                    }
+                }
+                a.s_nbr[row * k + pos] = out;
+                a.s_w[row * k + pos] = kInduced ? wgt[s] * scale : 1.0f;
+            }
+        }
+        a.s_cnt[row] = cnt;
+        a.row_eligible[row] = (int32_t) m;
     }
 }
 
@@ -587,6 +716,9 @@ static void fill_sample_template_gen(gns_ctx* c, int layer_index, int cache_gen,
     a.coarse_bitmap = L.coarse_shift ? cache_ptr<uint64_t>(c, L.coarse_bitmap, gen) : nullptr;
     a.coarse_words = L.coarse_words;
     a.coarse_shift = L.coarse_shift;
+    const bool induced = c->uses_cache && c->config.flag_mode == GNS_FLAGS_PER_CACHE;
+    a.srec = induced ? cache_ptr<ChunkRec>(c, L.srec, gen) : nullptr;
+    a.s_nodes = induced ? cache_ptr<int32_t>(c, L.s_nodes, gen) : nullptr;
 }
 
 void fill_sample_template(gns_ctx* c, int layer_index, SampleArgs* out)
@@ -653,7 +785,28 @@ hipError_t launch_sample_layer(const Group& g, int layer_index, hipStream_t s)
         else              hipLaunchKernelGGL((KERNEL<64>), rb, tb, 0, s, a, (RL), ##__VA_ARGS__); \
     } while (0)
 
-    if (c->config.policy[layer_index] == GNS_UNIFORM) {
+    // fan-outs up to 16: one row per lane, for UNIFORM layers and for CACHE_ONLY layers that have the induced subgraph
+    const int policy = c->config.policy[layer_index];
+    const bool induced = policy == GNS_CACHE_ONLY && c->config.flag_mode == GNS_FLAGS_PER_CACHE;
+    // (one row per lane needs many rows to fill the chip: 64 rows make one wave)
+    static const int64_t lane_rows_min = getenv("GNS_LANE_ROWS_MIN") ? atoll(getenv("GNS_LANE_ROWS_MIN")) : 262144;
+    const bool enough_rows = induced || rows_max * g.count >= lane_rows_min;
+    if (a.s.fanout <= 16 && (policy == GNS_UNIFORM || induced) && enough_rows && !getenv("GNS_NO_LANE_SAMPLER")) {
+        StageTimer t(c, GNS_STAGE_SELECT, s, induced);
+        int64_t lane_blocks = (rows_max + kBlock - 1) / kBlock;
+        if (lane_blocks > cap) lane_blocks = cap;
+        const dim3 lb((unsigned) (lane_blocks + rl), gy);
+        if (induced) {
+            if (a.s.fanout <= 8) hipLaunchKernelGGL((k_sample_lane<8, true>), lb, tb, 0, s, a, rl);
+            else                 hipLaunchKernelGGL((k_sample_lane<16, true>), lb, tb, 0, s, a, rl);
+        } else {
+            if (a.s.fanout <= 8) hipLaunchKernelGGL((k_sample_lane<8, false>), lb, tb, 0, s, a, rl);
+            else                 hipLaunchKernelGGL((k_sample_lane<16, false>), lb, tb, 0, s, a, rl);
+        }
+        return hipGetLastError();
+    }
+
+    if (policy == GNS_UNIFORM) {
         const dim3 rb((unsigned) (row_blocks + rl), gy);
         GNS_LAUNCH_BY_G(k_sample_uniform, rl);
         return hipGetLastError();

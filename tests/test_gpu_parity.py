@@ -940,3 +940,61 @@ def test_config2_pipeline_as_the_benchmark_drives_it():
             B.gns_destroy(f)
         gns.close()
         _release_cached_memory()
+
+
+@pytest.mark.parametrize("fanouts,policies,flag_mode", [((6, 4, 3), (U, U, C), 1), ((5, 7), (CF, CF), 0), ((20, 5), (U, C), 0)])
+def test_mark_bitmap_summary_on_a_small_graph(fanouts, policies, flag_mode, monkeypatch):
+    """Graphs with millions of nodes keep a summary of the frontier mark bitmap (one bit per word) so that the
+    union step only reads words that carry marks.  Forced here on a small graph whose bitmap spans several
+    summary words and tiles; group launches and repeated batches check that both levels are left clean."""
+    monkeypatch.setenv("GNS_MARK_SUMMARY_MIN_WORDS", "1")
+    ip, ix = _small(n=20000, avg=10, seed=43)
+    n = ip.numel() - 1
+    F = 8
+    feat = _feat(n, F, seed=3)
+    csize, bs, count = 500, 70, 3
+    gns = GpuGns(ip, ix, feat, fanouts=fanouts, policies=policies, cache_size=csize, max_seeds=bs, flag_mode=flag_mode)
+    ctxs, keep, bufs, call = _group_setup(gns, count)
+    try:
+        L = len(fanouts)
+        last = L - 1
+        cache = oracle.sample_cache(ip.numpy(), 4, 0, csize)
+        B.gns_sample_cache(gns.ctx, 4, 0)
+        xin = [torch.zeros((b.array[last].cap_src, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        hout = [torch.zeros((b.array[last].cap_dst, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        for rnd in range(3):
+            seeds = [synth.uniform_seed_batch(n, bs - 9 * b, 40 * rnd + b).cuda() for b in range(count)]
+            bseeds = [600 + 10 * rnd + b for b in range(count)]
+            call.sample(bseeds, seeds)
+            call.gather([b.tensors[last]["src_nodes"] for b in bufs], [-1] * count, xin)
+            call.aggregate(last, xin, F, hout)
+            call.wait()
+            torch.cuda.synchronize()
+            for b in range(count):
+                ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), cache[1], csize, bseeds[b], seeds[b].cpu().numpy(),
+                                           list(fanouts), list(policies))
+                _check_group_batch(gns, bufs[b], ref, feat, xin[b], hout[b], F)
+    finally:
+        for f in ctxs[1:]:
+            B.gns_destroy(f)
+        gns.close()
+
+
+@pytest.mark.parametrize("summary", [False, True])
+def test_union_step_with_large_tiles_and_several_lds_passes(summary, monkeypatch):
+    """The union step walks the frontier mark bitmap in tiles of up to 8192 words and passes a tile's marked
+    words through LDS 1024 at a time.  Forced here: one tile of 4096 words over a 300 K-node graph, and a batch
+    whose new nodes mark nearly every word of it (several passes), with and without the bitmap's summary."""
+    monkeypatch.setenv("GNS_MARK_TILE_WORDS", "4096")
+    monkeypatch.setenv("GNS_MARK_SUMMARY_MIN_WORDS", "1" if summary else "1000000000")
+    ip, ix = random_symmetric_csr(300000, 8, np.random.default_rng(47))
+    ip, ix = torch.from_numpy(ip), torch.from_numpy(ix)
+    n = ip.numel() - 1
+    gns = GpuGns(ip, ix, None, fanouts=(12, 6), policies=(U, CF), cache_size=3000, max_seeds=3000, flag_mode=1)
+    try:
+        for trial in range(2):
+            seeds = synth.uniform_seed_batch(n, 3000 - 500 * trial, 70 + trial)
+            views, ref = full_parity(gns, cache_seed=5, epoch=trial, batch_seed=80 + trial, seeds=seeds)
+            assert ref[1].num_src - ref[1].num_dst > 40000          # new nodes of the input layer: most words marked
+    finally:
+        gns.close()
