@@ -128,6 +128,8 @@ class Workload:
             self.z_out = [torch.empty((self.bufs[i].array[last].cap_dst, self.H), dtype=torch.float32, device=dev)
                           for i in range(nctx)]
         self.walk_info = None
+        self.draw_stream = torch.cuda.Stream()
+        self.pending_epoch = None          # cache period whose draw has been enqueued ahead of time
 
     def close(self):
         for c_ in self.ctxs[1:]:
@@ -158,13 +160,27 @@ class Workload:
     def refresh_cache(self, b):
         # The draw fills the copy of the cache structures that is not in use: the batches in flight keep reading
         # the old cache, the batches enqueued from here on read the new one.
-        self.B.gns_sample_cache(self.ctx, self.sd["cache"], b // self.refresh, self.streams[0])
+        epoch = b // self.refresh
+        if self.pending_epoch == epoch:
+            self.B.gns_activate_cache(self.ctx)           # drawn ahead of time on the draw stream: switch over
+        else:
+            self.B.gns_sample_cache(self.ctx, self.sd["cache"], epoch, self.streams[0])
+        self.pending_epoch = None
+
+    def prepare_next_cache(self, b):
+        # Half a period ahead, on a stream of its own and without any host synchronisation: the next period's
+        # cache only depends on (seed, epoch), so its draw overlaps the current period's mini-batches.
+        if self.args.async_refresh and self.pending_epoch is None:
+            self.B.gns_sample_cache_async(self.ctx, self.sd["cache"], b // self.refresh + 1, self.draw_stream)
+            self.pending_epoch = b // self.refresh + 1
 
     def run(self, b0, b1, aggregate=True, one_stream=False):
         B, last, F = self.B, self.last, self.F
         for slot, ids in self.groups(b0, b1):
             if ids[0] % self.refresh == 0:
                 self.refresh_cache(ids[0])
+            elif not one_stream and ids[0] % self.refresh >= self.refresh // 2:
+                self.prepare_next_cache(ids[0])
             if one_stream:
                 slot = 0
             st = self.streams[slot]
@@ -515,6 +531,9 @@ def main():
     ap.add_argument("--shape-batches", type=int, default=40, help="mini-batches replayed for the byte counts")
     ap.add_argument("--group", type=int, default=10, help="mini-batches per launch sequence (gns_*_group)")
     ap.add_argument("--slots", type=int, default=2, help="groups kept in flight (one stream each; they share the cache)")
+    ap.add_argument("--async-refresh", type=int, default=1,
+                    help="1: the next period's cache is drawn half a period ahead on its own stream "
+                         "(gns_sample_cache_async / gns_activate_cache); 0: a synchronous draw at every period start")
     ap.add_argument("--flag-mode", type=int, default=1,
                     help="cache-membership flags of the CSR entries: 1 (default) once per cache draw, inside the timed "
                          "region like the draw itself; 0 per mini-batch, for the dst rows' CSR segments only")

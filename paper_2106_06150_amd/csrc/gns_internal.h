@@ -63,6 +63,7 @@ struct Layout {
     // the entries that point into the cache; srec[g] = {flags of chunk g, number of such entries before chunk g},
     // so a row's cached neighbors are s_nodes[P(start) .. P(end)) with P(e) = off[e >> 6] + popcount(flags below e).
     size_t srec, s_nodes, sums_chunks;
+
     int64_t chunk_tiles;
     int64_t max_chunks;
     // scan partials
@@ -169,6 +170,7 @@ struct gns_ctx {
     uint32_t batch_id;               // id of the last mini-batch enqueued on this context (from 1)
     uint32_t bad_reported;           // DeviceState::bad_seed as of the last report to the caller
     gns_ctx* static_child;           // root only: the context of gns_sample_blocks_static (scratch in the library's array)
+    char static_err[160];            // root only: why the library's scratch array is unavailable on this device, if it is
     // optional stage timing (benchmarks only)
     uint32_t prof_mask;
     int32_t prof_capacity;

@@ -735,7 +735,13 @@ static void launch_flag_kernel(gns_ctx* c, const LayerArgs& a, int count, int64_
     else if (c->lay.coarse_shift > 0 && coarse_bytes <= c->lds_bitmap_limit)
         hipLaunchKernelGGL((k_flag_chunks<2>), dim3((unsigned) c->num_cus), dim3(1024), coarse_bytes, s, a, count, all_chunks);
     else
-        hipLaunchKernelGGL((k_flag_chunks<0>), dim3((unsigned) c->num_cus * 8), dim3(kBlock), 0, s, a, count, all_chunks);
+    {
+        // every wave keeps 32 x 64 bitmap reads in flight, so a few waves per CU already reach the rate the
+        // memory system gives scattered reads; a grid that filled the chip would keep the kernels of other
+        // streams out for the whole pass
+        static const int per_cu = getenv("GNS_FLAG_BLOCKS_PER_CU") ? atoi(getenv("GNS_FLAG_BLOCKS_PER_CU")) : 2;
+        hipLaunchKernelGGL((k_flag_chunks<0>), dim3((unsigned) (c->num_cus * per_cu)), dim3(kBlock), 0, s, a, count, all_chunks);
+    }
 }
 
 // GNS_FLAGS_PER_CACHE: one pass over every aligned chunk of the CSR entry array, for the copy of the cache

@@ -32,11 +32,16 @@ gns_status static_scratch_setup(gns_ctx* root)
     if (e != hipSuccess) return ctx_fail(root, GNS_EHIP, "hipGetDevice", e);
     if (dev < 0 || dev >= kMaxDevices) return GNS_OK;             // no static path on such a device id
     if (!g_scratch_ptr[dev]) {
+        // A failure here (the array could not be placed on this device) only disables
+        // gns_sample_blocks_static, which then reports it; the context itself does not depend on the array.
         void* ptr = nullptr;
         e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
-        if (e != hipSuccess) return ctx_fail(root, GNS_EHIP, "hipGetSymbolAddress(static scratch)", e);
-        if (!ptr || (reinterpret_cast<uintptr_t>(ptr) & 255u))
-            return ctx_fail(root, GNS_EHIP, "static scratch: null or misaligned device address");
+        if (e != hipSuccess || !ptr || (reinterpret_cast<uintptr_t>(ptr) & 255u)) {
+            snprintf(root->static_err, sizeof(root->static_err), "static scratch array unavailable on device %d: %s", dev,
+                     e != hipSuccess ? hipGetErrorString(e) : "null or misaligned device address");
+            (void) hipGetLastError();
+            return GNS_OK;
+        }
         g_scratch_ptr[dev] = ptr;
     }
     if (root->lay.shared_begin > kStaticScratchBytes) return GNS_OK;   // too big: the entry point says so
@@ -57,6 +62,10 @@ extern "C" gns_status gns_sample_blocks_static(gns_ctx* ctx, uint64_t seed, cons
     if (!ctx) return GNS_EINVAL;
     gns_ctx* root = ctx->root;
     gns_ctx* c = root->static_child;
+    if (!c && root->static_err[0]) {
+        snprintf(ctx->err, sizeof(ctx->err), "gns_sample_blocks_static: %s", root->static_err);
+        return GNS_EHIP;
+    }
     if (!c) {
         snprintf(ctx->err, sizeof(ctx->err),
                  "gns_sample_blocks_static: the per-batch scratch of this graph and config needs %zu bytes, the "

@@ -998,3 +998,25 @@ def test_union_step_with_large_tiles_and_several_lds_passes(summary, monkeypatch
             assert ref[1].num_src - ref[1].num_dst > 40000          # new nodes of the input layer: most words marked
     finally:
         gns.close()
+
+
+def test_directed_adjacency():
+    """Nothing in the path assumes a symmetric adjacency (deg(i) is the row length, the cache draw takes the
+    owner row of a uniform entry): the symmetric graph and a directed thinning of it, both against the oracle."""
+    ip, ix = _small(n=4000, avg=16, seed=53)
+    n = ip.numel() - 1
+    rng = np.random.default_rng(3)
+    keep = rng.random(ix.numel()) < 0.7                                   # drop 30 % of the entries, one direction at a time
+    row = np.repeat(np.arange(n), np.diff(ip.numpy()))
+    ip_d = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(np.bincount(row[keep], minlength=n), out=ip_d[1:])
+    ix_d = ix.numpy()[keep]
+    for indptr, indices in ((ip, ix), (torch.from_numpy(ip_d), torch.from_numpy(ix_d))):
+        gns = GpuGns(indptr, indices, _feat(n, 16), fanouts=(6, 5), policies=(CF, C), cache_size=300, max_seeds=100,
+                     flag_mode=1)
+        try:
+            for trial in range(2):
+                seeds = synth.uniform_seed_batch(n, 100 - 30 * trial, 11 + trial)
+                full_parity(gns, cache_seed=14, epoch=trial, batch_seed=15 + trial, seeds=seeds)
+        finally:
+            gns.close()
