@@ -103,7 +103,10 @@ class Workload:
                                     cache_probability=B.GNS_PROB_WALK if self.walk else B.GNS_PROB_DEGREE)
         self.ws = B.alloc_workspace(self.graph, self.config, dev)
         self.ctx = B.gns_create(self.graph, self.config, self.ws)
-        self.G = max(1, min(args.group, B.GNS_MAX_GROUP, self.refresh))
+        # measured: groups of 5 on two streams are best when the features live in HBM; with the PCIe-bound gather
+        # of a host feature store larger groups are
+        group = args.group if args.group > 0 else (10 if self.on_host else 5)
+        self.G = max(1, min(group, B.GNS_MAX_GROUP, self.refresh))
         self.S = max(1, args.slots)
         nctx = self.G * self.S
         self.ctxs, self.fork_ws = [self.ctx], []
@@ -529,7 +532,8 @@ def main():
                          "GPU), reported as a variant next to the configured pinned-host store")
     ap.add_argument("--cpu-batches", type=int, default=32, help="mini-batches the CPU oracle is timed on (0: skip)")
     ap.add_argument("--shape-batches", type=int, default=40, help="mini-batches replayed for the byte counts")
-    ap.add_argument("--group", type=int, default=10, help="mini-batches per launch sequence (gns_*_group)")
+    ap.add_argument("--group", type=int, default=0,
+                    help="mini-batches per launch sequence (gns_*_group); 0: 5, or 10 with a host feature store")
     ap.add_argument("--slots", type=int, default=2, help="groups kept in flight (one stream each; they share the cache)")
     ap.add_argument("--async-refresh", type=int, default=1,
                     help="1: the next period's cache is drawn half a period ahead on its own stream "

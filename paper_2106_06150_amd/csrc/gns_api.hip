@@ -164,11 +164,16 @@ bool compute_layout(const gns_graph* g, const gns_config* cfg, Layout* out, char
     if (uses_cache && (size_t) L.words * 8 > kLdsBitmapBytes) {
         int sh = 1;
         while (sh <= 4 && (size_t) (((n >> sh) + 63) / 64 + 1) * 8 > kLdsBitmapBytes) ++sh;
-        if (sh <= 4) {
-            L.coarse_shift = sh;
-            L.coarse_words = ((n >> sh) + 63) / 64 + 1;
-            L.coarse_bitmap = take((size_t) (L.coarse_words + 1) * 8);
+        // Too big for LDS even at one bit per 16 ids: the coarse bitmap then stays in global memory, where it
+        // is small enough for every XCD's L2 (n / 128 bytes at one bit per 16 ids), and still spares most entries
+        // the read of the exact bitmap, which costs a 64-byte fetch over the fabric each time.
+        if (sh > 4) {
+            sh = 4;
+            if (const char* e = getenv("GNS_COARSE_SHIFT")) { const int v = atoi(e); if (v >= 1 && v <= 6) sh = v; }
         }
+        L.coarse_shift = sh;
+        L.coarse_words = ((n >> sh) + 63) / 64 + 1;
+        L.coarse_bitmap = take((size_t) (L.coarse_words + 1) * 8);
     }
     L.cache_nodes = take((size_t) (C > 0 ? C : 1) * 4);
     L.cache_feat = take((size_t) (C > 0 ? C : 1) * (size_t) (g->feat_dim > 0 ? g->feat_dim : 1) * 4);

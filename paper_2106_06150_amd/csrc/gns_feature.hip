@@ -191,74 +191,73 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggGroup g)
     const uint32_t num_src = (uint32_t) (a.num_src_dev ? *a.num_src_dev : a.num_src);
     constexpr int kEdges = 8;       // edges whose rows are in flight together
     if (kVec && (g.slices > 1 || F <= 4 * kLanes)) {
-        // One float4 per lane covers a row.  The three dependent reads of a row (its offsets, its
-        // edges, its sources' rows) are staggered over three consecutive rows of the group, so every
-        // trip of the loop issues all three kinds of load before it waits for any of them:
-        //   row i: source rows -> fma;  row i+1: indices and weights;  row i+2: offsets.
+        // One float4 per lane covers a row (or the row's column slice).  Branch-free inner loop: the first
+        // kSlots lanes of a row's group read one edge each (index and weight, one coalesced read), every lane
+        // then takes edge t from lane t of its group, so the reads of up to kSlots source rows are issued back
+        // to back; slots past the row's end repeat its last edge with weight 0 (adds an exact 0), rows with
+        // more than kSlots edges take further rounds.  All lanes of the wave stay converged: trip counts are
+        // wave-uniform (the shuffles need every source lane).
+        constexpr int kSlots = kLanes < 8 ? kLanes : 8;
         const int64_t F4 = F >> 2;
-        const float4* x4 = reinterpret_cast<const float4*>(a.x_src) + col0;
+        const int col = col0 + lane < (int) F4 ? col0 + lane : (int) F4 - 1;       // idle lanes repeat the last column
         const bool has = col0 + lane < (int) F4;
-        int32_t b0 = 0, e0 = 0, b1 = 0, e1 = 0, b2 = 0, e2 = 0;          // offsets of rows i, i+1, i+2
-        uint32_t j1[kEdges];                                              // first kEdges edges of row i+1
-        float w1[kEdges];
-        const int64_t r0 = group, r1 = group + num_groups, r2 = group + 2 * num_groups;
-        if (r0 < count) { b0 = a.indptr[r0]; e0 = a.indptr[r0 + 1]; }
-        if (r1 < count) { b1 = a.indptr[r1]; e1 = a.indptr[r1 + 1]; }
-        if (r2 < count) { b2 = a.indptr[r2]; e2 = a.indptr[r2 + 1]; }
-#pragma unroll
-        for (int t = 0; t < kEdges; ++t) {                                // edges of row i (kept in j1 / w1)
-            const int32_t q = b0 + t;
-            j1[t] = (q < e0) ? (uint32_t) a.indices[q] : 0xFFFFFFFFu;
-            w1[t] = (q < e0) ? a.weights[q] : 0.f;
-        }
-        for (int64_t row = group; row < count; row += num_groups) {
-            // (1) source rows of this row's first kEdges edges
-            float4 x[kEdges];
-            float w[kEdges];
-#pragma unroll
-            for (int t = 0; t < kEdges; ++t) {
-                const bool ok = j1[t] < num_src;
-                w[t] = ok ? w1[t] : 0.f;
-                x[t] = (ok && has) ? x4[(int64_t) j1[t] * F4 + lane] : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-            // (2) edges of the next row, (3) offsets of the row after the next
-#pragma unroll
-            for (int t = 0; t < kEdges; ++t) {
-                const int32_t q = b1 + t;
-                j1[t] = (q < e1) ? (uint32_t) a.indices[q] : 0xFFFFFFFFu;
-                w1[t] = (q < e1) ? a.weights[q] : 0.f;
-            }
-            const int64_t r3 = row + 3 * num_groups;
-            int32_t b3 = 0, e3 = 0;
-            if (r3 < count) { b3 = a.indptr[r3]; e3 = a.indptr[r3 + 1]; }
-
+        const float4* x4 = reinterpret_cast<const float4*>(a.x_src) + col;
+        // row j of x_src starts at float4 index j * F4: a shift when F4 is a power of two and the product fits
+        // 32 bits (integer multiplies run at a quarter of the rate of other vector instructions)
+        const bool by_shift = (F4 & (F4 - 1)) == 0 && (uint64_t) num_src * (uint64_t) F4 < ((uint64_t) 1 << 32);
+        const uint32_t f4_shift = (uint32_t) __builtin_ctzll((unsigned long long) F4);
+        const int64_t trips = (count + num_groups - 1) / num_groups;                 // the same for every group
+        for (int64_t it = 0; it < trips; ++it) {
+            const int64_t row = group + it * num_groups;
+            const bool live = row < count;
+            int32_t b = 0, e = 0;
+            if (live) { b = a.indptr[row]; e = a.indptr[row + 1]; }
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int32_t q0 = b; __any(q0 < e); q0 += kSlots) {
+                const int32_t here = e - q0 < kSlots ? (e - q0 > 0 ? e - q0 : 0) : kSlots;   // edges of this round
+                const bool mine = lane < here;
+                uint32_t my_j = mine ? (uint32_t) a.indices[q0 + lane] : 0u;
+                float my_w = mine ? a.weights[q0 + lane] : 0.f;
+                const bool bad = my_j >= num_src;                    // an index outside [0, num_src) is skipped
+                if (bad) { my_j = 0u; my_w = 0.f; }
+                const bool any_bad = __any(bad && mine);
+                float4 x[kSlots];
+                float w[kSlots];
 #pragma unroll
-            for (int t = 0; t < kEdges; ++t) {                            // edge order, one fma per term
-                if (b0 + t < e0) {
-                    acc.x = fmaf(w[t], x[t].x, acc.x);
-                    acc.y = fmaf(w[t], x[t].y, acc.y);
-                    acc.z = fmaf(w[t], x[t].z, acc.z);
-                    acc.w = fmaf(w[t], x[t].w, acc.w);
+                for (int t = 0; t < kSlots; ++t) {
+                    w[t] = 0.f;
+                    x[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (t < 4 || __any(t < here)) {                  // slots no row of this wave needs are skipped
+                        const int from = t < here ? t : (here > 0 ? here - 1 : 0);
+                        const uint32_t j = (uint32_t) __shfl((int) my_j, from, kLanes);
+                        const float wt = __shfl(my_w, from, kLanes);
+                        w[t] = t < here ? wt : 0.f;
+                        x[t] = by_shift ? x4[j << f4_shift] : x4[(int64_t) j * F4];
+                    }
+                }
+                if (any_bad) {
+                    // rare: a skipped edge must not contribute even a NaN of the row it was redirected to
+#pragma unroll
+                    for (int t = 0; t < kSlots; ++t) {
+                        const int from = t < here ? t : (here > 0 ? here - 1 : 0);
+                        if (__shfl((int) (bad && mine), from, kLanes)) x[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < kSlots; ++t) {                    // edge order, one fma per term
+                    if (t < 4 || __any(t < here)) {
+                        acc.x = fmaf(w[t], x[t].x, acc.x);
+                        acc.y = fmaf(w[t], x[t].y, acc.y);
+                        acc.z = fmaf(w[t], x[t].z, acc.z);
+                        acc.w = fmaf(w[t], x[t].w, acc.w);
+                    }
                 }
             }
-            for (int32_t q = b0 + kEdges; q < e0; ++q) {                  // rows with more edges: the rest in order
-                const uint32_t j = (uint32_t) a.indices[q];
-                if (j < num_src && has) {
-                    const float wq = a.weights[q];
-                    const float4 xq = x4[(int64_t) j * F4 + lane];
-                    acc.x = fmaf(wq, xq.x, acc.x);
-                    acc.y = fmaf(wq, xq.y, acc.y);
-                    acc.z = fmaf(wq, xq.z, acc.z);
-                    acc.w = fmaf(wq, xq.w, acc.w);
-                }
+            if (e > b) {
+                const float inv_n = 1.0f / (float) (e - b);           // one division per row, then four products
+                acc.x *= inv_n; acc.y *= inv_n; acc.z *= inv_n; acc.w *= inv_n;
             }
-            if (e0 > b0) {
-                const float n_v = (float) (e0 - b0);
-                acc.x /= n_v; acc.y /= n_v; acc.z /= n_v; acc.w /= n_v;
-            }
-            if (has) store_streaming(reinterpret_cast<float4*>(a.out + row * F) + col0 + lane, acc);
-            b0 = b1; e0 = e1; b1 = b2; e1 = e2; b2 = b3; e2 = e3;
+            if (live && has) store_streaming(reinterpret_cast<float4*>(a.out + row * F) + col0 + lane, acc);
         }
         return;
     }

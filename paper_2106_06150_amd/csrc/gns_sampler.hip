@@ -347,7 +347,8 @@ constexpr int kFlagBatch = 64;      // work-list entries a wave fetches at once 
 //   kCareful: the set may hold the last chunk of the entry array, whose tail lanes lie beyond
 //   num_entries; those lanes re-read the last entry and are masked out of the ballot.
 //   kMode 0: the bitmap is read from global memory; 1: from LDS; 2: LDS holds the coarse bitmap (one bit
-//   per group of ids): only the entries whose group has a cached node go on to read the exact bitmap.
+//   per group of ids): only the entries whose group has a cached node go on to read the exact bitmap;
+//   3: as 2 with the coarse bitmap in global memory (small enough to stay in every XCD's L2).
 template <int kMode, bool kCareful>
 __device__ __forceinline__ void flag_chunk_set(const SampleArgs& a, const uint32_t* lds32, int32_t my_chunk, int sub,
                                                int lane, uint32_t* lo, uint32_t* hi)
@@ -370,9 +371,10 @@ __device__ __forceinline__ void flag_chunk_set(const SampleArgs& a, const uint32
     for (int i = 0; i < kFlagUnroll; ++i) {
         if (kMode == 1)      w[i] = lds32[u[i] >> 5];
         else if (kMode == 0) w[i] = exact32[u[i] >> 5];
-        else                 w[i] = lds32[(u[i] >> a.coarse_shift) >> 5];
+        else if (kMode == 2) w[i] = lds32[(u[i] >> a.coarse_shift) >> 5];
+        else                 w[i] = reinterpret_cast<const uint32_t*>(a.coarse_bitmap)[(u[i] >> a.coarse_shift) >> 5];
     }
-    if (kMode == 2) {
+    if (kMode >= 2) {
 #pragma unroll
         for (int i = 0; i < kFlagUnroll; ++i) {
             const bool maybe = (w[i] >> ((u[i] >> a.coarse_shift) & 31u)) & 1u;
@@ -429,7 +431,7 @@ __global__ void k_flag_chunks(LayerArgs g, int count, int64_t all_chunks)
 {
     extern __shared__ uint4 lds_bitmap16[];
     SampleArgs a = count > 0 ? bind_sample(g, 0) : g.s;
-    if (kMode != 0) {
+    if (kMode == 1 || kMode == 2) {
         const uint4* src = reinterpret_cast<const uint4*>(kMode == 1 ? a.cache_bitmap : a.coarse_bitmap);
         const int64_t n16 = ((kMode == 1 ? a.bitmap_words : a.coarse_words) + 1) / 2;
         constexpr int kFill = 4;
@@ -734,6 +736,11 @@ static void launch_flag_kernel(gns_ctx* c, const LayerArgs& a, int count, int64_
         hipLaunchKernelGGL((k_flag_chunks<1>), dim3((unsigned) c->num_cus), dim3(1024), lds_bytes, s, a, count, all_chunks);
     else if (c->lay.coarse_shift > 0 && coarse_bytes <= c->lds_bitmap_limit)
         hipLaunchKernelGGL((k_flag_chunks<2>), dim3((unsigned) c->num_cus), dim3(1024), coarse_bytes, s, a, count, all_chunks);
+    else if (c->lay.coarse_shift > 0 && !getenv("GNS_NO_COARSE_L2"))
+    {
+        static const int per_cu = getenv("GNS_FLAG_BLOCKS_PER_CU") ? atoi(getenv("GNS_FLAG_BLOCKS_PER_CU")) : 2;
+        hipLaunchKernelGGL((k_flag_chunks<3>), dim3((unsigned) (c->num_cus * per_cu)), dim3(kBlock), 0, s, a, count, all_chunks);
+    }
     else
     {
         // every wave keeps 32 x 64 bitmap reads in flight, so a few waves per CU already reach the rate the
