@@ -307,6 +307,40 @@ class Workload:
         return {k: v / count for k, v in acc.items()}
 
 
+    # ---- input nodes per mini-batch of plain node-wise sampling against GNS (the comparison of the paper's Table 3) ----
+    def input_node_shapes(self, b0, count):
+        torch, B = self.torch, self.B
+        U, CF, C = B.GNS_UNIFORM, B.GNS_CACHE_FIRST, B.GNS_CACHE_ONLY
+        settings = {"ns_all_layers_uniform": [U] * self.L,
+                    "gns_upper_layers_uniform": [U] * (self.L - 1) + [C],
+                    "gns_upper_layers_cache_first": [CF] * (self.L - 1) + [C]}
+        out = {}
+        B.gns_sample_cache(self.ctx, self.sd["cache"], b0 // self.refresh)
+        nodes_ptr, csize, _, _ = B.gns_cache_view(self.ctx)
+        is_cached = torch.zeros(self.n, dtype=torch.bool, device=self.dev)
+        is_cached[B.device_view_i32(nodes_ptr, csize, self.dev).to(torch.int64)] = True
+        for name, pol in settings.items():
+            cfg = B.make_config(self.fanouts, pol, self.cache_size, self.batch, flag_mode=self.args.flag_mode)
+            ws = B.alloc_workspace(self.graph, cfg, self.dev)
+            ctx = B.gns_create(self.graph, cfg, ws)
+            bufs = B.BlockBuffers(self.graph, cfg, self.dev)
+            if any(p != U for p in pol):
+                B.gns_sample_cache(ctx, self.sd["cache"], b0 // self.refresh)       # the same cache: (seed, epoch) fix it
+            total = cached = 0
+            for b in range(b0, b0 + count):
+                B.gns_sample_blocks(ctx, self.sd["batch"] + b, self.seeds[b], bufs.array)
+                total += bufs.array[self.last].num_src
+                cached += int(is_cached[bufs.views(self.last)["src_nodes"].to(torch.int64)].sum())
+            out[name] = {"input_nodes": round(total / count, 1), "of_them_cached": round(cached / count, 1)}
+            B.gns_destroy(ctx)
+            del ws, bufs
+        ns = out["ns_all_layers_uniform"]["input_nodes"]
+        out["ns_over_gns"] = {k_: round(ns / v["input_nodes"], 2) for k_, v in out.items() if k_.startswith("gns_")}
+        out["note"] = ("averages over %d mini-batches with one cache; the paper's Table 3 reports the same comparison on "
+                       "its datasets (its GNS also samples the upper layers cache first)" % count)
+        return out
+
+
 def algorithmic_bytes(w, avg, flag_mode):
     """Bytes each stage has to move per mini-batch (averages over the replayed batches)."""
     n, F, C = w.n, w.F, w.cache_size
@@ -468,6 +502,8 @@ def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat
         "group": w.G, "slots": w.S, "warmup_steps_run": warm, "setup_s": round(setup_s, 1),
         "walk_probability": w.walk_info,
     }
+    if args.input_node_batches > 0 and not w.walk and not feat_in_hbm:
+        res["input_nodes"] = w.input_node_shapes(b2, min(K, args.input_node_batches))
     if w.H > 0 and "dense" in launch_us:
         fl = 2.0 * avg["rows"] * 2 * F * w.H
         res["dense_update"] = {"hidden": w.H, "avg_launch_us": round(launch_us["dense"], 2), "bound": "mfma", "dtype": "f32",
@@ -532,6 +568,8 @@ def main():
                          "GPU), reported as a variant next to the configured pinned-host store")
     ap.add_argument("--cpu-batches", type=int, default=32, help="mini-batches the CPU oracle is timed on (0: skip)")
     ap.add_argument("--shape-batches", type=int, default=40, help="mini-batches replayed for the byte counts")
+    ap.add_argument("--input-node-batches", type=int, default=5,
+                    help="mini-batches for the input-node comparison of plain node-wise sampling and GNS (0: skip)")
     ap.add_argument("--group", type=int, default=0,
                     help="mini-batches per launch sequence (gns_*_group); 0: 5, or 10 with a host feature store")
     ap.add_argument("--slots", type=int, default=2, help="groups kept in flight (one stream each; they share the cache)")
@@ -617,6 +655,7 @@ def main():
         "one_stream": main_res["one_stream"],
         "walk_probability": main_res["walk_probability"],
         "dense_update": main_res.get("dense_update"),
+        "input_nodes": main_res.get("input_nodes"),
         "per_config": per_config,
     }
     print(json.dumps(out))
