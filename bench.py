@@ -133,6 +133,8 @@ class Workload:
         self.walk_info = None
         self.draw_stream = torch.cuda.Stream()
         self.pending_epoch = None          # cache period whose draw has been enqueued ahead of time
+        self.draw_ms = None                # the first (synchronous) draw, host clock
+        self.async_draw = args.async_refresh > 0
 
     def close(self):
         for c_ in self.ctxs[1:]:
@@ -167,13 +169,22 @@ class Workload:
         if self.pending_epoch == epoch:
             self.B.gns_activate_cache(self.ctx)           # drawn ahead of time on the draw stream: switch over
         else:
-            self.B.gns_sample_cache(self.ctx, self.sd["cache"], epoch, self.streams[0])
+            t0 = time.perf_counter()
+            self.B.gns_sample_cache(self.ctx, self.sd["cache"], epoch, self.streams[0])     # returns when the draw is done
+            if self.draw_ms is None and b == 0:
+                self.torch.cuda.synchronize()
+                self.draw_ms = 1e3 * (time.perf_counter() - t0)
+                # A long draw (a flag pass over billions of CSR entries) keeps the L2 request queues full and slows the
+                # mini-batches it overlaps by more than it saves (measured: -24 % on the 111 M-node graph, +6 % on the
+                # 1 M- and 2.4 M-node graphs): draw ahead of time only when a draw is short.
+                if self.args.async_refresh < 0:
+                    self.async_draw = self.draw_ms < 5.0
         self.pending_epoch = None
 
     def prepare_next_cache(self, b):
         # Half a period ahead, on a stream of its own and without any host synchronisation: the next period's
         # cache only depends on (seed, epoch), so its draw overlaps the current period's mini-batches.
-        if self.args.async_refresh and self.pending_epoch is None:
+        if self.async_draw and self.pending_epoch is None:
             self.B.gns_sample_cache_async(self.ctx, self.sd["cache"], b // self.refresh + 1, self.draw_stream)
             self.pending_epoch = b // self.refresh + 1
 
@@ -500,6 +511,7 @@ def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat
                        w.cache_size, w.refresh, w.fanouts, w.batch),
         "max_degree": w.g.max_degree,
         "group": w.G, "slots": w.S, "warmup_steps_run": warm, "setup_s": round(setup_s, 1),
+        "cache_draw_ahead_of_time": bool(w.async_draw), "first_cache_draw_ms": round(w.draw_ms or 0.0, 3),
         "walk_probability": w.walk_info,
     }
     if args.input_node_batches > 0 and not w.walk and not feat_in_hbm:
@@ -573,9 +585,10 @@ def main():
     ap.add_argument("--group", type=int, default=0,
                     help="mini-batches per launch sequence (gns_*_group); 0: 5, or 10 with a host feature store")
     ap.add_argument("--slots", type=int, default=2, help="groups kept in flight (one stream each; they share the cache)")
-    ap.add_argument("--async-refresh", type=int, default=1,
+    ap.add_argument("--async-refresh", type=int, default=-1,
                     help="1: the next period's cache is drawn half a period ahead on its own stream "
-                         "(gns_sample_cache_async / gns_activate_cache); 0: a synchronous draw at every period start")
+                         "(gns_sample_cache_async / gns_activate_cache); 0: a synchronous draw at every period start; "
+                         "-1: ahead of time when the workload's first draw took under 5 ms")
     ap.add_argument("--flag-mode", type=int, default=1,
                     help="cache-membership flags of the CSR entries: 1 (default) once per cache draw, inside the timed "
                          "region like the draw itself; 0 per mini-batch, for the dst rows' CSR segments only")
@@ -638,6 +651,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": main_res.pop("workload"), "max_degree": main_res.pop("max_degree"),
                    "mini_batches_per_launch": main_res["group"], "groups_in_flight": main_res["slots"],
+                   "cache_draw_ahead_of_time": main_res["cache_draw_ahead_of_time"],
                    "cache_flags": "per mini-batch (CSR-segment scan)" if args.flag_mode == 0 else "per cache draw",
                    "upper_layers": args.upper_policy, "cache_probability": args.cache_probability,
                    "timing": "median of %d windows of %d steps, host clock between device synchronisations"

@@ -153,12 +153,6 @@ struct AggBatch {
 struct AggGroup {
     AggBatch b[GNS_MAX_GROUP];
     int32_t feat_dim;
-    // Column slices: the chip's 8 XCDs have an L2 each and workgroups go to them round robin, so block
-    // x of a launch runs on XCD x % 8.  With `slices` > 1 a block works on float4 columns
-    // [slice * kLanes, (slice + 1) * kLanes) of its rows only, slice = (x % 8) % slices: each XCD's L2 then
-    // holds one slice of the few thousand hot source rows instead of all of them.
-    int32_t slices;
-    int32_t fold;       // XCDs that share a slice (8 / slices when that divides, else 1: surplus XCDs' blocks stand down)
 };
 
 // the view of one batch the kernel body works on
@@ -166,7 +160,268 @@ struct AggArgs : AggBatch {
     int32_t feat_dim;
 };
 
-template <int kLanes, bool kVec>
+// Rows of at most kLanes float4 columns, one column per lane: the plain form of the loop below, for widths whose
+// rows do not start on cache-line boundaries or do not fill several columns per lane.  Branch-free inner loop:
+// the first kSlots lanes of a row's group read one edge each (index and weight, one coalesced read), every lane
+// then takes edge t from lane t of its group, so the reads of up to kSlots source rows are issued back to back;
+// slots past the row's end repeat its last edge with weight 0 (adds an exact 0), rows with more than kSlots edges
+// take further rounds.  All lanes of the wave stay converged: trip counts are wave-uniform (the shuffles need
+// every source lane).
+template <int kLanes>
+__device__ __forceinline__ void aggregate_rows_one_column(const AggArgs& a, int64_t group, int64_t num_groups, int64_t count,
+                                                          uint32_t num_src)
+{
+    constexpr int kSlots = kLanes < 8 ? kLanes : 8;
+    const int lane = (int) (threadIdx.x % kLanes);
+    const int64_t F = a.feat_dim;
+    const int64_t F4 = F >> 2;
+    const int col = lane < (int) F4 ? lane : (int) F4 - 1;       // idle lanes repeat the last column
+    const bool has = lane < (int) F4;
+    const float4* x4 = reinterpret_cast<const float4*>(a.x_src) + col;
+    // row j of x_src starts at float4 index j * F4: a shift when F4 is a power of two and the product fits
+    // 32 bits (integer multiplies run at a quarter of the rate of other vector instructions)
+    const bool by_shift = (F4 & (F4 - 1)) == 0 && (uint64_t) num_src * (uint64_t) F4 < ((uint64_t) 1 << 32);
+    const uint32_t f4_shift = (uint32_t) __builtin_ctzll((unsigned long long) F4);
+    const int64_t trips = (count + num_groups - 1) / num_groups;                 // the same for every group
+    for (int64_t it = 0; it < trips; ++it) {
+        const int64_t row = group + it * num_groups;
+        const bool live = row < count;
+        int32_t b = 0, e = 0;
+        if (live) { b = a.indptr[row]; e = a.indptr[row + 1]; }
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int32_t q0 = b; __any(q0 < e); q0 += kSlots) {
+            const int32_t here = e - q0 < kSlots ? (e - q0 > 0 ? e - q0 : 0) : kSlots;   // edges of this round
+            const bool mine = lane < here;
+            uint32_t my_j = mine ? (uint32_t) a.indices[q0 + lane] : 0u;
+            float my_w = mine ? a.weights[q0 + lane] : 0.f;
+            const bool bad = my_j >= num_src;                    // an index outside [0, num_src) is skipped
+            if (bad) { my_j = 0u; my_w = 0.f; }
+            // A row that has run out of edges while others of its wave go on has nothing of its own to repeat: what
+            // its slots read (source row 0) is replaced by zeros like the row of a skipped edge.  (A row without any
+            // edge is set to 0 at the end.)
+            const bool spent = here == 0 && q0 != b;
+            const bool any_bad = __any((bad && mine) || spent);
+            float4 x[kSlots];
+            float w[kSlots];
+#pragma unroll
+            for (int t = 0; t < kSlots; ++t) {
+                w[t] = 0.f;
+                x[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (t < 4 || __any(t < here)) {                  // slots no row of this wave needs are skipped
+                    const int from = t < here ? t : (here > 0 ? here - 1 : 0);
+                    const uint32_t j = (uint32_t) __shfl((int) my_j, from, kLanes);
+                    const float wt = __shfl(my_w, from, kLanes);
+                    w[t] = t < here ? wt : 0.f;
+                    x[t] = by_shift ? x4[j << f4_shift] : x4[(int64_t) j * F4];
+                }
+            }
+            if (any_bad) {
+                // rare: a skipped edge must not contribute even a NaN of the row it was redirected to
+#pragma unroll
+                for (int t = 0; t < kSlots; ++t) {
+                    const int from = t < here ? t : (here > 0 ? here - 1 : 0);
+                    if (__shfl((int) (bad && mine), from, kLanes) || spent) x[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < kSlots; ++t) {                    // edge order, one fma per term
+                if (t < 4 || __any(t < here)) {
+                    acc.x = fmaf(w[t], x[t].x, acc.x);
+                    acc.y = fmaf(w[t], x[t].y, acc.y);
+                    acc.z = fmaf(w[t], x[t].z, acc.z);
+                    acc.w = fmaf(w[t], x[t].w, acc.w);
+                }
+            }
+        }
+        if (e > b) {
+            const float inv_n = 1.0f / (float) (e - b);           // one division per row, then four products
+            acc.x *= inv_n; acc.y *= inv_n; acc.z *= inv_n; acc.w *= inv_n;
+        } else {
+            // a row without edges took part in its wave's round with weight 0 on source row 0: its result is 0
+            // whatever that row holds
+            acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        if (live && has) store_streaming(reinterpret_cast<float4*>(a.out + row * F) + lane, acc);
+    }
+}
+
+// Rows whose features are float4-aligned and fit kLanes * kPer float4 columns: a group of kLanes lanes owns a
+// dst row, lane l accumulates columns l, l + kLanes, ... (kPer of them).  Branch-free inner loop: the first
+// kSlots lanes of the group hold one edge each (index and weight, one coalesced read), every lane then takes
+// edge t from lane t of its group, so the reads of the source rows are issued back to back; slots past the
+// row's end repeat its last edge with weight 0 (adds an exact 0), rows with more than kSlots edges take
+// further rounds.  All lanes of the wave stay converged: trip counts are wave-uniform (the shuffles need
+// every source lane).
+// A row is a chain of dependent accesses (row extent -> edges -> source rows -> store); it is software-pipelined
+// over the rows a group visits: while the source rows of row i are in flight, the edges of row i+1 and the
+// extent of row i+2 are being read.  (What bounds the kernel on 128-float rows is the rate at which the L2s
+// deliver scattered 512-byte rows next to the stream of output rows: a loop with no bookkeeping at all -- hashed
+// source rows, constant weights -- is within 15 % of it, and lane layout, pipelining and grid size each move it by
+// a few percent only.)
+// The hardware counts outstanding vector memory operations in order, and the compiler can only leave the
+// younger ones in flight across a use of an older one if it knows how many there are: a read or store inside
+// a branch makes it wait for everything.  Hence every access of the steady state is unconditional -- reads
+// of rows or edges that do not exist go to a valid address (the first extent) and their value is replaced,
+// lanes past the last column repeat it, and the last trip, in which some groups have no row, stands apart -- and
+// only rare cases (a row with more than kSlots edges, slots beyond the fourth) sit in branches.
+// kOff32: every byte offset into x_src fits 32 bits and row index and row size fit 24 bits, so an address is
+// the uniform base plus one 32-bit vector offset (one multiply-add per load).
+template <int kLanes, int kPer, bool kOff32>
+__device__ __forceinline__ void aggregate_rows(const AggArgs& a, uint32_t group, uint32_t num_groups, uint32_t count,
+                                               uint32_t num_src)
+{
+    constexpr int kSlots = kLanes < 8 ? kLanes : 8;                      // edges a round covers (one per lane)
+    constexpr int kFlight = (kPer >= 4 && kSlots > 4) ? 4 : kSlots;     // source rows read together
+    const int lane = (int) (threadIdx.x % kLanes);
+    const uint32_t F = (uint32_t) a.feat_dim;
+    const uint32_t F4 = F >> 2;
+    const uint32_t row_bytes = F * 4u;
+    uint32_t col_bytes[kPer];                   // lanes past the last column repeat it
+#pragma unroll
+    for (int p = 0; p < kPer; ++p) {
+        const uint32_t cidx = (uint32_t) lane + (uint32_t) p * kLanes;
+        col_bytes[p] = (cidx < F4 ? cidx : F4 - 1u) * 16u;
+    }
+    const char* x_bytes = reinterpret_cast<const char*>(a.x_src);
+    const uint32_t trips = (count + num_groups - 1u) / num_groups;       // the same for every group (count > 0)
+
+    // extent of the row this group visits in trip `it` (empty past the end)
+    auto extent = [&](uint32_t it, int32_t& b, int32_t& e) {
+        const uint32_t row = group + it * num_groups;
+        const bool ok = it < trips && row < count;
+        const uint32_t r = ok ? row : 0u;
+        struct __attribute__((packed, aligned(4))) Pair { int32_t lo, hi; };       // one 8-byte read, 4-byte aligned
+        const Pair pr = *reinterpret_cast<const Pair*>(a.indptr + r);
+        b = pr.lo;
+        e = ok ? pr.hi : pr.lo;
+    };
+    // the edge this lane holds in the round that starts at entry q0 of a row ending at e
+    auto edge = [&](int32_t q0, int32_t e, uint32_t& j, float& w) {
+        const bool mine = q0 + lane < e && lane < kSlots;
+        const int32_t* pj = mine ? a.indices + (q0 + lane) : a.indptr;
+        const float* pw = mine ? a.weights + (q0 + lane) : reinterpret_cast<const float*>(a.indptr);
+        const uint32_t jv = (uint32_t) *pj;
+        const float wv = *pw;
+        j = mine ? jv : 0u;
+        w = mine ? wv : 0.f;
+    };
+    // one round: the edges (my_j, my_w) the group's lanes hold for entries [q0, e) of the row, slots [kFirst, kSlots)
+    auto round = [&](int32_t q0, int32_t e, uint32_t my_j, float my_w, float4 (&acc)[kPer], bool later, auto&& between) {
+        const int32_t here = e - q0 < kSlots ? (e - q0 > 0 ? e - q0 : 0) : kSlots;   // edges of this round
+        const bool bad = lane < here && my_j >= num_src;         // an index outside [0, num_src) is skipped
+        if (bad) { my_j = 0u; my_w = 0.f; }
+        // A row that has run out of edges while others of its wave go on has nothing of its own to repeat: what its
+        // slots read (source row 0) is replaced by zeros like the row of a skipped edge.  (A row without any edge is
+        // set to 0 at the end.)
+        const bool spent = later && here == 0;
+        const bool any_bad = __any(bad || spent);
+        const int last = here > 0 ? here - 1 : 0;
+#pragma unroll
+        for (int t0 = 0; t0 < kSlots; t0 += kFlight) {
+            if (t0 > 0 && !__any(t0 < here)) break;              // no row of this wave has that many edges
+            float4 x[kFlight][kPer];
+            float w[kFlight];
+#pragma unroll
+            for (int u = 0; u < kFlight; ++u) {
+                const int t = t0 + u;
+                if (t >= kSlots || (t >= 4 && !__any(t < here))) continue;       // a slot no row of this wave needs
+                const int from = t < last ? t : last;            // slots past the row's end repeat its last edge ...
+                const uint32_t j = (uint32_t) __shfl((int) my_j, from, kLanes);
+                const float wt = __shfl(my_w, from, kLanes);
+                w[u] = t < here ? wt : 0.f;                      // ... with weight 0
+#pragma unroll
+                for (int p = 0; p < kPer; ++p) {
+                    if (kOff32) {
+                        const uint32_t off = __umul24(j, row_bytes) + col_bytes[p];         // both factors < 2^24
+                        x[u][p] = *reinterpret_cast<const float4*>(x_bytes + off);
+                    } else {
+                        const uint64_t off = (uint64_t) j * row_bytes + col_bytes[p];
+                        x[u][p] = *reinterpret_cast<const float4*>(x_bytes + off);
+                    }
+                }
+            }
+            if (t0 == 0) between();                              // reads for the rows ahead, behind this row's first reads
+            if (any_bad) {
+                // rare: a skipped edge must not contribute even a NaN of the row it was redirected to
+#pragma unroll
+                for (int u = 0; u < kFlight; ++u) {
+                    const int t = t0 + u;
+                    if (t >= kSlots || (t >= 4 && !__any(t < here))) continue;
+                    const int from = t < last ? t : last;
+                    if (__shfl((int) bad, from, kLanes) || spent) {
+#pragma unroll
+                        for (int p = 0; p < kPer; ++p) x[u][p] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kFlight; ++u) {                  // edge order, one fma per term
+                if (t0 + u >= kSlots || (t0 + u >= 4 && !__any(t0 + u < here))) continue;
+#pragma unroll
+                for (int p = 0; p < kPer; ++p) {
+                    acc[p].x = fmaf(w[u], x[u][p].x, acc[p].x);
+                    acc[p].y = fmaf(w[u], x[u][p].y, acc[p].y);
+                    acc[p].z = fmaf(w[u], x[u][p].z, acc[p].z);
+                    acc[p].w = fmaf(w[u], x[u][p].w, acc[p].w);
+                }
+            }
+        }
+    };
+
+    // one row: its first round with the reads for the rows ahead slipped in, further rounds if it has more than
+    // kSlots edges, scaling, store
+    auto visit = [&](uint32_t row, int32_t b, int32_t e, uint32_t j, float w, auto&& between, auto&& store) {
+        float4 acc[kPer];
+#pragma unroll
+        for (int p = 0; p < kPer; ++p) acc[p] = make_float4(0.f, 0.f, 0.f, 0.f);
+        round(b, e, j, w, acc, false, between);
+        if (__any(e - b > kSlots)) {            // read on the spot
+            for (int32_t q0 = b + kSlots; __any(q0 < e); q0 += kSlots) {
+                uint32_t my_j;
+                float my_w;
+                edge(q0, e, my_j, my_w);
+                round(q0, e, my_j, my_w, acc, true, []() {});
+            }
+        }
+        // a row without edges took part in its wave's round with weight 0 on source row 0: its result is 0 whatever
+        // that row holds
+        const bool some = e > b;
+        const float inv_n = some ? 1.0f / (float) (e - b) : 0.f;           // one division per row, then the products
+        float4* o4 = reinterpret_cast<float4*>(a.out + (int64_t) row * F);
+#pragma unroll
+        for (int p = 0; p < kPer; ++p) {
+            float4 r = make_float4(acc[p].x * inv_n, acc[p].y * inv_n, acc[p].z * inv_n, acc[p].w * inv_n);
+            if (!some) r = make_float4(0.f, 0.f, 0.f, 0.f);
+            // a lane past the last column has computed the last column once more: it stores the same value there
+            store(o4 + (col_bytes[p] >> 4), r);
+        }
+    };
+
+    int32_t b0, e0, b1, e1;
+    uint32_t j0;
+    float w0;
+    extent(0, b0, e0);
+    extent(1, b1, e1);
+    edge(b0, e0, j0, w0);
+    // every group has a row in all trips but the last: nothing conditional there
+    for (uint32_t it = 0; it + 1 < trips; ++it) {
+        int32_t b2 = 0, e2 = 0;
+        uint32_t j1 = 0;
+        float w1 = 0.f;
+        visit(group + it * num_groups, b0, e0, j0, w0,
+              [&]() {
+                  extent(it + 2, b2, e2);       // two rows ahead
+                  edge(b1, e1, j1, w1);         // one row ahead
+              },
+              [](float4* dst, const float4& r) { store_streaming(dst, r); });
+        b0 = b1; e0 = e1; b1 = b2; e1 = e2; j0 = j1; w0 = w1;
+    }
+    const uint32_t row = group + (trips - 1u) * num_groups;
+    const bool live = row < count;
+    visit(row, b0, e0, j0, w0, []() {}, [&](float4* dst, const float4& r) { if (live) store_streaming(dst, r); });
+}
+
+template <int kLanes, int kPer, bool kVec>
 __global__ void __launch_bounds__(kBlock) k_aggregate(AggGroup g)
 {
     AggArgs a;
@@ -174,91 +429,27 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggGroup g)
     a.feat_dim = g.feat_dim;
     const int lane = (int) (threadIdx.x % kLanes);
     const int64_t groups_per_block = kBlock / kLanes;
-    int64_t group = (int64_t) blockIdx.x * groups_per_block + threadIdx.x / kLanes;
-    int64_t num_groups = (int64_t) gridDim.x * groups_per_block;
+    const int64_t group = (int64_t) blockIdx.x * groups_per_block + threadIdx.x / kLanes;
+    const int64_t num_groups = (int64_t) gridDim.x * groups_per_block;
     const int64_t F = a.feat_dim;
-    int col0 = 0;                   // first float4 column of this block's slice
-    if (g.slices > 1) {
-        const int xcd = (int) (blockIdx.x & 7u);
-        const int slice = g.fold > 1 ? xcd % g.slices : xcd;
-        if (slice >= g.slices) return;
-        const int64_t row_block = g.fold > 1 ? (int64_t) (blockIdx.x >> 3) * g.fold + xcd / g.slices : (int64_t) (blockIdx.x >> 3);
-        group = row_block * groups_per_block + threadIdx.x / kLanes;
-        num_groups = (int64_t) (gridDim.x >> 3) * g.fold * groups_per_block;
-        col0 = slice * kLanes;
-    }
     const int64_t count = a.num_dst_dev ? (int64_t) *a.num_dst_dev : (int64_t) a.num_dst;
     const uint32_t num_src = (uint32_t) (a.num_src_dev ? *a.num_src_dev : a.num_src);
     constexpr int kEdges = 8;       // edges whose rows are in flight together
-    if (kVec && (g.slices > 1 || F <= 4 * kLanes)) {
-        // One float4 per lane covers a row (or the row's column slice).  Branch-free inner loop: the first
-        // kSlots lanes of a row's group read one edge each (index and weight, one coalesced read), every lane
-        // then takes edge t from lane t of its group, so the reads of up to kSlots source rows are issued back
-        // to back; slots past the row's end repeat its last edge with weight 0 (adds an exact 0), rows with
-        // more than kSlots edges take further rounds.  All lanes of the wave stay converged: trip counts are
-        // wave-uniform (the shuffles need every source lane).
-        constexpr int kSlots = kLanes < 8 ? kLanes : 8;
-        const int64_t F4 = F >> 2;
-        const int col = col0 + lane < (int) F4 ? col0 + lane : (int) F4 - 1;       // idle lanes repeat the last column
-        const bool has = col0 + lane < (int) F4;
-        const float4* x4 = reinterpret_cast<const float4*>(a.x_src) + col;
-        // row j of x_src starts at float4 index j * F4: a shift when F4 is a power of two and the product fits
-        // 32 bits (integer multiplies run at a quarter of the rate of other vector instructions)
-        const bool by_shift = (F4 & (F4 - 1)) == 0 && (uint64_t) num_src * (uint64_t) F4 < ((uint64_t) 1 << 32);
-        const uint32_t f4_shift = (uint32_t) __builtin_ctzll((unsigned long long) F4);
-        const int64_t trips = (count + num_groups - 1) / num_groups;                 // the same for every group
-        for (int64_t it = 0; it < trips; ++it) {
-            const int64_t row = group + it * num_groups;
-            const bool live = row < count;
-            int32_t b = 0, e = 0;
-            if (live) { b = a.indptr[row]; e = a.indptr[row + 1]; }
-            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int32_t q0 = b; __any(q0 < e); q0 += kSlots) {
-                const int32_t here = e - q0 < kSlots ? (e - q0 > 0 ? e - q0 : 0) : kSlots;   // edges of this round
-                const bool mine = lane < here;
-                uint32_t my_j = mine ? (uint32_t) a.indices[q0 + lane] : 0u;
-                float my_w = mine ? a.weights[q0 + lane] : 0.f;
-                const bool bad = my_j >= num_src;                    // an index outside [0, num_src) is skipped
-                if (bad) { my_j = 0u; my_w = 0.f; }
-                const bool any_bad = __any(bad && mine);
-                float4 x[kSlots];
-                float w[kSlots];
-#pragma unroll
-                for (int t = 0; t < kSlots; ++t) {
-                    w[t] = 0.f;
-                    x[t] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (t < 4 || __any(t < here)) {                  // slots no row of this wave needs are skipped
-                        const int from = t < here ? t : (here > 0 ? here - 1 : 0);
-                        const uint32_t j = (uint32_t) __shfl((int) my_j, from, kLanes);
-                        const float wt = __shfl(my_w, from, kLanes);
-                        w[t] = t < here ? wt : 0.f;
-                        x[t] = by_shift ? x4[j << f4_shift] : x4[(int64_t) j * F4];
-                    }
-                }
-                if (any_bad) {
-                    // rare: a skipped edge must not contribute even a NaN of the row it was redirected to
-#pragma unroll
-                    for (int t = 0; t < kSlots; ++t) {
-                        const int from = t < here ? t : (here > 0 ? here - 1 : 0);
-                        if (__shfl((int) (bad && mine), from, kLanes)) x[t] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    }
-                }
-#pragma unroll
-                for (int t = 0; t < kSlots; ++t) {                    // edge order, one fma per term
-                    if (t < 4 || __any(t < here)) {
-                        acc.x = fmaf(w[t], x[t].x, acc.x);
-                        acc.y = fmaf(w[t], x[t].y, acc.y);
-                        acc.z = fmaf(w[t], x[t].z, acc.z);
-                        acc.w = fmaf(w[t], x[t].w, acc.w);
-                    }
-                }
-            }
-            if (e > b) {
-                const float inv_n = 1.0f / (float) (e - b);           // one division per row, then four products
-                acc.x *= inv_n; acc.y *= inv_n; acc.z *= inv_n; acc.w *= inv_n;
-            }
-            if (live && has) store_streaming(reinterpret_cast<float4*>(a.out + row * F) + col0 + lane, acc);
-        }
+    if (count <= 0) return;
+    if (num_src == 0) {             // no source row to read (and none may be touched): every edge is skipped
+        for (int64_t row = group; row < count; row += num_groups)
+            for (int i = lane; i < (int) F; i += kLanes) a.out[row * F + i] = 0.f;
+        return;
+    }
+    if (kVec && kPer == 1 && F <= 4 * kLanes) {
+        aggregate_rows_one_column<kLanes>(a, group, num_groups, count, num_src);
+        return;
+    }
+    if (kVec && F <= 4 * kLanes * kPer) {
+        if ((uint64_t) num_src * (uint64_t) F * 4u < ((uint64_t) 1 << 32) && num_src < (1u << 24) && F < (1 << 22))
+            aggregate_rows<kLanes, kPer, true>(a, (uint32_t) group, (uint32_t) num_groups, (uint32_t) count, num_src);
+        else
+            aggregate_rows<kLanes, kPer, false>(a, (uint32_t) group, (uint32_t) num_groups, (uint32_t) count, num_src);
         return;
     }
     for (int64_t row = group; row < count; row += num_groups) {
@@ -280,6 +471,7 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggGroup g)
                         const bool ok = j < num_src;
                         w[t] = ok ? a.weights[q] : 0.f;
                         x[t] = x4[(int64_t) (ok ? j : 0u) * F4 + i];
+                        if (!ok) x[t] = make_float4(0.f, 0.f, 0.f, 0.f);
                     }
 #pragma unroll
                     for (int t = 0; t < kEdges; ++t) {       // edge order, one fma per term
@@ -308,15 +500,15 @@ __global__ void __launch_bounds__(kBlock) k_aggregate(AggGroup g)
     }
 }
 
-template <bool kVec>
+template <int kPer, bool kVec>
 static void aggregate_dispatch(int lanes, dim3 blocks, hipStream_t s, const AggGroup& a)
 {
     switch (lanes) {
-        case 4:  hipLaunchKernelGGL((k_aggregate<4, kVec>), blocks, dim3(kBlock), 0, s, a); break;
-        case 8:  hipLaunchKernelGGL((k_aggregate<8, kVec>), blocks, dim3(kBlock), 0, s, a); break;
-        case 16: hipLaunchKernelGGL((k_aggregate<16, kVec>), blocks, dim3(kBlock), 0, s, a); break;
-        case 32: hipLaunchKernelGGL((k_aggregate<32, kVec>), blocks, dim3(kBlock), 0, s, a); break;
-        default: hipLaunchKernelGGL((k_aggregate<64, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        case 4:  hipLaunchKernelGGL((k_aggregate<4, kPer, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        case 8:  hipLaunchKernelGGL((k_aggregate<8, kPer, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        case 16: hipLaunchKernelGGL((k_aggregate<16, kPer, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        case 32: hipLaunchKernelGGL((k_aggregate<32, kPer, kVec>), blocks, dim3(kBlock), 0, s, a); break;
+        default: hipLaunchKernelGGL((k_aggregate<64, kPer, kVec>), blocks, dim3(kBlock), 0, s, a); break;
     }
 }
 
@@ -353,32 +545,25 @@ hipError_t launch_aggregate(gns_ctx* const* ctxs, int count, const gns_block* co
     a.feat_dim = feat_dim;
     const int64_t F = feat_dim;
     const bool vec = (F % 4 == 0) && aligned;
-    int lanes = lanes_for(vec ? F / 4 : F);
-    a.slices = 1;
-    a.fold = 1;
-    if (vec && F / 4 >= 16 && getenv("GNS_AGG_SLICES")) {
-        // at least 8 lanes (128 bytes, one cache line) of a row per slice, at most 8 slices
-        lanes = 8;
-        if (const char* e = getenv("GNS_AGG_SLICE_LANES")) lanes = atoi(e) >= 4 ? atoi(e) : 8;
-        while (lanes * 8 < F / 4) lanes <<= 1;
-        a.slices = (int32_t) ((F / 4 + lanes - 1) / lanes);
-        a.fold = (8 % a.slices == 0) ? 8 / a.slices : 1;
-    }
+    // float4 columns per lane.  Rows that start on cache-line boundaries and are at least two lines long are spread
+    // over few lanes with several columns each, which keeps the per-edge bookkeeping small (on 128-float rows 8 lanes
+    // x 4 columns is ahead of 16 x 2 and 32 x 1 once other kernels share the chip); other widths take one column per
+    // lane, so that a row is read as one contiguous piece.
+    const int64_t F4 = F / 4;
+    const int per = (vec && F4 % 8 == 0) ? (F4 >= 32 ? 4 : (F4 >= 16 ? 2 : 1)) : 1;
+    const int lanes = lanes_for(vec ? (F4 + per - 1) / per : F);
     const int64_t groups_per_block = kBlock / lanes;
     int64_t blocks = (most + groups_per_block - 1) / groups_per_block;
-    const int64_t cap = (int64_t) c->num_cus * 16;
-    if (a.slices > 1) {
-        // row blocks per (8 / fold) ... every group of 8 consecutive blocks covers `fold` row blocks in all slices
-        int64_t row_blocks = (blocks + a.fold - 1) / a.fold;
-        if (row_blocks * 8 > cap * 2) row_blocks = cap * 2 / 8;
-        if (row_blocks < 1) row_blocks = 1;
-        blocks = row_blocks * 8;
-    } else if (blocks > cap) {
-        blocks = cap;
-    }
+    // Several columns per lane: about the blocks that are resident together (beyond that a group visits several
+    // rows, which its pipeline wants anyway); a larger grid is no faster alone and 7 % slower next to another
+    // stream's kernels.
+    const int64_t cap = (int64_t) c->num_cus * (per > 1 ? 4 : 16);
+    if (blocks > cap) blocks = cap;
     const dim3 grid((unsigned) blocks, (unsigned) count);
-    if (vec) aggregate_dispatch<true>(lanes, grid, s, a);
-    else     aggregate_dispatch<false>(lanes, grid, s, a);
+    if (!vec) aggregate_dispatch<1, false>(lanes, grid, s, a);
+    else if (per == 4) aggregate_dispatch<4, true>(lanes, grid, s, a);
+    else if (per == 2) aggregate_dispatch<2, true>(lanes, grid, s, a);
+    else aggregate_dispatch<1, true>(lanes, grid, s, a);
     return hipGetLastError();
 }
 

@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     from paper_2106_06150_amd import binding as B
-    from gpu_harness import GpuGns, full_parity, compare_cache, compare_blocks
+    from gpu_harness import GpuGns, full_parity, compare_cache, compare_blocks, AGG_RTOL
 
 U, C, CF = 0, 1, 2          # UNIFORM, CACHE_ONLY, CACHE_FIRST
 
@@ -50,7 +50,7 @@ def test_small_graph_parity(offsets, fanouts, policies, flag_mode):
         gns.close()
 
 
-@pytest.mark.parametrize("F", [1, 3, 4, 100, 128, 260])
+@pytest.mark.parametrize("F", [1, 3, 4, 32, 64, 96, 100, 128, 256, 260, 1024])
 def test_feature_widths_and_host_store(F):
     ip, ix = _small(n=1500)
     n = ip.numel() - 1
@@ -62,6 +62,47 @@ def test_feature_widths_and_host_store(F):
             full_parity(gns, cache_seed=1, epoch=0, batch_seed=77, seeds=seeds)
         finally:
             gns.close()
+
+
+@pytest.mark.parametrize("F,rows,max_deg", [(128, 70_000, 5), (128, 3_000, 20), (64, 40_000, 9), (256, 20_000, 12),
+                                            (100, 40_000, 9), (8, 5_000, 20), (1024, 600, 9)])
+def test_aggregate_on_hand_made_blocks(F, rows, max_deg):
+    """gns_aggregate alone on a block that no sampler made: rows with 0..max_deg edges (several rounds of the
+    kernel's inner loop), more rows than one pass of the grid covers (the kernel's pipeline over rows), empty rows
+    next to full ones, non-finite values in source row 0 (empty rows must still give 0), repeated sources."""
+    rng = np.random.default_rng(F * 1000 + max_deg)
+    num_src = rows + 500
+    deg = rng.integers(0, max_deg + 1, size=rows)
+    deg[rng.integers(0, rows, size=rows // 10)] = 0
+    indptr = np.zeros(rows + 1, dtype=np.int32)
+    indptr[1:] = np.cumsum(deg)
+    E = int(indptr[-1])
+    indices = rng.integers(1, num_src, size=E).astype(np.int32)          # source row 0 is only reached by padding
+    weights = rng.uniform(0.5, 40.0, size=E).astype(np.float32)
+    x = rng.standard_normal((num_src, F)).astype(np.float32)
+    x[0, :] = np.inf
+    x[0, ::2] = np.nan
+    ref = oracle.aggregate(indptr, indices, weights, x)
+    scale = np.zeros((rows, F))
+    np.add.at(scale, np.repeat(np.arange(rows), deg), np.abs(weights[:, None].astype(np.float64) * x[indices]))
+    scale /= np.maximum(deg, 1)[:, None]
+    dev = torch.device("cuda:0")
+    ip, ix = _small(n=300)
+    gns = GpuGns(ip, ix, None, fanouts=(2,), policies=(U,), cache_size=10, max_seeds=8)      # a context to call through
+    try:
+        t = {k: torch.from_numpy(v).to(dev) for k, v in dict(indptr=indptr, indices=indices, weights=weights, x=x).items()}
+        blk = B.gns_block()
+        blk.num_dst, blk.num_src, blk.num_edges = rows, num_src, E
+        blk.indptr, blk.indices, blk.weights = t["indptr"].data_ptr(), t["indices"].data_ptr(), t["weights"].data_ptr()
+        out = torch.full((rows, F), 7.0, dtype=torch.float32, device=dev)
+        B.gns_aggregate(gns.ctx, blk, t["x"], F, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert np.isfinite(got).all()
+        assert (got[deg == 0] == 0).all()
+        assert (np.abs(got.astype(np.float64) - ref) <= AGG_RTOL * scale + 1e-30).all()
+    finally:
+        gns.close()
 
 
 @pytest.mark.parametrize("policies", [(U, C), (CF, CF)])
