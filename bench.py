@@ -134,7 +134,10 @@ class Workload:
         self.draw_stream = torch.cuda.Stream()
         self.pending_epoch = None          # cache period whose draw has been enqueued ahead of time
         self.draw_ms = None                # the first (synchronous) draw, host clock
-        self.async_draw = args.async_refresh > 0
+        # A long draw (a flag pass over billions of CSR entries) keeps the L2 request queues full and slows the
+        # mini-batches it overlaps by more than it saves (measured: -24 % on the 111 M-node graph, +6 % on the 1 M- and
+        # 2.4 M-node graphs): by default the cache is drawn ahead of time only on graphs of under 2^29 entries.
+        self.async_draw = args.async_refresh > 0 or (args.async_refresh < 0 and self.g.nnz < (1 << 29))
 
     def close(self):
         for c_ in self.ctxs[1:]:
@@ -174,11 +177,6 @@ class Workload:
             if self.draw_ms is None and b == 0:
                 self.torch.cuda.synchronize()
                 self.draw_ms = 1e3 * (time.perf_counter() - t0)
-                # A long draw (a flag pass over billions of CSR entries) keeps the L2 request queues full and slows the
-                # mini-batches it overlaps by more than it saves (measured: -24 % on the 111 M-node graph, +6 % on the
-                # 1 M- and 2.4 M-node graphs): draw ahead of time only when a draw is short.
-                if self.args.async_refresh < 0:
-                    self.async_draw = self.draw_ms < 5.0
         self.pending_epoch = None
 
     def prepare_next_cache(self, b):
@@ -588,7 +586,7 @@ def main():
     ap.add_argument("--async-refresh", type=int, default=-1,
                     help="1: the next period's cache is drawn half a period ahead on its own stream "
                          "(gns_sample_cache_async / gns_activate_cache); 0: a synchronous draw at every period start; "
-                         "-1: ahead of time when the workload's first draw took under 5 ms")
+                         "-1: ahead of time on graphs of under 2^29 CSR entries")
     ap.add_argument("--flag-mode", type=int, default=1,
                     help="cache-membership flags of the CSR entries: 1 (default) once per cache draw, inside the timed "
                          "region like the draw itself; 0 per mini-batch, for the dst rows' CSR segments only")
