@@ -40,6 +40,23 @@
  *  - Results are a pure function of (graph, config, seed, epoch, seeds): the
  *    random source is the counter-based Philox4x32-10 generator, so a repeated
  *    call reproduces its output bit for bit.
+ *  - Environment variables (testing and tuning aids; none changes a result,
+ *    only which kernel or launch shape produces it; the first three are read
+ *    when a workspace is sized and when the context is created, and must be
+ *    the same at both times):
+ *      GNS_MARK_TILE_WORDS=<64..8192, power of two>  words of the frontier
+ *        mark bitmap per block of the union step
+ *      GNS_MARK_SUMMARY_MIN_WORDS=<n>  bitmaps of at least n words keep a
+ *        summary (one bit per word; default 65536)
+ *      GNS_COARSE_SHIFT=<1..6>  ids per bit (as a power of two) of the coarse
+ *        cache bitmap of graphs whose bitmap does not fit LDS
+ *      GNS_NO_COARSE_L2=1  flag pass of such graphs without the coarse bitmap
+ *      GNS_FLAG_BLOCKS_PER_CU=<n>  grid of that flag pass (default 2)
+ *      GNS_LANE_ROWS_MIN=<n>  UNIFORM layers use the one-row-per-lane sampler
+ *        from n rows per launch on (default 262144)
+ *      GNS_NO_LANE_SAMPLER=1  never use the one-row-per-lane sampler
+ *      GNS_NO_GRAPH=1  enqueue a mini-batch's kernels one by one instead of
+ *        replaying a captured HIP graph
  */
 #ifndef GNS_H_
 #define GNS_H_

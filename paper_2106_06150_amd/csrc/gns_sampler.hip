@@ -738,7 +738,7 @@ static void launch_flag_kernel(gns_ctx* c, const LayerArgs& a, int count, int64_
         hipLaunchKernelGGL((k_flag_chunks<2>), dim3((unsigned) c->num_cus), dim3(1024), coarse_bytes, s, a, count, all_chunks);
     else if (c->lay.coarse_shift > 0 && !getenv("GNS_NO_COARSE_L2"))
     {
-        static const int per_cu = getenv("GNS_FLAG_BLOCKS_PER_CU") ? atoi(getenv("GNS_FLAG_BLOCKS_PER_CU")) : 2;
+        const int per_cu = getenv("GNS_FLAG_BLOCKS_PER_CU") ? atoi(getenv("GNS_FLAG_BLOCKS_PER_CU")) : 2;
         hipLaunchKernelGGL((k_flag_chunks<3>), dim3((unsigned) (c->num_cus * per_cu)), dim3(kBlock), 0, s, a, count, all_chunks);
     }
     else
@@ -746,7 +746,7 @@ static void launch_flag_kernel(gns_ctx* c, const LayerArgs& a, int count, int64_
         // every wave keeps 32 x 64 bitmap reads in flight, so a few waves per CU already reach the rate the
         // memory system gives scattered reads; a grid that filled the chip would keep the kernels of other
         // streams out for the whole pass
-        static const int per_cu = getenv("GNS_FLAG_BLOCKS_PER_CU") ? atoi(getenv("GNS_FLAG_BLOCKS_PER_CU")) : 2;
+        const int per_cu = getenv("GNS_FLAG_BLOCKS_PER_CU") ? atoi(getenv("GNS_FLAG_BLOCKS_PER_CU")) : 2;
         hipLaunchKernelGGL((k_flag_chunks<0>), dim3((unsigned) (c->num_cus * per_cu)), dim3(kBlock), 0, s, a, count, all_chunks);
     }
 }
@@ -802,7 +802,7 @@ hipError_t launch_sample_layer(const Group& g, int layer_index, hipStream_t s)
     const int policy = c->config.policy[layer_index];
     const bool induced = policy == GNS_CACHE_ONLY && c->config.flag_mode == GNS_FLAGS_PER_CACHE;
     // (one row per lane needs many rows to fill the chip: 64 rows make one wave)
-    static const int64_t lane_rows_min = getenv("GNS_LANE_ROWS_MIN") ? atoll(getenv("GNS_LANE_ROWS_MIN")) : 262144;
+    const int64_t lane_rows_min = getenv("GNS_LANE_ROWS_MIN") ? atoll(getenv("GNS_LANE_ROWS_MIN")) : 262144;
     const bool enough_rows = induced || rows_max * g.count >= lane_rows_min;
     if (a.s.fanout <= 16 && (policy == GNS_UNIFORM || induced) && enough_rows && !getenv("GNS_NO_LANE_SAMPLER")) {
         StageTimer t(c, GNS_STAGE_SELECT, s, induced);

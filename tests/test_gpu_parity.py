@@ -1080,6 +1080,49 @@ def test_mark_bitmap_summary_on_a_small_graph(fanouts, policies, flag_mode, monk
         gns.close()
 
 
+@pytest.mark.parametrize("env", [{"GNS_LANE_ROWS_MIN": "1"}, {"GNS_NO_LANE_SAMPLER": "1"}, {"GNS_NO_GRAPH": "1"}])
+@pytest.mark.parametrize("fanouts,policies,flag_mode", [((15, 10, 5), (U, U, U), 0), ((16, 8), (U, C), 1), ((4, 10, 3), (U, U, C), 1),
+                                                        ((6, 5), (CF, C), 1)])
+def test_sampler_kernel_choices_give_the_same_blocks(env, fanouts, policies, flag_mode, monkeypatch):
+    """Which sampler kernel serves a layer is a matter of size: one row per lane for large UNIFORM launches and
+    for CACHE_ONLY on the induced subgraph, a lane group per row otherwise, flag words where there is no induced
+    subgraph; launches replayed from a captured graph or enqueued one by one.  Each choice forced here on a small
+    graph (the switches are the library's testing aids), in groups of three mini-batches, against the oracle."""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    ip, ix = _small(n=20000, avg=12, seed=61)
+    n = ip.numel() - 1
+    F = 8
+    feat = _feat(n, F, seed=6)
+    csize, bs, count = 2000, 80, 3
+    gns = GpuGns(ip, ix, feat, fanouts=fanouts, policies=policies, cache_size=csize, max_seeds=bs, flag_mode=flag_mode)
+    ctxs, keep, bufs, call = _group_setup(gns, count)
+    try:
+        last = len(fanouts) - 1
+        uses_cache = any(p != U for p in policies)
+        cache = oracle.sample_cache(ip.numpy(), 4, 0, csize)
+        if uses_cache:
+            B.gns_sample_cache(gns.ctx, 4, 0)
+        xin = [torch.zeros((b.array[last].cap_src, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        hout = [torch.zeros((b.array[last].cap_dst, F), dtype=torch.float32, device=gns.device) for b in bufs]
+        for rnd in range(2):
+            seeds = [synth.uniform_seed_batch(n, bs - 13 * b, 60 * rnd + b).cuda() for b in range(count)]
+            bseeds = [900 + 10 * rnd + b for b in range(count)]
+            call.sample(bseeds, seeds)
+            call.gather([b.tensors[last]["src_nodes"] for b in bufs], [-1] * count, xin)
+            call.aggregate(last, xin, F, hout)
+            call.wait()
+            torch.cuda.synchronize()
+            for b in range(count):
+                ref = oracle.sample_blocks(ip.numpy(), ix.numpy(), cache[1], csize, bseeds[b], seeds[b].cpu().numpy(),
+                                           list(fanouts), list(policies))
+                _check_group_batch(gns, bufs[b], ref, feat, xin[b], hout[b], F)
+    finally:
+        for f in ctxs[1:]:
+            B.gns_destroy(f)
+        gns.close()
+
+
 @pytest.mark.parametrize("summary", [False, True])
 def test_union_step_with_large_tiles_and_several_lds_passes(summary, monkeypatch):
     """The union step walks the frontier mark bitmap in tiles of up to 8192 words and passes a tile's marked
