@@ -77,7 +77,7 @@ def measured_copy_gbps(torch, dev):
 class Workload:
     """One config: graph, features, contexts, buffers; the passes of the benchmark."""
 
-    def __init__(self, torch, B, synth, cfg_id, args, total_batches, feat_in_hbm=False):
+    def __init__(self, torch, B, synth, cfg_id, args, total_batches, feat_in_hbm=False, upper_policy=None):
         self.torch, self.B, self.synth, self.args = torch, B, synth, args
         dev = self.dev = torch.device("cuda:0")
         c = self.c = synth.CONFIGS[cfg_id]
@@ -87,7 +87,8 @@ class Workload:
         self.fanouts = list(c["fanouts"])
         L = self.L = len(self.fanouts)
         self.last = L - 1
-        upper = B.GNS_UNIFORM if args.upper_policy == "uniform" else B.GNS_CACHE_FIRST
+        self.upper_policy = upper_policy or args.upper_policy
+        upper = B.GNS_UNIFORM if self.upper_policy == "uniform" else B.GNS_CACHE_FIRST
         self.policies = [upper] * (L - 1) + [B.GNS_CACHE_ONLY]
         self.cache_size = int(self.n * c["cache_frac"])
         self.refresh = c.get("refresh_every", 20)
@@ -379,7 +380,7 @@ def algorithmic_bytes(w, avg, flag_mode):
     return alg
 
 
-def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat_in_hbm=False):
+def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat_in_hbm=False, upper_policy=None):
     c = synth.CONFIGS[cfg_id]
     refresh = c.get("refresh_every", 20)
     warm = max(W, refresh)
@@ -388,7 +389,7 @@ def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat
         warm = 2 * refresh                                     # both copies of the cache structures get drawn
     total = warm + (2 * repeats + 1) * K
     t_setup = time.perf_counter()
-    w = Workload(torch, B, synth, cfg_id, args, total, feat_in_hbm=feat_in_hbm)
+    w = Workload(torch, B, synth, cfg_id, args, total, feat_in_hbm=feat_in_hbm, upper_policy=upper_policy)
     if w.walk:
         w.walk_probability()
     torch.cuda.synchronize()
@@ -430,7 +431,9 @@ def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat
     avg = w.shape_stats(b2, min(K, args.shape_batches))
     alg = algorithmic_bytes(w, avg, args.flag_mode)
     F = w.F
-    kernel_of = {"flag": "k_flag_chunks", "select": "k_select_rows", "gather": "k_gather", "aggregate": "k_aggregate"}
+    # the input layer's CACHE_ONLY sampler: one row per lane on the induced subgraph when there is one, else flag words
+    select_kernel = "k_sample_lane" if (args.flag_mode == 1 and w.fanouts[-1] <= 16) else "k_select_rows"
+    kernel_of = {"flag": "k_flag_chunks", "select": select_kernel, "gather": "k_gather", "aggregate": "k_aggregate"}
     candidates = [s_ for s_ in kernel_of if s_ in launch_us]
     dom = max(candidates, key=lambda s_: launch_us[s_])
     bytes_per_launch = alg[dom] * per_launch
@@ -512,7 +515,7 @@ def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat
         "cache_draw_ahead_of_time": bool(w.async_draw), "first_cache_draw_ms": round(w.draw_ms or 0.0, 3),
         "walk_probability": w.walk_info,
     }
-    if args.input_node_batches > 0 and not w.walk and not feat_in_hbm:
+    if args.input_node_batches > 0 and not w.walk and not feat_in_hbm and upper_policy is None:
         res["input_nodes"] = w.input_node_shapes(b2, min(K, args.input_node_batches))
     if w.H > 0 and "dense" in launch_us:
         fl = 2.0 * avg["rows"] * 2 * F * w.H
@@ -578,6 +581,8 @@ def main():
                          "GPU), reported as a variant next to the configured pinned-host store")
     ap.add_argument("--cpu-batches", type=int, default=32, help="mini-batches the CPU oracle is timed on (0: skip)")
     ap.add_argument("--shape-batches", type=int, default=40, help="mini-batches replayed for the byte counts")
+    ap.add_argument("--paper-upper-layers", type=int, default=1,
+                    help="1: also measure --config with the upper layers sampled cache first (reported under per_config)")
     ap.add_argument("--input-node-batches", type=int, default=5,
                     help="mini-batches for the input-node comparison of plain node-wise sampling and GNS (0: skip)")
     ap.add_argument("--group", type=int, default=0,
@@ -629,6 +634,13 @@ def main():
             r2 = bench_config(torch, B, synth, cid, args, args.per_config_steps, 0, 3, with_oracle=False, feat_in_hbm=True)
             r2["variant"] = "the same graph and batches with the full feature matrix resident in HBM instead of pinned host memory"
             per_config["config_%d_features_in_hbm" % cid] = r2
+
+    if args.paper_upper_layers and args.upper_policy == "uniform":
+        # the same workload with the upper layers sampled cache first, as the paper's own runs do (Section 4.1)
+        r3 = bench_config(torch, B, synth, args.config, args, args.per_config_steps, 0, 3, with_oracle=False,
+                          upper_policy="cache_first")
+        r3["variant"] = "the headline workload with the upper layers sampled cache first (the paper's setting) instead of uniformly"
+        per_config["config_%d_upper_layers_cache_first" % args.config] = r3
 
     c = synth.CONFIGS[args.config]
     roofline = main_res.pop("roofline")
