@@ -583,6 +583,8 @@ def main():
     ap.add_argument("--shape-batches", type=int, default=40, help="mini-batches replayed for the byte counts")
     ap.add_argument("--paper-upper-layers", type=int, default=1,
                     help="1: also measure --config with the upper layers sampled cache first (reported under per_config)")
+    ap.add_argument("--scan-variant", type=int, default=1,
+                    help="1: also measure --config with GNS_FLAGS_PER_BATCH (reported under per_config)")
     ap.add_argument("--input-node-batches", type=int, default=5,
                     help="mini-batches for the input-node comparison of plain node-wise sampling and GNS (0: skip)")
     ap.add_argument("--group", type=int, default=0,
@@ -641,6 +643,14 @@ def main():
                           upper_policy="cache_first")
         r3["variant"] = "the headline workload with the upper layers sampled cache first (the paper's setting) instead of uniformly"
         per_config["config_%d_upper_layers_cache_first" % args.config] = r3
+
+    if args.scan_variant and args.flag_mode == 1:
+        # the same workload with the cache membership of the input layer's rows found per mini-batch, by scanning their
+        # CSR segments against the cache bitmap, instead of once per cache draw
+        args0 = argparse.Namespace(**{**vars(args), "flag_mode": 0})
+        r4 = bench_config(torch, B, synth, args.config, args0, args.per_config_steps, 0, 3, with_oracle=False)
+        r4["variant"] = "the headline workload with the CSR-segment scan per mini-batch (GNS_FLAGS_PER_BATCH) instead of flags per cache draw"
+        per_config["config_%d_flags_per_batch" % args.config] = r4
 
     c = synth.CONFIGS[args.config]
     roofline = main_res.pop("roofline")
