@@ -25,8 +25,12 @@ Passes over the same workload:
      object of the single kernel that takes the most time.
 Then an untimed replay counts algorithmic bytes, and the CPU oracle is timed on a
 bounded sample of the same mini-batches.  The default run repeats passes A-C
-(fewer steps, no oracle) on the products-shaped and the giant workload
-(`per_config`).  Prints one JSON line.
+(fewer steps, no oracle) on the products-shaped and the giant workload, on the
+giant workload with its features in HBM, and on two variants of the headline
+workload (upper layers sampled cache first as in the paper's runs; cache flags
+found per mini-batch by a CSR-segment scan), all under `per_config`; it also counts
+the input nodes of plain node-wise sampling against GNS (`input_nodes`).
+Prints one JSON line.
 """
 import argparse
 import json
