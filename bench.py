@@ -193,25 +193,40 @@ class Workload:
 
     def run(self, b0, b1, aggregate=True, one_stream=False):
         B, last, F = self.B, self.last, self.F
-        for slot, ids in self.groups(b0, b1):
-            if ids[0] % self.refresh == 0:
-                self.refresh_cache(ids[0])
-            elif not one_stream and ids[0] % self.refresh >= self.refresh // 2:
-                self.prepare_next_cache(ids[0])
-            if one_stream:
-                slot = 0
-            st = self.streams[slot]
-            call = self.call(slot, len(ids))
-            lo = slot * self.G
-            hi = lo + len(ids)
-            call.sample([self.sd["batch"] + b for b in ids], [self.seeds[b] for b in ids], st)
-            call.gather(self.src_nodes[lo:hi], [-1] * len(ids), self.x_in[lo:hi], st)
-            if aggregate:
-                call.aggregate(last, self.x_in[lo:hi], F, self.h_out[lo:hi], st)
-                if self.H > 0:   # the dst nodes are the first rows of the gathered input features
-                    for i in range(lo, hi):
-                        B.gns_sage_dense(self.ctxs[i], self.x_in[i], self.h_out[i], self.w_dense, self.b_dense, True,
-                                         self.z_out[i], -1 - last, st)
+        groups = self.groups(b0, b1)
+        i = 0
+        while i < len(groups):
+            # The groups that are in flight together (one per stream) are enqueued side by side: first the sampling
+            # sequence of each, then the feature kernels of each, so that no stream waits for the host to finish
+            # with another one's calls.  A group that starts a cache period starts such a set.
+            n = 1
+            while (not one_stream and n < self.S and i + n < len(groups)
+                   and groups[i + n][1][0] % self.refresh != 0):
+                n += 1
+            chunk = groups[i:i + n]
+            i += n
+            work = []
+            for slot, ids in chunk:
+                if ids[0] % self.refresh == 0:
+                    self.refresh_cache(ids[0])
+                elif not one_stream and ids[0] % self.refresh >= self.refresh // 2:
+                    self.prepare_next_cache(ids[0])
+                if one_stream:
+                    slot = 0
+                st = self.streams[slot]
+                call = self.call(slot, len(ids))
+                call.sample([self.sd["batch"] + b for b in ids], [self.seeds[b] for b in ids], st)
+                work.append((slot, ids, st, call))
+            for slot, ids, st, call in work:
+                lo = slot * self.G
+                hi = lo + len(ids)
+                call.gather(self.src_nodes[lo:hi], [-1] * len(ids), self.x_in[lo:hi], st)
+                if aggregate:
+                    call.aggregate(last, self.x_in[lo:hi], F, self.h_out[lo:hi], st)
+                    if self.H > 0:   # the dst nodes are the first rows of the gathered input features
+                        for k_ in range(lo, hi):
+                            B.gns_sage_dense(self.ctxs[k_], self.x_in[k_], self.h_out[k_], self.w_dense, self.b_dense, True,
+                                             self.z_out[k_], -1 - last, st)
 
     def windows(self, b0, K, repeats, aggregate=True):
         """`repeats` windows of K steps back to back; seconds per window (host clock between device
