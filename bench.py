@@ -81,7 +81,7 @@ def measured_copy_gbps(torch, dev):
 class Workload:
     """One config: graph, features, contexts, buffers; the passes of the benchmark."""
 
-    def __init__(self, torch, B, synth, cfg_id, args, total_batches, feat_in_hbm=False, upper_policy=None):
+    def __init__(self, torch, B, synth, cfg_id, args, total_batches, feat_in_hbm=False, upper_policy=None, refresh_every=None):
         self.torch, self.B, self.synth, self.args = torch, B, synth, args
         dev = self.dev = torch.device("cuda:0")
         c = self.c = synth.CONFIGS[cfg_id]
@@ -95,7 +95,7 @@ class Workload:
         upper = B.GNS_UNIFORM if self.upper_policy == "uniform" else B.GNS_CACHE_FIRST
         self.policies = [upper] * (L - 1) + [B.GNS_CACHE_ONLY]
         self.cache_size = int(self.n * c["cache_frac"])
-        self.refresh = c.get("refresh_every", 20)
+        self.refresh = refresh_every or c.get("refresh_every", 20)
         self.g = synth.make_config_graph(cfg_id, device=dev)
         self.on_host = bool(c.get("feat_on_host")) and not feat_in_hbm
         self.feat = synth.node_features(self.n, self.F, sd["feat"], device=dev, pin=self.on_host)
@@ -399,16 +399,18 @@ def algorithmic_bytes(w, avg, flag_mode):
     return alg
 
 
-def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat_in_hbm=False, upper_policy=None):
+def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat_in_hbm=False, upper_policy=None,
+                 refresh_every=None):
     c = synth.CONFIGS[cfg_id]
-    refresh = c.get("refresh_every", 20)
+    refresh = refresh_every or c.get("refresh_every", 20)
     warm = max(W, refresh)
     warm = (warm + refresh - 1) // refresh * refresh          # whole cache periods: the windows start at a refresh
     if warm // refresh < 2:
         warm = 2 * refresh                                     # both copies of the cache structures get drawn
     total = warm + (2 * repeats + 1) * K
     t_setup = time.perf_counter()
-    w = Workload(torch, B, synth, cfg_id, args, total, feat_in_hbm=feat_in_hbm, upper_policy=upper_policy)
+    w = Workload(torch, B, synth, cfg_id, args, total, feat_in_hbm=feat_in_hbm, upper_policy=upper_policy,
+                 refresh_every=refresh_every)
     if w.walk:
         w.walk_probability()
     torch.cuda.synchronize()
@@ -602,6 +604,8 @@ def main():
     ap.add_argument("--shape-batches", type=int, default=40, help="mini-batches replayed for the byte counts")
     ap.add_argument("--paper-upper-layers", type=int, default=1,
                     help="1: also measure --config with the upper layers sampled cache first (reported under per_config)")
+    ap.add_argument("--epoch-period", type=int, default=1,
+                    help="1: also measure the giant workload (features in HBM) with one cache draw per epoch")
     ap.add_argument("--scan-variant", type=int, default=1,
                     help="1: also measure --config with GNS_FLAGS_PER_BATCH (reported under per_config)")
     ap.add_argument("--input-node-batches", type=int, default=5,
@@ -655,6 +659,15 @@ def main():
             r2 = bench_config(torch, B, synth, cid, args, args.per_config_steps, 0, 3, with_oracle=False, feat_in_hbm=True)
             r2["variant"] = "the same graph and batches with the full feature matrix resident in HBM instead of pinned host memory"
             per_config["config_%d_features_in_hbm" % cid] = r2
+            if args.epoch_period and "split" in synth.CONFIGS[cid]:
+                # the paper redraws the cache every P >= 1 epochs (Section 4.3), not every 100 mini-batches: the same
+                # variant with one draw per epoch over the training split, timed over whole periods
+                period = synth.CONFIGS[cid]["split"] // synth.CONFIGS[cid]["batch"]
+                r5 = bench_config(torch, B, synth, cid, args, period, 0, 3, with_oracle=False, feat_in_hbm=True,
+                                  refresh_every=period)
+                r5["variant"] = ("features in HBM and the cache redrawn once per epoch over the training split (%d mini-batches), "
+                                 "the paper's update period, instead of every %d" % (period, synth.CONFIGS[cid].get("refresh_every", 20)))
+                per_config["config_%d_features_in_hbm_cache_per_epoch" % cid] = r5
 
     if args.paper_upper_layers and args.upper_policy == "uniform":
         # the same workload with the upper layers sampled cache first, as the paper's own runs do (Section 4.1)
