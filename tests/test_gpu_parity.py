@@ -555,7 +555,7 @@ def test_walk_probability_recomputed_while_batches_are_in_flight():
         seeds = [train[40 * b:40 * b + bs].contiguous().cuda() for b in range(nb)]
         prefixes = []
         for rnd, scale in enumerate((10, 20)):
-            w, pre, total, support = gns.walk_probability(train, scale)     # while round 0's batches may still run
+            w, pre, total, support = gns.walk_probability(train, scale)     # while the previous pass's batches may still run
             w_ref, pre_ref = oracle.walk_weights(ip.numpy(), ix.numpy(), train.numpy(), list(fanouts), scale_log2=scale)
             assert np.array_equal(pre, pre_ref)
             prefixes.append(pre_ref)
