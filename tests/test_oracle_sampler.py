@@ -286,3 +286,37 @@ def test_cache_first_unbiased_weights_given_the_cache():
     p1 = 1.0 / 18.0
     pc = 1 - (1 - p1) ** 2
     assert abs(float(w[0, 0]) - 1.0 / pc) < 1e-6 / pc
+
+
+def test_slots_beyond_the_fourth_take_later_philox_blocks():
+    """A row with more than four draws uses several Philox blocks: slot s takes word s & 3 of the block whose
+    counter is (node, s >> 2, layer, tag) under the key (seed low, seed high).  Pinned against the word-size-generic
+    Philox of test_oracle_philox (validated there against numpy's generator) and Floyd's draw written out here:
+    one hub row of degree 200, fan-outs 5..16, several nodes, layers and seeds above 2^32.  A swapped counter word,
+    a word taken from the wrong block or a block reused for slots 4.. changes the sample."""
+    from test_oracle_philox import philox4_generic, M32, W32
+    tag = 0x4E424853                                    # the neighbor-draw stream's counter word
+    deg = 200
+    n = deg + 8
+    rows = [np.arange(1, deg + 1) if v in (0, 203, 207) else np.array([], dtype=np.int64) for v in range(n)]
+    rows[203] = np.arange(0, deg)                       # other hubs with other neighbor lists
+    rows[207] = np.arange(3, deg + 3)
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum([len(r) for r in rows])
+    indices = np.concatenate(rows).astype(np.int32)
+    for seed in (5, (7 << 32) | 11):
+        key = (seed & 0xFFFFFFFF, seed >> 32)
+        for layer in (1, 3):
+            for k in (5, 8, 10, 15, 16):
+                for node in (0, 203, 207):
+                    chosen = []
+                    for s_ in range(k):
+                        word = philox4_generic((node, s_ >> 2, layer, tag), key, 32, M32, W32)[s_ & 3]
+                        j = deg - k + s_
+                        t = (word * (j + 1)) >> 32
+                        chosen.append(j if t in chosen else t)
+                    expect = rows[node][sorted(chosen)]
+                    nbr, _, cnt, elig = oracle.sample_layer(indptr, indices, None, 0, seed, layer, oracle.UNIFORM, 0, k,
+                                                            np.array([node], dtype=np.int32))
+                    assert cnt[0] == k and elig[0] == deg
+                    assert np.array_equal(nbr[0], expect), (seed, layer, k, node)
