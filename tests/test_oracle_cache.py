@@ -60,6 +60,29 @@ def test_single_draw_uses_row_owner_of_a_uniform_entry():
     assert abs(got[0] / 40_000 - 0.25) < 0.01
 
 
+def test_cache_stream_keying_and_range_map():
+    """Draw j of the cache stream of (seed, epoch): the Philox block with counter (j low, j high, epoch, tag) under the
+    key (seed low, seed high) gives r = word1 * 2^32 + word0, the entry is floor(r * nnz / 2^64) and the node is the
+    row that owns it.  Pinned against the word-size-generic Philox of test_oracle_philox and Python integers, on
+    ragged degrees, stream positions above 2^32, epochs and seeds above 2^32."""
+    from test_oracle_philox import philox4_generic, M32, W32
+    tag = 0x43414348                                    # the cache stream's counter word
+    rng = np.random.default_rng(3)
+    deg = rng.integers(0, 50, size=400)
+    deg[::7] = 0
+    indptr = np.zeros(401, dtype=np.int64)
+    indptr[1:] = np.cumsum(deg)
+    nnz = int(indptr[-1])
+    for seed in (9, (3 << 40) | 77):
+        for epoch in (0, 5, (1 << 31) + 3):
+            for j in (0, 1, 2, 1000, (1 << 32) + 5, (1 << 40) + 123):
+                w = philox4_generic((j & 0xFFFFFFFF, j >> 32, epoch & 0xFFFFFFFF, tag), (seed & 0xFFFFFFFF, seed >> 32), 32, M32, W32)
+                r = (w[1] << 32) | w[0]
+                e = (r * nnz) >> 64
+                node = int(np.searchsorted(indptr, e, side="right")) - 1
+                assert oracle.cache_draw_node(indptr, seed, epoch, j) == node, (seed, epoch, j)
+
+
 def exact_wor_inclusion(p, c):
     """Successive sampling without replacement: P(sequence) = prod p_i/(1 - mass already taken)."""
     n = len(p)
