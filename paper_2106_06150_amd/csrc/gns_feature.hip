@@ -164,7 +164,7 @@ struct AggArgs : AggBatch {
 // rows do not start on cache-line boundaries or do not fill several columns per lane.  Branch-free inner loop:
 // the first kSlots lanes of a row's group read one edge each (index and weight, one coalesced read), every lane
 // then takes edge t from lane t of its group, so the reads of up to kSlots source rows are issued back to back;
-// slots past the row's end repeat its last edge with weight 0 (adds an exact 0), rows with more than kSlots edges
+// in a slot past its row's end a lane group stands aside (weight 0 on zeros), rows with more than kSlots edges
 // take further rounds.  All lanes of the wave stay converged: trip counts are wave-uniform (the shuffles need
 // every source lane).
 template <int kLanes>
@@ -196,11 +196,7 @@ __device__ __forceinline__ void aggregate_rows_one_column(const AggArgs& a, int6
             float my_w = mine ? a.weights[q0 + lane] : 0.f;
             const bool bad = my_j >= num_src;                    // an index outside [0, num_src) is skipped
             if (bad) { my_j = 0u; my_w = 0.f; }
-            // A row that has run out of edges while others of its wave go on has nothing of its own to repeat: what
-            // its slots read (source row 0) is replaced by zeros like the row of a skipped edge.  (A row without any
-            // edge is set to 0 at the end.)
-            const bool spent = here == 0 && q0 != b;
-            const bool any_bad = __any((bad && mine) || spent);
+            const bool any_bad = __any(bad && mine);
             float4 x[kSlots];
             float w[kSlots];
 #pragma unroll
@@ -208,20 +204,19 @@ __device__ __forceinline__ void aggregate_rows_one_column(const AggArgs& a, int6
                 w[t] = 0.f;
                 x[t] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (t < 4 || __any(t < here)) {                  // slots no row of this wave needs are skipped
-                    const int from = t < here ? t : (here > 0 ? here - 1 : 0);
-                    const uint32_t j = (uint32_t) __shfl((int) my_j, from, kLanes);
-                    const float wt = __shfl(my_w, from, kLanes);
-                    w[t] = t < here ? wt : 0.f;
-                    x[t] = by_shift ? x4[j << f4_shift] : x4[(int64_t) j * F4];
+                    const uint32_t j = (uint32_t) __shfl((int) my_j, t, kLanes);
+                    const float wt = __shfl(my_w, t, kLanes);
+                    if (t < here) {                              // a row without an edge in this slot stands aside
+                        w[t] = wt;
+                        x[t] = by_shift ? x4[j << f4_shift] : x4[(int64_t) j * F4];
+                    }
                 }
             }
             if (any_bad) {
                 // rare: a skipped edge must not contribute even a NaN of the row it was redirected to
 #pragma unroll
-                for (int t = 0; t < kSlots; ++t) {
-                    const int from = t < here ? t : (here > 0 ? here - 1 : 0);
-                    if (__shfl((int) (bad && mine), from, kLanes) || spent) x[t] = make_float4(0.f, 0.f, 0.f, 0.f);
-                }
+                for (int t = 0; t < kSlots; ++t)
+                    if (__shfl((int) (bad && mine), t, kLanes)) x[t] = make_float4(0.f, 0.f, 0.f, 0.f);
             }
 #pragma unroll
             for (int t = 0; t < kSlots; ++t) {                    // edge order, one fma per term
@@ -233,13 +228,9 @@ __device__ __forceinline__ void aggregate_rows_one_column(const AggArgs& a, int6
                 }
             }
         }
-        if (e > b) {
+        if (e > b) {                                              // (a row without edges has read nothing: 0)
             const float inv_n = 1.0f / (float) (e - b);           // one division per row, then four products
             acc.x *= inv_n; acc.y *= inv_n; acc.z *= inv_n; acc.w *= inv_n;
-        } else {
-            // a row without edges took part in its wave's round with weight 0 on source row 0: its result is 0
-            // whatever that row holds
-            acc = make_float4(0.f, 0.f, 0.f, 0.f);
         }
         if (live && has) store_streaming(reinterpret_cast<float4*>(a.out + row * F) + lane, acc);
     }
@@ -248,9 +239,9 @@ __device__ __forceinline__ void aggregate_rows_one_column(const AggArgs& a, int6
 // Rows whose features are float4-aligned and fit kLanes * kPer float4 columns: a group of kLanes lanes owns a
 // dst row, lane l accumulates columns l, l + kLanes, ... (kPer of them).  Branch-free inner loop: the first
 // kSlots lanes of the group hold one edge each (index and weight, one coalesced read), every lane then takes
-// edge t from lane t of its group, so the reads of the source rows are issued back to back; slots past the
-// row's end repeat its last edge with weight 0 (adds an exact 0), rows with more than kSlots edges take
-// further rounds.  All lanes of the wave stay converged: trip counts are wave-uniform (the shuffles need
+// edge t from lane t of its group, so the reads of the source rows are issued back to back; in a slot past its
+// row's end a lane group stands aside (weight 0 on zeros: the texture addressers only work for lanes that take
+// part in a read), rows with more than kSlots edges take further rounds.  All lanes of the wave stay converged: trip counts are wave-uniform (the shuffles need
 // every source lane).
 // A row is a chain of dependent accesses (row extent -> edges -> source rows -> store); it is software-pipelined
 // over the rows a group visits: while the source rows of row i are in flight, the edges of row i+1 and the
@@ -306,16 +297,11 @@ __device__ __forceinline__ void aggregate_rows(const AggArgs& a, uint32_t group,
         w = mine ? wv : 0.f;
     };
     // one round: the edges (my_j, my_w) the group's lanes hold for entries [q0, e) of the row, slots [kFirst, kSlots)
-    auto round = [&](int32_t q0, int32_t e, uint32_t my_j, float my_w, float4 (&acc)[kPer], bool later, auto&& between) {
+    auto round = [&](int32_t q0, int32_t e, uint32_t my_j, float my_w, float4 (&acc)[kPer], auto&& between) {
         const int32_t here = e - q0 < kSlots ? (e - q0 > 0 ? e - q0 : 0) : kSlots;   // edges of this round
         const bool bad = lane < here && my_j >= num_src;         // an index outside [0, num_src) is skipped
         if (bad) { my_j = 0u; my_w = 0.f; }
-        // A row that has run out of edges while others of its wave go on has nothing of its own to repeat: what its
-        // slots read (source row 0) is replaced by zeros like the row of a skipped edge.  (A row without any edge is
-        // set to 0 at the end.)
-        const bool spent = later && here == 0;
-        const bool any_bad = __any(bad || spent);
-        const int last = here > 0 ? here - 1 : 0;
+        const bool any_bad = __any(bad);
 #pragma unroll
         for (int t0 = 0; t0 < kSlots; t0 += kFlight) {
             if (t0 > 0 && !__any(t0 < here)) break;              // no row of this wave has that many edges
@@ -324,19 +310,25 @@ __device__ __forceinline__ void aggregate_rows(const AggArgs& a, uint32_t group,
 #pragma unroll
             for (int u = 0; u < kFlight; ++u) {
                 const int t = t0 + u;
-                if (t >= kSlots || (t >= 4 && !__any(t < here))) continue;       // a slot no row of this wave needs
-                const int from = t < last ? t : last;            // slots past the row's end repeat its last edge ...
-                const uint32_t j = (uint32_t) __shfl((int) my_j, from, kLanes);
-                const float wt = __shfl(my_w, from, kLanes);
-                w[u] = t < here ? wt : 0.f;                      // ... with weight 0
+                w[u] = 0.f;
 #pragma unroll
-                for (int p = 0; p < kPer; ++p) {
-                    if (kOff32) {
-                        const uint32_t off = __umul24(j, row_bytes) + col_bytes[p];         // both factors < 2^24
-                        x[u][p] = *reinterpret_cast<const float4*>(x_bytes + off);
-                    } else {
-                        const uint64_t off = (uint64_t) j * row_bytes + col_bytes[p];
-                        x[u][p] = *reinterpret_cast<const float4*>(x_bytes + off);
+                for (int p = 0; p < kPer; ++p) x[u][p] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (t >= kSlots || (t >= 4 && !__any(t < here))) continue;       // a slot no row of this wave needs
+                const uint32_t j = (uint32_t) __shfl((int) my_j, t, kLanes);
+                const float wt = __shfl(my_w, t, kLanes);
+                // Lanes of rows that have no edge in this slot stand aside: the texture addressers, which bound this
+                // kernel, only work for the lanes that take part in a read.
+                if (t < here) {
+                    w[u] = wt;
+#pragma unroll
+                    for (int p = 0; p < kPer; ++p) {
+                        if (kOff32) {
+                            const uint32_t off = __umul24(j, row_bytes) + col_bytes[p];     // both factors < 2^24
+                            x[u][p] = *reinterpret_cast<const float4*>(x_bytes + off);
+                        } else {
+                            const uint64_t off = (uint64_t) j * row_bytes + col_bytes[p];
+                            x[u][p] = *reinterpret_cast<const float4*>(x_bytes + off);
+                        }
                     }
                 }
             }
@@ -346,9 +338,8 @@ __device__ __forceinline__ void aggregate_rows(const AggArgs& a, uint32_t group,
 #pragma unroll
                 for (int u = 0; u < kFlight; ++u) {
                     const int t = t0 + u;
-                    if (t >= kSlots || (t >= 4 && !__any(t < here))) continue;
-                    const int from = t < last ? t : last;
-                    if (__shfl((int) bad, from, kLanes) || spent) {
+                    if (t >= kSlots) continue;
+                    if (__shfl((int) bad, t, kLanes)) {
 #pragma unroll
                         for (int p = 0; p < kPer; ++p) x[u][p] = make_float4(0.f, 0.f, 0.f, 0.f);
                     }
@@ -374,24 +365,21 @@ __device__ __forceinline__ void aggregate_rows(const AggArgs& a, uint32_t group,
         float4 acc[kPer];
 #pragma unroll
         for (int p = 0; p < kPer; ++p) acc[p] = make_float4(0.f, 0.f, 0.f, 0.f);
-        round(b, e, j, w, acc, false, between);
+        round(b, e, j, w, acc, between);
         if (__any(e - b > kSlots)) {            // read on the spot
             for (int32_t q0 = b + kSlots; __any(q0 < e); q0 += kSlots) {
                 uint32_t my_j;
                 float my_w;
                 edge(q0, e, my_j, my_w);
-                round(q0, e, my_j, my_w, acc, true, []() {});
+                round(q0, e, my_j, my_w, acc, []() {});
             }
         }
-        // a row without edges took part in its wave's round with weight 0 on source row 0: its result is 0 whatever
-        // that row holds
-        const bool some = e > b;
+        const bool some = e > b;                                           // (a row without edges has read nothing: 0)
         const float inv_n = some ? 1.0f / (float) (e - b) : 0.f;           // one division per row, then the products
         float4* o4 = reinterpret_cast<float4*>(a.out + (int64_t) row * F);
 #pragma unroll
         for (int p = 0; p < kPer; ++p) {
-            float4 r = make_float4(acc[p].x * inv_n, acc[p].y * inv_n, acc[p].z * inv_n, acc[p].w * inv_n);
-            if (!some) r = make_float4(0.f, 0.f, 0.f, 0.f);
+            const float4 r = make_float4(acc[p].x * inv_n, acc[p].y * inv_n, acc[p].z * inv_n, acc[p].w * inv_n);
             // a lane past the last column has computed the last column once more: it stores the same value there
             store(o4 + (col_bytes[p] >> 4), r);
         }
