@@ -262,7 +262,7 @@ __device__ __forceinline__ void aggregate_rows(const AggArgs& a, uint32_t group,
                                                uint32_t num_src)
 {
     constexpr int kSlots = kLanes < 8 ? kLanes : 8;                      // edges a round covers (one per lane)
-    constexpr int kFlight = (kPer >= 4 && kSlots > 4) ? 4 : kSlots;     // source rows read together
+    constexpr int kFlight = (kPer >= 4 && kSlots > 4) ? 5 : kSlots;     // source rows read together
     const int lane = (int) (threadIdx.x % kLanes);
     const uint32_t F = (uint32_t) a.feat_dim;
     const uint32_t F4 = F >> 2;
