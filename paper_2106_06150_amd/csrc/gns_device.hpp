@@ -10,7 +10,7 @@ constexpr int kBlock = 256;                 // threads per block for the scan-st
 constexpr int kItems = 8;                   // items per thread in a scan tile
 constexpr int kTile = kBlock * kItems;      // 2048 items per scan tile
 constexpr int kMarkTileMin = 64;             // frontier mark bitmap: words per tile, a power of two chosen per graph
-constexpr int kMarkTileMax = 32 * kBlock;    //   so that the tiles number a few hundred (at most 32 words per thread)
+constexpr int kMarkTileMax = 32 * kBlock;    //   so that the tiles number about a hundred (at most 32 words per thread)
 constexpr int kMarkCap = 1024;               // marked words of a tile the union step keeps in LDS at a time
 
 constexpr uint32_t kTagCache = 0x43414348u;     // 'CACH'
