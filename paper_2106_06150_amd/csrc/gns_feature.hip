@@ -129,7 +129,7 @@ hipError_t launch_gather(gns_ctx* const* ctxs, int count, const int32_t* const* 
     const int lanes = lanes_for(vec ? F / 4 : F);
     const int64_t groups_per_block = kBlock / lanes;
     int64_t blocks = (most + groups_per_block - 1) / groups_per_block;
-    const int64_t cap = (int64_t) c->num_cus * 16;
+    const int64_t cap = (int64_t) c->num_cus * 8;        // what is resident together; beyond that a group copies several rows
     if (blocks > cap) blocks = cap;
     const dim3 grid((unsigned) blocks, (unsigned) count);
     if (vec) gather_dispatch<true>(lanes, grid, s, a);
