@@ -357,7 +357,7 @@ int relabel_grid(const gns_ctx* c, int layer_index)
 {
     const int64_t max_slots = c->lay.rows[layer_index] * (int64_t) c->config.fanout[layer_index];
     int64_t rb = (max_slots + kBlock - 1) / kBlock;
-    if (rb > (int64_t) c->num_cus * 16) rb = (int64_t) c->num_cus * 16;
+    if (rb > (int64_t) c->num_cus * 8) rb = (int64_t) c->num_cus * 8;
     if (rb < 1) rb = 1;
     return (int) rb;
 }
