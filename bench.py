@@ -47,6 +47,12 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 
+def progress(msg):
+    """One line on stderr per phase when GNS_BENCH_PROGRESS is set (a long or stuck run then says where it is)."""
+    if os.environ.get("GNS_BENCH_PROGRESS"):
+        print("bench: " + msg, file=sys.stderr, flush=True)
+
+
 def profile_traffic(kernel, cfg_id):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary
     (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel factors stated there), or None."""
@@ -409,6 +415,7 @@ def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat
         warm = 2 * refresh                                     # both copies of the cache structures get drawn
     total = warm + (2 * repeats + 1) * K
     t_setup = time.perf_counter()
+    progress("config %d: building graph, features and contexts" % cfg_id)
     w = Workload(torch, B, synth, cfg_id, args, total, feat_in_hbm=feat_in_hbm, upper_policy=upper_policy,
                  refresh_every=refresh_every)
     if w.walk:
@@ -424,9 +431,11 @@ def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat
         del src, dst
 
     # warm-up: whole cache periods, and one window's worth of the exact group pattern the windows use
+    progress("config %d: set up in %.1f s, warm-up of %d steps" % (cfg_id, setup_s, warm))
     w.run(0, warm)
     torch.cuda.synchronize()
     b0 = warm
+    progress("pass A")
     # ---- pass A
     if args.skip_pass_a:
         host, devs = [float("nan")], [float("nan")]
@@ -434,10 +443,12 @@ def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat
         host, devs = w.windows(b0, K, repeats)
     elapsed = statistics.median(host)
     b1 = b0 + repeats * K
+    progress("pass C")
     # ---- pass C: sampler + gather only
     host_c, devs_c = ([float("nan")], [float("nan")]) if args.skip_pass_a else w.windows(b1, K, repeats, aggregate=False)
     elapsed_c = statistics.median(host_c)
     b2 = b1 + repeats * K
+    progress("cache draws alone")
     # ---- refresh alone (host clock around the synchronising call, the streams idle)
     refresh_ms = []
     for r in range(3):
@@ -446,8 +457,10 @@ def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat
         w.refresh_cache((b2 // refresh + r) * refresh)
         torch.cuda.synchronize()
         refresh_ms.append(1e3 * (time.perf_counter() - t0))
+    progress("pass B")
     # ---- pass B
     launch_us, launches, per_launch, elapsed_b = w.stage_times(b2, K)
+    progress("replay for byte counts")
     # ---- shapes and algorithmic bytes
     avg = w.shape_stats(b2, min(K, args.shape_batches))
     alg = algorithmic_bytes(w, avg, args.flag_mode)
@@ -544,6 +557,7 @@ def bench_config(torch, B, synth, cfg_id, args, K, W, repeats, with_oracle, feat
                                "achieved": round(fl / (launch_us["dense"] * 1e-6) / 1e12, 2), "peak": 157.3,
                                "unit": "TFLOP/s", "frac": round(fl / (launch_us["dense"] * 1e-6) / 1e12 / 157.3, 4)}
 
+    progress("stages done")
     # ---- CPU oracle on a bounded sample of the same mini-batches
     if with_oracle and args.cpu_batches > 0:
         import oracle
@@ -646,7 +660,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     K, W = args.steps, args.warmup
+    progress("start")
     copy_gbps = measured_copy_gbps(torch, dev)
+    progress("copy rate measured")
     main_res = bench_config(torch, B, synth, args.config, args, K, W, args.repeats, with_oracle=True)
     per_config = {}
     for tok in [t for t in args.per_config.split(",") if t.strip()]:
